@@ -1,0 +1,32 @@
+"""Device-side model tables: uploads fp16 weights, packs the matrices with
+ghd_pack_weight and builds the pointer tables ghd_verify_stack takes.
+Plumbing only; no arithmetic of the method happens here."""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Tuple
+
+import torch
+
+from . import binding as B
+
+MATRICES = ("Wqkv", "Wo", "Wgu", "Wdown")
+
+
+def upload_layer(w: Dict[str, torch.Tensor], device="cuda") -> Dict[str, torch.Tensor]:
+    """fp16 layer weights (row-major, any device) -> gains + packed matrices on the GPU."""
+    out = {}
+    for name, t in w.items():
+        t = t.to(device)
+        out[name] = B.ghd_pack_weight(t) if name in MATRICES else t.contiguous()
+    return out
+
+
+def upload_head(h: Dict[str, torch.Tensor], device="cuda") -> Dict[str, torch.Tensor]:
+    return {"g_final": h["g_final"].to(device).contiguous(),
+            "Wlm": B.ghd_pack_weight(h["Wlm"].to(device))}
+
+
+def build_stack(shape, capacity: int, layers: List[Dict[str, torch.Tensor]],
+                caches: List[Tuple[torch.Tensor, torch.Tensor]],
+                head: Dict[str, torch.Tensor]) -> B.Stack:
+    return B.Stack(B.make_cfg(shape, capacity), layers, caches, head)

@@ -1,0 +1,181 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function the header declares, and rejects bad arguments before touching
+the device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2505_23219_amd import binding as B
+from paper_2505_23219_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # non-null, 16-byte aligned, never dereferenced on these paths
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2505_23219_amd.build import build
+        build()
+    return B.lib()
+
+
+def test_header_functions_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "ghd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ghd_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(0, -8, -1):
+        s = B.status_str(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert B.status_str(-99) == "unknown status"
+
+
+def test_tree_validate(lib):
+    assert B.ghd_tree_validate([-1]) == B.GHD_OK
+    assert B.ghd_tree_validate([-1, 0, 0, 2, 3]) == B.GHD_OK
+    assert B.ghd_tree_validate([0]) == B.GHD_ERR_TREE
+    assert B.ghd_tree_validate([-1, 1]) == B.GHD_ERR_TREE
+    assert B.ghd_tree_validate([-1, 0, 2]) == B.GHD_ERR_TREE
+    assert B.ghd_tree_validate([-1, -1]) == B.GHD_ERR_TREE
+    assert B.ghd_tree_validate([-1] + [0] * 128) == B.GHD_ERR_SHAPE
+    assert lib.ghd_tree_validate(None, 4) == B.GHD_ERR_NULL
+    for M in (1, 2, 3, 4, 5):
+        for parent in wl.all_trees(M):
+            assert B.ghd_tree_validate(list(parent)) == B.GHD_OK
+    for w in ("tiny", "layer7b", "stack7b", "stack13b"):
+        assert B.ghd_tree_validate(list(wl.workload(w).parent)) == B.GHD_OK
+
+
+def test_packed_size(lib):
+    assert lib.ghd_packed_weight_bytes(16, 32) == 1024
+    assert lib.ghd_packed_weight_bytes(17, 33) == 4 * 1024
+    assert lib.ghd_packed_weight_bytes(12288, 4096) == 12288 * 4096 * 2   # same bytes as row-major
+    assert lib.ghd_packed_weight_bytes(0, 32) == 0
+
+
+def test_linear_rejects_bad_arguments(lib):
+    f = lib.ghd_linear_skinny
+    ok = dict(y=FAKE, x=FAKE, W=FAKE, M=16, N=64, K=64, ldx=64, ldy=64, flags=0, ws=FAKE,
+              ws_bytes=1 << 30, stream=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["y"], a["x"], a["W"], a["M"], a["N"], a["K"], a["ldx"], a["ldy"], a["flags"],
+                 a["ws"], a["ws_bytes"], a["stream"])
+
+    assert call(y=None) == B.GHD_ERR_NULL
+    assert call(x=None) == B.GHD_ERR_NULL
+    assert call(W=None) == B.GHD_ERR_NULL
+    assert call(M=0) == B.GHD_ERR_SHAPE
+    assert call(M=129) == B.GHD_ERR_SHAPE
+    assert call(K=60) == B.GHD_ERR_SHAPE
+    assert call(ldx=56) == B.GHD_ERR_SHAPE
+    assert call(ldy=8) == B.GHD_ERR_SHAPE
+    assert call(flags=7) == B.GHD_ERR_SHAPE
+    assert call(x=FAKE + 2) == B.GHD_ERR_ALIGN
+    assert call(ldx=68) == B.GHD_ERR_ALIGN
+    assert call(ws=None) == B.GHD_ERR_WORKSPACE
+    assert call(ws_bytes=16) == B.GHD_ERR_WORKSPACE
+    assert lib.ghd_linear_workspace_bytes(16, 64, 64) >= 16 * 64 * 4
+    assert lib.ghd_linear_workspace_bytes(0, 64, 64) == 0
+
+
+def test_attention_rejects_bad_arguments(lib):
+    f = lib.ghd_tree_attention
+    ok = dict(out=FAKE, q=FAKE, k=FAKE, v=FAKE, parent=FAKE, M=8, kv_len=100, nh=4, d=64,
+              sh=64 * 256, st=64, scale=0.125, ws=FAKE, ws_bytes=1 << 30, stream=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["out"], a["q"], a["k"], a["v"], a["parent"], a["M"], a["kv_len"], a["nh"], a["d"],
+                 a["sh"], a["st"], a["scale"], a["ws"], a["ws_bytes"], a["stream"])
+
+    for name in ("out", "q", "k", "v", "parent"):
+        assert call(**{name: None}) == B.GHD_ERR_NULL
+    assert call(M=0) == B.GHD_ERR_SHAPE
+    assert call(M=200) == B.GHD_ERR_SHAPE
+    assert call(d=96) == B.GHD_ERR_SHAPE
+    assert call(kv_len=-1) == B.GHD_ERR_SHAPE
+    assert call(st=32) == B.GHD_ERR_SHAPE
+    assert call(q=FAKE + 8) == B.GHD_ERR_ALIGN
+    assert call(st=68) == B.GHD_ERR_ALIGN
+    assert call(ws=None) == B.GHD_ERR_WORKSPACE
+    assert call(ws_bytes=8) == B.GHD_ERR_WORKSPACE
+
+
+def _cfg(shape, cap):
+    return B.make_cfg(shape, cap)
+
+
+def test_layer_and_stack_reject_bad_arguments(lib):
+    cfg = _cfg(wl.TINY, 256)
+    lw = B.LayerWeights(*([FAKE] * 6))
+    kv = B.KV(FAKE, FAKE)
+    need = lib.ghd_workspace_bytes(C.byref(cfg), 8, 128)
+    assert need > 0
+
+    def layer(cfgp=C.byref(cfg), lwp=C.byref(lw), kvp=C.byref(kv), x=FAKE, parent=FAKE, M=8,
+              kv_len=128, ws=FAKE, ws_bytes=1 << 30):
+        return lib.ghd_verify_layer(cfgp, lwp, kvp, x, parent, M, kv_len, ws, ws_bytes, None)
+
+    assert layer(cfgp=None) == B.GHD_ERR_NULL
+    assert layer(x=None) == B.GHD_ERR_NULL
+    assert layer(parent=None) == B.GHD_ERR_NULL
+    bad = B.LayerWeights(FAKE, None, FAKE, FAKE, FAKE, FAKE)
+    assert layer(lwp=C.byref(bad)) == B.GHD_ERR_NULL
+    assert layer(M=0) == B.GHD_ERR_SHAPE
+    assert layer(M=129) == B.GHD_ERR_SHAPE
+    assert layer(kv_len=250) == B.GHD_ERR_CAPACITY
+    assert layer(x=FAKE + 4) == B.GHD_ERR_ALIGN
+    assert layer(ws=None) == B.GHD_ERR_WORKSPACE
+    assert layer(ws_bytes=need - 1) == B.GHD_ERR_WORKSPACE
+    badcfg = _cfg(wl.ModelShape("bad", H=256, nh=4, d=32, F=64, V=10, L=1), 256)
+    assert layer(cfgp=C.byref(badcfg)) == B.GHD_ERR_SHAPE
+    badcfg = _cfg(wl.ModelShape("bad", H=250, nh=4, d=64, F=64, V=10, L=1), 256)
+    assert layer(cfgp=C.byref(badcfg)) == B.GHD_ERR_SHAPE
+    assert lib.ghd_workspace_bytes(C.byref(badcfg), 8, 128) == 0
+
+    lws = (B.LayerWeights * 1)(lw)
+    kvs = (B.KV * 1)(kv)
+
+    def stack(g=FAKE, W=FAKE, x_in=FAKE, logits=FAKE, M=8, kv_len=128, ws=FAKE, ws_bytes=1 << 30):
+        return lib.ghd_verify_stack(C.byref(cfg), lws, kvs, g, W, x_in, FAKE, M, kv_len, logits,
+                                    None, ws, ws_bytes, None)
+
+    assert stack(g=None) == B.GHD_ERR_NULL
+    assert stack(logits=None) == B.GHD_ERR_NULL
+    assert stack(M=130) == B.GHD_ERR_SHAPE
+    assert stack(kv_len=249) == B.GHD_ERR_CAPACITY
+    assert stack(x_in=FAKE + 2) == B.GHD_ERR_ALIGN
+    assert stack(ws_bytes=100) == B.GHD_ERR_WORKSPACE
+
+
+def test_accept_rejects_bad_arguments(lib):
+    f = lib.ghd_accept_greedy
+    assert f(None, FAKE, FAKE, 4, 10, FAKE, None, FAKE, 1 << 20, None) == B.GHD_ERR_NULL
+    assert f(FAKE, FAKE, FAKE, 4, 10, None, None, FAKE, 1 << 20, None) == B.GHD_ERR_NULL
+    assert f(FAKE, FAKE, FAKE, 0, 10, FAKE, None, FAKE, 1 << 20, None) == B.GHD_ERR_SHAPE
+    assert f(FAKE, FAKE, FAKE, 4, 0, FAKE, None, FAKE, 1 << 20, None) == B.GHD_ERR_SHAPE
+    assert f(FAKE, FAKE, FAKE, 4, 10, FAKE, None, None, 1 << 20, None) == B.GHD_ERR_WORKSPACE
+    assert f(FAKE, FAKE, FAKE, 4, 10, FAKE, None, FAKE, 4, None) == B.GHD_ERR_WORKSPACE
+
+
+def test_workspace_sizes_grow_with_the_problem(lib):
+    cfg = _cfg(wl.LLAMA_7B, 4096)
+    a = lib.ghd_workspace_bytes(C.byref(cfg), 1, 2048)
+    b = lib.ghd_workspace_bytes(C.byref(cfg), 64, 2048)
+    assert 0 < a < b < (1 << 30)
+    assert lib.ghd_attention_workspace_bytes(64, 2048, 32, 128) > 0
+    assert lib.ghd_accept_workspace_bytes(64) >= 64 * 4

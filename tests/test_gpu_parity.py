@@ -1,0 +1,317 @@
+"""GPU-vs-oracle parity through the C ABI, on the same seeded inputs.
+
+Integer results (packed bytes, masks, argmax, accepted paths) must be
+bit-identical.  Floating-point tolerances:
+  * fp32 outputs of a single linear layer: both sides add exact fp16 x fp16
+    products in fp32 in different orders, so the gap is accumulation noise;
+    bound used: 2e-4 + 2e-4*|ref| (K <= 11008, |terms| ~ 0.02).
+  * fp16 activations / residual stream / logits after whole layers:
+    |gpu - ref| <= 2e-2 + 1e-2*|ref| against the fp32 oracle with the fp16
+    rounding points switched on.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_23219_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2505_23219_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.lib()          # fails loudly when libghd.so is missing
+    return binding
+
+
+@pytest.fixture(scope="module")
+def model():
+    from paper_2505_23219_amd import model
+    return model
+
+
+def close(got, ref, atol, rtol):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    err = np.abs(got - ref)
+    bound = atol + rtol * np.abs(ref)
+    worst = float((err - bound).max())
+    return worst <= 0, float(err.max()), float((err / np.maximum(np.abs(ref), 1e-3)).max())
+
+
+def reference_pack(W):
+    """The packed layout written out from its definition (include/ghd.h)."""
+    N, K = W.shape
+    nt, ks = (N + 15) // 16, (K + 31) // 32
+    Wp = np.zeros((nt * 16, ks * 32), dtype=np.uint16)
+    Wp[:N, :K] = W.view(np.uint16)
+    # [tile, kstep, kgroup, row, 8]
+    out = Wp.reshape(nt, 16, ks, 4, 8).transpose(0, 2, 3, 1, 4)
+    return np.ascontiguousarray(out).reshape(-1)
+
+
+@pytest.mark.parametrize("N,K", [(16, 32), (40, 72), (1000, 256), (256, 688)])
+def test_pack_weight_bytes(B, N, K):
+    say("pack", N, K)
+    W = wl.activations(N, K, 21, tag="w", std=0.02)
+    got = B.ghd_pack_weight(W.cuda()).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, reference_pack(W.numpy()))
+
+
+def test_tree_mask_bit_exact(B, orc32):
+    cases = [p for M in range(1, 6) for p in wl.all_trees(M)]
+    cases += [wl.tree_random(M, dep, s) for M, dep, s in ((8, 3, 0), (64, 5, 2), (65, 9, 5),
+                                                          (128, 5, 3), (128, 127, 4))]
+    cases += [wl.tree_chain(128), wl.tree_star(128), wl.tree_wide_shallow(64, 32, 4)]
+    for parent in cases:
+        M = len(parent)
+        got = B.ghd_tree_mask(torch.from_numpy(parent).cuda()).cpu().numpy().view(np.uint64)
+        ref = orc32.tree_mask(parent)
+        bits = np.zeros((M, 2), dtype=np.uint64)
+        for i in range(M):
+            for j in range(M):
+                if ref[i, j]:
+                    bits[i, j // 64] |= np.uint64(1) << np.uint64(j % 64)
+        assert np.array_equal(got, bits), list(parent)
+
+
+LINEAR_CASES = [(1, 64, 64), (3, 130, 688), (8, 1000, 256), (16, 256, 256), (17, 48, 96),
+                (33, 688 * 2, 256), (64, 256, 688), (100, 130, 520), (128, 512, 1024),
+                (16, 12288, 4096), (64, 4096, 11008), (1, 4096, 4096)]
+
+
+@pytest.mark.parametrize("M,N,K", LINEAR_CASES)
+def test_linear_skinny(B, orc32, M, N, K):
+    say("linear", M, N, K)
+    x = wl.activations(M, K, 31)
+    W = wl.activations(N, K, 32, tag="w", std=0.02)
+    Wp = B.ghd_pack_weight(W.cuda())
+    ref = orc32.linear(x.numpy().astype(np.float32), W.numpy())
+    y = B.ghd_linear_skinny(x.cuda(), Wp, N).cpu().numpy()
+    ok, ma, mr = close(y, ref, 2e-4, 2e-4)
+    assert ok, (ma, mr)
+    # fp16 output = the fp32 result rounded once
+    y16 = B.ghd_linear_skinny(x.cuda(), Wp, N, out_dtype=torch.float16).cpu().numpy()
+    ok, ma, mr = close(y16, ref, 1e-3, 1e-3)
+    assert ok, (ma, mr)
+
+
+def attention_case(M, nh, d, kv_len, parent, seed, cap=None):
+    shape = wl.ModelShape("t", H=nh * d, nh=nh, d=d, F=8, V=8, L=1)
+    cap = cap or ((kv_len + M + 63) // 64) * 64
+    kc, vc = wl.kv_cache(shape, cap, kv_len, seed, 0)
+    tk = wl.activations(M, nh * d, seed, tag="tk").reshape(M, nh, d)
+    tv = wl.activations(M, nh * d, seed, tag="tv").reshape(M, nh, d)
+    kc[:, kv_len:kv_len + M] = tk.permute(1, 0, 2)
+    vc[:, kv_len:kv_len + M] = tv.permute(1, 0, 2)
+    q = wl.activations(M, nh * d, seed, tag="q").reshape(M, nh, d).contiguous()
+    return q, kc.contiguous(), vc.contiguous()
+
+
+ATTN_CASES = [
+    # M, nh, d, kv_len, tree
+    (1, 4, 64, 128, "chain"), (8, 4, 64, 128, "rand3"), (8, 4, 64, 0, "rand3"),
+    (16, 2, 128, 1024, "medusa"), (16, 3, 128, 100, "chain"), (16, 3, 128, 63, "star"),
+    (17, 2, 128, 65, "rand5"), (64, 32, 128, 2048, "rand5"), (64, 4, 128, 2048, "chain"),
+    (64, 5, 128, 8192, "wide"), (100, 2, 64, 300, "rand5"), (128, 2, 128, 257, "rand5"),
+    (128, 2, 128, 1000, "chain"), (128, 2, 64, 0, "star"), (1, 2, 128, 0, "chain"),
+]
+
+
+def make_tree(kind, M):
+    if kind == "chain":
+        return wl.tree_chain(M)
+    if kind == "star":
+        return wl.tree_star(M)
+    if kind == "medusa":
+        return wl.tree_medusa(M, (4, 2, 1, 1), 1)
+    if kind == "wide":
+        return wl.tree_wide_shallow(M, 32, 4)
+    return wl.tree_random(M, int(kind[4:]), 7)
+
+
+@pytest.mark.parametrize("M,nh,d,kv_len,tree", ATTN_CASES)
+def test_tree_attention(B, orc32, M, nh, d, kv_len, tree):
+    say("attention", M, nh, d, kv_len, tree)
+    parent = make_tree(tree, M)
+    q, kc, vc = attention_case(M, nh, d, kv_len, parent, 41)
+    ref = orc32.tree_attention(q.numpy().astype(np.float32), kc.numpy(), vc.numpy(), parent, kv_len)
+    got = B.ghd_tree_attention(q.cuda(), kc.cuda(), vc.cuda(), torch.from_numpy(parent).cuda(),
+                               kv_len).cpu().numpy()
+    ok, ma, mr = close(got, ref, 5e-3, 5e-3)
+    assert ok, (ma, mr)
+
+
+def test_tree_attention_ignores_rows_past_the_tree(B):
+    M, nh, d, kv_len = 9, 2, 128, 70
+    parent = wl.tree_random(M, 3, 1)
+    q, kc, vc = attention_case(M, nh, d, kv_len, parent, 43, cap=256)
+    a = B.ghd_tree_attention(q.cuda(), kc.cuda(), vc.cuda(), torch.from_numpy(parent).cuda(), kv_len)
+    kc[:, kv_len + M:] = 100.0
+    vc[:, kv_len + M:] = -100.0
+    b = B.ghd_tree_attention(q.cuda(), kc.cuda(), vc.cuda(), torch.from_numpy(parent).cuda(), kv_len)
+    assert torch.equal(a, b)
+
+
+def run_layer_case(B, model, orc32, shape, M, kv_len, parent, seed):
+    cap = ((kv_len + M + 63) // 64) * 64
+    w = wl.layer_weights(shape, seed, 0)
+    kc, vc = wl.kv_cache(shape, cap, kv_len, seed, 0)
+    x16 = wl.activations(M, shape.H, seed)
+    # oracle
+    kc_o, vc_o = kc.numpy().copy(), vc.numpy().copy()
+    ref = orc32.verify_layer(shape, {k: v.numpy() for k, v in w.items()}, kc_o, vc_o,
+                             x16.numpy().astype(np.float32), parent, kv_len, round16=True)
+    # GPU
+    wd = model.upload_layer(w)
+    kc_d, vc_d = kc.cuda(), vc.cuda()
+    x = x16.float().cuda()
+    cfg = B.make_cfg(shape, cap)
+    B.ghd_verify_layer(cfg, wd, kc_d, vc_d, x, torch.from_numpy(parent).cuda(), kv_len)
+    torch.cuda.synchronize()
+    ok, ma, mr = close(x.cpu().numpy(), ref, 2e-2, 1e-2)
+    assert ok, ("residual stream", ma, mr)
+    for name, got, want in (("k", kc_d, kc_o), ("v", vc_d, vc_o)):
+        got = got.cpu().numpy()
+        # committed rows untouched, rows past the tree untouched
+        assert np.array_equal(got[:, :kv_len], want[:, :kv_len]), name
+        assert np.array_equal(got[:, kv_len + M:], want[:, kv_len + M:]), name
+        ok, ma, mr = close(got[:, kv_len:kv_len + M], want[:, kv_len:kv_len + M], 2e-3, 2e-3)
+        assert ok, (name, ma, mr)
+    return ma
+
+
+def test_verify_layer_tiny(B, model, orc32):
+    w = wl.workload("tiny")
+    say("layer tiny")
+    run_layer_case(B, model, orc32, w.shape, w.M, w.kv_len, w.parent, w.seed)
+
+
+@pytest.mark.parametrize("M,kv_len,tree", [(1, 77, "chain"), (5, 0, "rand3"), (16, 130, "star"),
+                                           (40, 64, "rand5"), (128, 200, "rand5")])
+def test_verify_layer_small_shapes(B, model, orc32, M, kv_len, tree):
+    say("layer small", M, kv_len, tree)
+    shape = wl.ModelShape("small", H=512, nh=4, d=128, F=1376, V=100, L=1)
+    run_layer_case(B, model, orc32, shape, M, kv_len, make_tree(tree, M), 5)
+
+
+def test_verify_layer_7b_shape(B, model, orc32):
+    w = wl.workload("layer7b")
+    say("layer 7b", w.M, w.kv_len)
+    run_layer_case(B, model, orc32, w.shape, w.M, w.kv_len, w.parent, w.seed)
+
+
+def run_stack_case(B, model, orc32, shape, M, kv_len, parent, seed):
+    cap = ((kv_len + M + 63) // 64) * 64
+    layers = [wl.layer_weights(shape, seed, l) for l in range(shape.L)]
+    head = wl.head_weights(shape, seed)
+    caches = [wl.kv_cache(shape, cap, kv_len, seed, l) for l in range(shape.L)]
+    x16 = wl.activations(M, shape.H, seed)
+    kcs = [c[0].numpy().copy() for c in caches]
+    vcs = [c[1].numpy().copy() for c in caches]
+    ref_logits, ref_x = orc32.verify_stack(
+        shape, [{k: v.numpy() for k, v in w.items()} for w in layers], kcs, vcs,
+        {k: v.numpy() for k, v in head.items()}, x16.numpy(), parent, kv_len, round16=True)
+    stack = model.build_stack(shape, cap, [model.upload_layer(w) for w in layers],
+                              [(k.cuda(), v.cuda()) for k, v in caches], model.upload_head(head))
+    x_out = torch.empty((M, shape.H), dtype=torch.float32, device="cuda")
+    pd = torch.from_numpy(parent).cuda()
+    logits = B.ghd_verify_stack(stack, x16.cuda(), pd, kv_len, x_out=x_out)
+    torch.cuda.synchronize()
+    ok, ma, mr = close(x_out.cpu().numpy(), ref_x, 2e-2, 1e-2)
+    assert ok, ("final residual", ma, mr)
+    ok, ma, mr = close(logits.cpu().numpy(), ref_logits, 2e-2, 1e-2)
+    assert ok, ("logits", ma, mr)
+    return stack, logits, ref_logits, pd
+
+
+def check_accept(B, orc32, logits, ref_logits, parent, pd, V, seed):
+    """argmax must agree wherever the oracle's top-2 margin exceeds 1e-3; then
+    plant a path from the agreed argmaxes and compare the accepted paths."""
+    M = len(parent)
+    top2 = np.sort(ref_logits, axis=1)[:, -2:]
+    safe = (top2[:, 1] - top2[:, 0]) > 1e-3
+    tokens = wl.draft_tokens(M, V, seed)
+    _, _, _, ref_amax = orc32.accept_greedy(ref_logits, tokens, parent)
+    # plant: every node on the path to the deepest leaf carries its parent's argmax
+    depth = orc32.tree_depth(parent)
+    j = int(np.argmax(depth))
+    while parent[j] >= 0:
+        tokens[j] = ref_amax[parent[j]]
+        j = int(parent[j])
+    res, amax = B.ghd_accept_greedy(logits, torch.from_numpy(tokens).cuda(), pd)
+    res, amax = res.cpu().numpy(), amax.cpu().numpy()
+    assert np.array_equal(amax[safe], ref_amax[safe])
+    n, nxt, path, _ = orc32.accept_greedy(ref_logits, tokens, parent)
+    if safe.all():
+        assert res[0] == n and res[1] == nxt and np.array_equal(res[2:2 + n], path)
+        assert n == depth.max() + 1
+    return int(safe.sum())
+
+
+def test_verify_stack_tiny_with_acceptance(B, model, orc32):
+    w = wl.workload("tiny")
+    say("stack tiny")
+    stack, logits, ref_logits, pd = run_stack_case(B, model, orc32, w.shape, w.M, w.kv_len,
+                                                   w.parent, w.seed)
+    check_accept(B, orc32, logits, ref_logits, w.parent, pd, w.shape.V, w.seed)
+
+
+def test_verify_stack_small_multilayer(B, model, orc32):
+    shape = wl.ModelShape("small3", H=512, nh=4, d=128, F=1376, V=3000, L=3)
+    parent = wl.tree_random(48, 5, 9)
+    say("stack small3")
+    stack, logits, ref_logits, pd = run_stack_case(B, model, orc32, shape, 48, 333, parent, 9)
+    check_accept(B, orc32, logits, ref_logits, parent, pd, shape.V, 9)
+
+
+def test_stack_is_deterministic(B, model, orc32):
+    shape = wl.ModelShape("small2", H=512, nh=4, d=128, F=1376, V=3000, L=2)
+    parent = wl.tree_random(33, 4, 10)
+    say("stack determinism")
+    stack, logits, _, pd = run_stack_case(B, model, orc32, shape, 33, 100, parent, 10)
+    x16 = wl.activations(33, shape.H, 10).cuda()
+    again = B.ghd_verify_stack(stack, x16, pd, 100)
+    torch.cuda.synchronize()
+    assert torch.equal(logits, again)
+
+
+@pytest.mark.parametrize("M,V", [(1, 10), (8, 1000), (64, 32000), (128, 257)])
+def test_accept_greedy_same_logits_bit_exact(B, orc32, M, V):
+    say("accept", M, V)
+    rng = np.random.default_rng(M * 1000 + V)
+    parent = wl.tree_random(M, 6, M)
+    logits = rng.standard_normal((M, V)).astype(np.float32)
+    # exact ties: the lowest index must win on both sides
+    logits[:, V // 2] = logits.max(axis=1)
+    if V > 3:
+        logits[0, 1] = logits[0, V // 2]
+    pd = torch.from_numpy(parent).cuda()
+    lg = torch.from_numpy(logits).cuda()
+    ref_amax = orc32.accept_greedy(logits, np.zeros(M, np.int32), parent)[3]
+    depth = orc32.tree_depth(parent)
+    targets = sorted(set([0, M - 1, int(np.argmax(depth)), M // 2]))
+    for target in targets:
+        tokens = np.full(M, -1, dtype=np.int32)
+        j = target
+        while parent[j] >= 0:
+            tokens[j] = ref_amax[parent[j]]
+            j = int(parent[j])
+        # a duplicate sibling of the first accepted node
+        sib = [c for c in range(1, M) if parent[c] == 0 and tokens[c] == -1]
+        if sib and target != 0:
+            tokens[sib[0]] = ref_amax[0]
+        n, nxt, path, amax = orc32.accept_greedy(logits, tokens, parent)
+        res, amax_g = B.ghd_accept_greedy(lg, torch.from_numpy(tokens).cuda(), pd)
+        res, amax_g = res.cpu().numpy(), amax_g.cpu().numpy()
+        assert np.array_equal(amax_g, amax)
+        assert res[0] == n and res[1] == nxt and np.array_equal(res[2:2 + n], path)
