@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification step on one MI355X.
+
+A "step" is one pass of the whole hot path: ghd_verify_stack (32 decoder layers
++ LM head over a 64-node tree against a 2048-token KV cache, 7B-shaped) followed
+by ghd_accept_greedy.  Inputs are synthetic (random fp16 weights, random cache),
+already resident in HBM when the timed region starts.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload stack7b]
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_gpu_model(wl, B, model, w, device):
+    s = w.shape
+    layers, caches = [], []
+    for l in range(s.L):
+        layers.append(model.upload_layer(wl.layer_weights(s, w.seed, l, device=device), device))
+        caches.append(wl.kv_cache(s, w.capacity, w.kv_len, w.seed, l, device=device))
+        if l % 8 == 7:
+            log("  built layer %d/%d" % (l + 1, s.L))
+    head = model.upload_head(wl.head_weights(s, w.seed, device=device), device)
+    return model.build_stack(s, w.capacity, layers, caches, head)
+
+
+def time_steps(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, res, amax, stream,
+               steps, warmup):
+    def step():
+        B.ghd_verify_stack(stack, x_in, parent, kv_len, logits=logits, ws=ws)
+        B.ghd_accept_greedy(logits, tokens, parent, res=res, amax=amax, ws=aws)
+
+    with torch.cuda.stream(stream):
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(steps):
+            step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def gemm_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w, steps):
+    """Dominant kernel: the skinny-GEMM kernel (every linear layer of the step).
+    Its launches are bracketed by HIP events inside the library on the launch
+    stream; achieved = weight bytes streamed by those launches / summed duration."""
+    lib = B.lib()
+    lib.ghd_debug_profile_read.argtypes = [C.POINTER(C.c_float)]
+    s = w.shape
+    per_step_bytes = s.L * s.weight_bytes_per_layer() + s.lm_head_bytes()
+    tot_ms, launches = 0.0, 0
+    with torch.cuda.stream(stream):
+        for _ in range(steps):
+            lib.ghd_debug_profile_gemm(1)
+            B.ghd_verify_stack(stack, x_in, parent, kv_len, logits=logits, ws=ws)
+            lib.ghd_debug_profile_gemm(0)
+            torch.cuda.synchronize()
+            ms = C.c_float(0)
+            n = lib.ghd_debug_profile_read(C.byref(ms))
+            tot_ms += ms.value
+            launches += n
+    per_launch_bytes = per_step_bytes * steps / launches
+    avg_ms = tot_ms / launches
+    achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
+    return {"bound": "hbm", "kernel": "k_gemm_skinny", "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": None, "launches_per_step": launches // steps,
+            "avg_launch_us": round(avg_ms * 1e3, 2),
+            "algorithmic_bytes_per_launch": int(per_launch_bytes)}
+
+
+def cpu_baseline(wl, w, sample_layers):
+    """The CPU oracle, as it stands, timed on the host cores on a bounded sample of
+    the same workload: `sample_layers` decoder layers + the LM head; the step
+    latency is extrapolated linearly to all layers."""
+    import numpy as np
+    from oracle import Oracle
+    orc = Oracle("f32")
+    s = wl.with_layers(w.shape, sample_layers)
+    layers = [{k: v.numpy() for k, v in wl.layer_weights(s, w.seed, l).items()}
+              for l in range(sample_layers)]
+    head = {k: v.numpy() for k, v in wl.head_weights(s, w.seed).items()}
+    kcs, vcs = [], []
+    for l in range(sample_layers):
+        k, v = wl.kv_cache(s, w.capacity, w.kv_len, w.seed, l)
+        kcs.append(k.numpy())
+        vcs.append(v.numpy())
+    x16 = wl.activations(w.M, s.H, w.seed).numpy()
+    t0 = time.perf_counter()
+    _, x_out = orc.verify_stack(s, layers, kcs, vcs, None, x16, w.parent, w.kv_len, True)
+    t_layers = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    logits = orc.lm_head(s, head["g_final"], head["Wlm"], x_out, True)
+    orc.accept_greedy(logits, wl.draft_tokens(w.M, s.V, w.seed), w.parent)
+    t_head = time.perf_counter() - t0
+    full = t_layers * (w.shape.L / sample_layers) + t_head
+    cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
+    return {"value": round(full * 1e6, 1), "unit": "us", "cores": cores, "kind": "oracle",
+            "sample": "%d of %d layers + LM head + acceptance, M=%d, kv_len=%d; %.2f s measured, "
+                      "layers scaled x%g" % (sample_layers, w.shape.L, w.M, w.kv_len,
+                                             t_layers + t_head, w.shape.L / sample_layers)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="stack7b")
+    ap.add_argument("--cpu-sample-layers", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: the verification step runs on a single MI355X and "
+                 "no multi-GPU path exists in this build (--gpus %d refused)" % args.gpus)
+
+    import torch
+    from paper_2505_23219_amd import binding as B, model, workloads as wl
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    B.lib()
+    dev = "cuda"
+    w = wl.workload(args.workload)
+    s = w.shape
+    log("building %s: L=%d H=%d F=%d V=%d M=%d kv_len=%d" % (w.name, s.L, s.H, s.F, s.V, w.M, w.kv_len))
+    stack = build_gpu_model(wl, B, model, w, dev)
+    cfg = stack.cfg
+    stream = torch.cuda.Stream()
+
+    def inputs(M, parent_np):
+        return dict(
+            x_in=wl.activations(M, s.H, w.seed).to(dev),
+            parent=torch.from_numpy(parent_np).to(dev),
+            tokens=torch.from_numpy(wl.draft_tokens(M, s.V, w.seed)).to(dev),
+            ws=B.workspace(B.ghd_workspace_bytes(cfg, M, w.kv_len)),
+            aws=B.workspace(B.lib().ghd_accept_workspace_bytes(M)),
+            logits=torch.empty((M, s.V), dtype=torch.float32, device=dev),
+            res=torch.zeros(2 + M, dtype=torch.int32, device=dev),
+            amax=torch.empty(M, dtype=torch.int32, device=dev))
+
+    tree = inputs(w.M, w.parent)
+    ms, wall_ms = time_steps(torch, B, stack, tree["x_in"], tree["parent"], tree["tokens"], w.kv_len,
+                             tree["ws"], tree["aws"], tree["logits"], tree["res"], tree["amax"],
+                             stream, args.steps, args.warmup)
+    log("tree step: %.1f us (wall %.1f us)" % (ms * 1e3, wall_ms * 1e3))
+    # the same model as a plain 1-token decode step: denominator of the "within 1.3x" target
+    dec = inputs(1, wl.tree_chain(1))
+    dec_ms, _ = time_steps(torch, B, stack, dec["x_in"], dec["parent"], dec["tokens"], w.kv_len,
+                           dec["ws"], dec["aws"], dec["logits"], dec["res"], dec["amax"], stream,
+                           args.steps, args.warmup)
+    log("decode step: %.1f us" % (dec_ms * 1e3))
+    roof = gemm_roofline(torch, B, stack, tree["x_in"], tree["parent"], w.kv_len, tree["ws"],
+                         tree["logits"], stream, w, max(2, min(args.steps, 5)))
+    log("roofline:", roof)
+
+    step_bytes = w.algorithmic_bytes()
+    gbps = step_bytes / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "tree_verify_step_latency", "value": round(ms * 1e3, 1), "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d-layer 7B-shaped stack + LM head, %d-node tree (depth<=5), "
+                               "kv_len %d, greedy acceptance" % (w.name, s.L, w.M, w.kv_len)
+                   if w.name == "stack7b" else w.name,
+                   "M": w.M, "kv_len": w.kv_len, "L": s.L, "H": s.H, "F": s.F, "V": s.V},
+        "step_algorithmic_bytes": step_bytes,
+        "step_hbm_gbps": round(gbps, 1),
+        "step_hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
+        "decode_step_us": round(dec_ms * 1e3, 1),
+        "tree_over_decode": round(ms / dec_ms, 3),
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on %d layers ..." % args.cpu_sample_layers)
+        out["cpu_baseline"] = cpu_baseline(wl, w, args.cpu_sample_layers)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -18,6 +18,31 @@ ghd_status check_launch()
     return e == hipSuccess ? GHD_OK : hip_fail(e);
 }
 
+// ---- optional timing of the skinny-GEMM launches (benchmark support) ---------
+// When enabled, every launch_gemm call made through timed_gemm is bracketed by a
+// pair of HIP events on its stream; the caller reads the summed duration after
+// synchronising.  Off by default: the hot path records nothing.
+static bool g_prof_on = false;
+static const int kProfMax = 512;
+static hipEvent_t g_prof_ev[2 * kProfMax];
+static int g_prof_made = 0, g_prof_used = 0;
+
+static ghd_status timed_gemm(const GemmPlan& p, const void* Wp, const half_t* x, int64_t ldx,
+                             float* out, int64_t ld, int M, int N, int K, hipStream_t st)
+{
+    if (!g_prof_on || g_prof_used >= kProfMax) return launch_gemm(p, Wp, x, ldx, out, ld, M, N, K, st);
+    while (g_prof_made < 2 * (g_prof_used + 1)) {
+        hipError_t e = hipEventCreate(&g_prof_ev[g_prof_made]);
+        if (e != hipSuccess) return hip_fail(e);
+        ++g_prof_made;
+    }
+    (void)hipEventRecord(g_prof_ev[2 * g_prof_used], st);
+    ghd_status s = launch_gemm(p, Wp, x, ldx, out, ld, M, N, K, st);
+    (void)hipEventRecord(g_prof_ev[2 * g_prof_used + 1], st);
+    ++g_prof_used;
+    return s;
+}
+
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 // ---- workspace carving -------------------------------------------------------
@@ -101,7 +126,7 @@ static ghd_status run_layer(const ghd_model_cfg* c, const ghd_layer_weights* w, 
     // MHA block: QKV linear, rotate + append, tree attention, output linear
     GemmPlan p = plan_gemm(M, 3 * H, H);
     int64_t ld = (int64_t)p.ntiles * 16;
-    if ((s = launch_gemm(p, w->Wqkv, ws.n16, H, ws.part, ld, M, 3 * H, H, st))) return s;
+    if ((s = timed_gemm(p, w->Wqkv, ws.n16, H, ws.part, ld, M, 3 * H, H, st))) return s;
     if ((s = launch_qkv_epilogue(ws.part, p.S, ld, ws.rope, ws.q16, (half_t*)kv->k, (half_t*)kv->v,
                                  M, c->nh, c->d, kv_len, stride_head, stride_tok, st)))
         return s;
@@ -112,18 +137,18 @@ static ghd_status run_layer(const ghd_model_cfg* c, const ghd_layer_weights* w, 
         return s;
     p = plan_gemm(M, H, H);
     ld = (int64_t)p.ntiles * 16;
-    if ((s = launch_gemm(p, w->Wo, ws.o16, H, ws.part, ld, M, H, H, st))) return s;
+    if ((s = timed_gemm(p, w->Wo, ws.o16, H, ws.part, ld, M, H, H, st))) return s;
     if ((s = launch_residual_norm(x, nullptr, ws.part, p.S, ld, (const half_t*)w->g_ffn, ws.n16, M,
                                   H, c->rms_eps, st)))
         return s;
     // MLP block: gate|up linear + SwiGLU, down linear
     p = plan_gemm(M, 2 * F, H);
     ld = (int64_t)p.ntiles * 16;
-    if ((s = launch_gemm(p, w->Wgu, ws.n16, H, ws.part, ld, M, 2 * F, H, st))) return s;
+    if ((s = timed_gemm(p, w->Wgu, ws.n16, H, ws.part, ld, M, 2 * F, H, st))) return s;
     if ((s = launch_swiglu(ws.part, p.S, ld, ws.a16, M, F, st))) return s;
     p = plan_gemm(M, H, F);
     ld = (int64_t)p.ntiles * 16;
-    if ((s = launch_gemm(p, w->Wdown, ws.a16, F, ws.part, ld, M, H, F, st))) return s;
+    if ((s = timed_gemm(p, w->Wdown, ws.a16, F, ws.part, ld, M, H, F, st))) return s;
     return launch_residual_norm(x, nullptr, ws.part, p.S, ld, next_g, ws.n16, M, H, c->rms_eps, st);
 }
 
@@ -202,7 +227,7 @@ ghd_status ghd_linear_skinny(void* y, const void* x, const void* Wp, int M, int 
     hipStream_t st = (hipStream_t)stream;
     GemmPlan p = plan_gemm(M, N, K);
     int64_t ld = (int64_t)p.ntiles * 16;
-    ghd_status s = launch_gemm(p, Wp, (const half_t*)x, ldx, (float*)ws, ld, M, N, K, st);
+    ghd_status s = timed_gemm(p, Wp, (const half_t*)x, ldx, (float*)ws, ld, M, N, K, st);
     if (s) return s;
     return launch_reduce_out(y, ldy, flags == GHD_OUT_F16, (const float*)ws, p.S, ld, M, N, st);
 }
@@ -324,7 +349,7 @@ ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* l
     // LM head on the final norm
     GemmPlan p = plan_gemm(M, cfg->V, H);
     int64_t ld = (int64_t)p.ntiles * 16;
-    if ((s = launch_gemm(p, Wlm, lw.n16, H, lw.part, ld, M, cfg->V, H, st))) return s;
+    if ((s = timed_gemm(p, Wlm, lw.n16, H, lw.part, ld, M, cfg->V, H, st))) return s;
     return launch_reduce_out(logits, cfg->V, false, lw.part, p.S, ld, M, cfg->V, st);
 }
 
@@ -348,7 +373,29 @@ ghd_status ghd_accept_greedy(const float* logits, const int32_t* tokens_dev,
 }
 
 /* Tuning hooks for sweeps (not part of the documented ABI). */
-void ghd_debug_set_gemm_plan(int nt, int s) { set_gemm_override(nt, s); }
+void ghd_debug_set_gemm_plan(int nt, int s, int nw, int lds) { set_gemm_override(nt, s, nw, lds); }
 void ghd_debug_set_attn_splits(int p) { set_attn_override(p); }
+
+/* Benchmark support: time the skinny-GEMM launches of ghd_verify_layer/stack with
+ * HIP events.  ghd_debug_profile_gemm(1) starts a fresh measurement,
+ * ghd_debug_profile_gemm(0) stops it; after synchronising the stream,
+ * ghd_debug_profile_read returns the number of launches and their summed
+ * duration in milliseconds. */
+void ghd_debug_profile_gemm(int enable)
+{
+    g_prof_on = enable != 0;
+    if (enable) g_prof_used = 0;
+}
+
+int ghd_debug_profile_read(float* total_ms)
+{
+    float tot = 0.f;
+    for (int i = 0; i < g_prof_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_prof_ev[2 * i], g_prof_ev[2 * i + 1]) == hipSuccess) tot += ms;
+    }
+    if (total_ms) *total_ms = tot;
+    return g_prof_used;
+}
 
 }  // extern "C"

@@ -31,10 +31,12 @@ struct GemmPlan {
     int kps;     // k-steps (32 columns each) per split
     int ksteps;  // ceil(K/32)
     int ntiles;  // ceil(N/16)
+    int NW;      // wavefronts per workgroup
+    bool lds;    // stage x through LDS (M > 16)
 };
 GemmPlan plan_gemm(int M, int N, int K);
 // test hook: force NT / S (0 = automatic)
-void set_gemm_override(int nt, int s);
+void set_gemm_override(int nt, int s, int nw, int lds);
 
 struct AttnPlan {
     int P;       // key-range splits

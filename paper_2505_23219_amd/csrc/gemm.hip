@@ -137,8 +137,144 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(const half8* __restrict__ W
     }
 }
 
-static int g_force_nt = 0, g_force_s = 0;
-void set_gemm_override(int nt, int s) { g_force_nt = nt; g_force_s = s; }
+
+// Variant for M > 16: x no longer fits the register/L1 budget of every
+// wavefront, so the workgroup (NW wavefronts that share a K range and own
+// NW*NT consecutive weight tiles) stages x through LDS in chunks of DEPTH
+// k-steps, double buffered, one barrier per chunk.  Fragments are stored in
+// B-operand order (k-step, row tile, lane) with each 16-lane group padded by
+// 16 bytes, so the 128-bit reads are conflict free.  The weight stream is
+// unchanged: DEPTH k-steps of 128-bit loads in flight per wavefront.
+template <int MT, int NT, int NW, int DEPTH>
+__global__ __launch_bounds__(NW * 64) void k_gemm_lds(const half8* __restrict__ Wp,
+                                                      const half_t* __restrict__ x,
+                                                      float* __restrict__ out, int M, int N, int K,
+                                                      int64_t ldx, int64_t ld, int ksteps, int kps,
+                                                      int ntiles)
+{
+    constexpr int FRAG = 4 * 272;                 // bytes of one padded 16x32 fragment
+    constexpr int CHUNK = DEPTH * MT * FRAG;      // bytes of one x chunk
+    constexpr int PIECES = DEPTH * MT * 64;       // 16-byte pieces per chunk
+    constexpr int T = NW * 64;
+    constexpr int PPT = (PIECES + T - 1) / T;
+    __shared__ __attribute__((aligned(16))) char xs[2 * CHUNK];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c = lane & 15, g = lane >> 4;
+    const int tile0 = (blockIdx.x * NW + wave) * NT;
+    const int split = blockIdx.y;
+    const int ks0 = split * kps;
+    const int ks1 = min(ks0 + kps, ksteps);
+    const int nchunks = (ks1 - ks0 + DEPTH - 1) / DEPTH;
+
+    const half8* wptr[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        int tile = min(tile0 + t, ntiles - 1);
+        wptr[t] = Wp + (size_t)tile * ksteps * 64 + lane;
+    }
+
+    // x staging: piece p -> (fragment f = p/64, row c = (p/4)%16, k group g = p%4)
+    const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    int p_src_row[PPT], p_koff[PPT], p_dst[PPT];
+    bool p_ok[PPT];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) {
+        int p = tid + i * T;
+        int f = p >> 6, pc = (p >> 2) & 15, pg = p & 3;
+        int s = f / MT, mt = f % MT;
+        int m = mt * 16 + pc;
+        p_ok[i] = (p < PIECES) && (m < M);
+        p_src_row[i] = min(m, M - 1);
+        p_koff[i] = s * 32 + pg * 8;
+        p_dst[i] = f * FRAG + pg * 272 + pc * 16;
+    }
+    half8 xr[PPT];
+    auto x_fetch = [&](int chunk) {
+        int kbase = (ks0 + chunk * DEPTH) * 32;
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            int k = kbase + p_koff[i];
+            bool ok = p_ok[i] && k < K && (k >> 5) < ks1;
+            xr[i] = ok ? *(const half8*)(x + (size_t)p_src_row[i] * ldx + k) : zero8;
+        }
+    };
+    auto x_store = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < PPT; ++i)
+            if (tid + i * T < PIECES) *(half8*)(xs + buf * CHUNK + p_dst[i]) = xr[i];
+    };
+
+    floatx4 acc[NT][MT];
+#pragma unroll
+    for (int a = 0; a < NT; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b) acc[a][b] = (floatx4){0.f, 0.f, 0.f, 0.f};
+
+    half8 wb[DEPTH][NT];
+    auto w_fetch = [&](int slot, int ks) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) wb[slot][t] = (ks < ks1) ? wptr[t][(size_t)ks * 64] : zero8;
+    };
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) w_fetch(u, ks0 + u);
+
+    x_fetch(0);
+    x_store(0);
+    if (nchunks > 1) x_fetch(1);
+    __syncthreads();
+
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const char* xb = xs + (ch & 1) * CHUNK + g * 272 + c * 16;
+        const int ks = ks0 + ch * DEPTH;
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+            half8 xf[MT];
+#pragma unroll
+            for (int b = 0; b < MT; ++b) xf[b] = *(const half8*)(xb + (u * MT + b) * FRAG);
+#pragma unroll
+            for (int a = 0; a < NT; ++a)
+#pragma unroll
+                for (int b = 0; b < MT; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wb[u][a], xf[b], acc[a][b], 0,
+                                                                      0, 0);
+            w_fetch(u, ks + u + DEPTH);
+        }
+        if (ch + 1 < nchunks) {
+            x_store((ch + 1) & 1);
+            if (ch + 2 < nchunks) x_fetch(ch + 2);
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int a = 0; a < NT; ++a) {
+        if (tile0 + a >= ntiles) break;
+        int n0 = (tile0 + a) * 16 + g * 4;
+#pragma unroll
+        for (int b = 0; b < MT; ++b) {
+            int m = b * 16 + c;
+            if (m >= M) continue;
+            float* o = out + ((size_t)split * M + m) * ld + n0;
+            if (n0 + 3 < N && ((ld & 3) == 0)) {
+                *(floatx4*)o = acc[a][b];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (n0 + r < N) o[r] = acc[a][b][r];
+            }
+        }
+    }
+}
+
+static int g_force_nt = 0, g_force_s = 0, g_force_nw = 0, g_force_lds = -1;
+void set_gemm_override(int nt, int s, int nw, int lds)
+{
+    g_force_nt = nt;
+    g_force_s = s;
+    g_force_nw = nw;
+    g_force_lds = lds;
+}
 
 GemmPlan plan_gemm(int M, int N, int K)
 {
@@ -146,9 +282,15 @@ GemmPlan plan_gemm(int M, int N, int K)
     p.MT = ceil_div(M, 16);
     p.ksteps = ceil_div(K, 32);
     p.ntiles = ceil_div(N, 16);
+    p.lds = p.MT >= 2;
+    if (g_force_lds >= 0) p.lds = g_force_lds != 0 && p.MT >= 2;
+    p.NW = 4;
+    if (g_force_nw) p.NW = g_force_nw;
+    if (!p.lds) p.NW = 4;
     // Two weight tiles per wavefront reuse every x fragment twice once x traffic matters.
     p.NT = (p.MT >= 2 && p.ntiles >= 512) ? 2 : 1;
     if (g_force_nt) p.NT = g_force_nt;
+    if (p.lds && p.NW == 8 && p.MT >= 7 && p.NT > 2) p.NT = 2;   // register budget of 512 threads
     // Enough wavefronts to keep ~8 per compute unit streaming, at least 8 k-steps each.
     int waves = ceil_div(p.ntiles, p.NT);
     int S = 1;
@@ -165,37 +307,63 @@ GemmPlan plan_gemm(int M, int N, int K)
 }
 
 template <int MT, int NT>
-static void launch_gemm_t(const GemmPlan& p, const void* Wp, const half_t* x, int64_t ldx,
+static void launch_direct(const GemmPlan& p, const void* Wp, const half_t* x, int64_t ldx,
                           float* out, int64_t ld, int M, int N, int K, hipStream_t st)
 {
-    constexpr int DEPTH = (NT * 4 >= 8) ? (NT == 4 ? 2 : 4) : 6;
+    constexpr int DEPTH = (NT == 1) ? 6 : (NT == 2 ? 4 : 2);
     dim3 grid(ceil_div(p.ntiles, 4 * NT), p.S);
     hipLaunchKernelGGL((k_gemm_skinny<MT, NT, DEPTH>), grid, dim3(256), 0, st, (const half8*)Wp, x,
                        out, M, N, K, ldx, ld, p.ksteps, p.kps, p.ntiles);
 }
 
-template <int NT>
-static void launch_gemm_nt(const GemmPlan& p, const void* Wp, const half_t* x, int64_t ldx,
-                           float* out, int64_t ld, int M, int N, int K, hipStream_t st)
+template <int MT, int NT, int NW>
+static void launch_lds(const GemmPlan& p, const void* Wp, const half_t* x, int64_t ldx, float* out,
+                       int64_t ld, int M, int N, int K, hipStream_t st)
 {
-    switch (p.MT) {
-    case 1: launch_gemm_t<1, NT>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
-    case 2: launch_gemm_t<2, NT>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
-    case 3: launch_gemm_t<3, NT>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
-    case 4: launch_gemm_t<4, NT>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
-    case 5: launch_gemm_t<5, NT>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
-    case 6: launch_gemm_t<6, NT>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
-    case 7: launch_gemm_t<7, NT>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
-    default: launch_gemm_t<8, NT>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
+    constexpr int DEPTH = 4;
+    dim3 grid(ceil_div(p.ntiles, NW * NT), p.S);
+    hipLaunchKernelGGL((k_gemm_lds<MT, NT, NW, DEPTH>), grid, dim3(NW * 64), 0, st, (const half8*)Wp,
+                       x, out, M, N, K, ldx, ld, p.ksteps, p.kps, p.ntiles);
+}
+
+template <int MT>
+static void launch_mt(const GemmPlan& p, const void* Wp, const half_t* x, int64_t ldx, float* out,
+                      int64_t ld, int M, int N, int K, hipStream_t st)
+{
+#define GHD_ARGS p, Wp, x, ldx, out, ld, M, N, K, st
+    if constexpr (MT >= 2) {
+        if (p.lds) {
+            if (p.NW == 8) {
+                if (p.NT == 1) launch_lds<MT, 1, 8>(GHD_ARGS);
+                else if (p.NT == 2) launch_lds<MT, 2, 8>(GHD_ARGS);
+                else launch_lds<MT, 4, 8>(GHD_ARGS);
+            } else {
+                if (p.NT == 1) launch_lds<MT, 1, 4>(GHD_ARGS);
+                else if (p.NT == 2) launch_lds<MT, 2, 4>(GHD_ARGS);
+                else launch_lds<MT, 4, 4>(GHD_ARGS);
+            }
+            return;
+        }
     }
+    if (p.NT == 1) launch_direct<MT, 1>(GHD_ARGS);
+    else if (p.NT == 2) launch_direct<MT, 2>(GHD_ARGS);
+    else launch_direct<MT, 4>(GHD_ARGS);
+#undef GHD_ARGS
 }
 
 ghd_status launch_gemm(const GemmPlan& p, const void* Wp, const half_t* x, int64_t ldx, float* out,
                        int64_t ld, int M, int N, int K, hipStream_t st)
 {
-    if (p.NT == 1) launch_gemm_nt<1>(p, Wp, x, ldx, out, ld, M, N, K, st);
-    else if (p.NT == 2) launch_gemm_nt<2>(p, Wp, x, ldx, out, ld, M, N, K, st);
-    else launch_gemm_nt<4>(p, Wp, x, ldx, out, ld, M, N, K, st);
+    switch (p.MT) {
+    case 1: launch_mt<1>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
+    case 2: launch_mt<2>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
+    case 3: launch_mt<3>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
+    case 4: launch_mt<4>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
+    case 5: launch_mt<5>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
+    case 6: launch_mt<6>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
+    case 7: launch_mt<7>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
+    default: launch_mt<8>(p, Wp, x, ldx, out, ld, M, N, K, st); break;
+    }
     return check_launch();
 }
 
