@@ -29,7 +29,7 @@ def build_gpu_model(wl, B, model, w, device):
     s = w.shape
     layers, caches = [], []
     for l in range(s.L):
-        layers.append(model.upload_layer(wl.layer_weights(s, w.seed, l, device=device), device))
+        layers.append(model.upload_layer(wl.layer_weights(s, w.seed, l, device=device), s.d, device))
         caches.append(wl.kv_cache(s, w.capacity, w.kv_len, w.seed, l, device=device))
         if l % 8 == 7:
             log("  built layer %d/%d" % (l + 1, s.L))
@@ -59,29 +59,28 @@ def time_steps(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, r
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
-def gemm_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w, steps):
-    """Dominant kernel: the skinny-GEMM kernel (every linear layer of the step).
-    Its launches are bracketed by HIP events inside the library on the launch
-    stream; achieved = weight bytes streamed by those launches / summed duration."""
+def fused_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w, steps):
+    """Dominant kernel: the persistent verification kernel (one launch runs every
+    linear layer and every attention of the step).  Its launches are bracketed by HIP
+    events inside the library, on the launch stream; achieved = algorithmic bytes of
+    one step (all weights once + all cache rows once) / average launch duration."""
     lib = B.lib()
     lib.ghd_debug_profile_read.argtypes = [C.POINTER(C.c_float)]
-    s = w.shape
-    per_step_bytes = s.L * s.weight_bytes_per_layer() + s.lm_head_bytes()
     tot_ms, launches = 0.0, 0
     with torch.cuda.stream(stream):
         for _ in range(steps):
-            lib.ghd_debug_profile_gemm(1)
+            lib.ghd_debug_profile(1)
             B.ghd_verify_stack(stack, x_in, parent, kv_len, logits=logits, ws=ws)
-            lib.ghd_debug_profile_gemm(0)
+            lib.ghd_debug_profile(0)
             torch.cuda.synchronize()
             ms = C.c_float(0)
             n = lib.ghd_debug_profile_read(C.byref(ms))
             tot_ms += ms.value
             launches += n
-    per_launch_bytes = per_step_bytes * steps / launches
+    per_launch_bytes = w.algorithmic_bytes()
     avg_ms = tot_ms / launches
     achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
-    return {"bound": "hbm", "kernel": "k_gemm_skinny", "achieved": round(achieved, 1),
+    return {"bound": "hbm", "kernel": "k_fused", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": None, "launches_per_step": launches // steps,
             "avg_launch_us": round(avg_ms * 1e3, 2),
@@ -168,7 +167,7 @@ def main():
                            dec["ws"], dec["aws"], dec["logits"], dec["res"], dec["amax"], stream,
                            args.steps, args.warmup)
     log("decode step: %.1f us" % (dec_ms * 1e3))
-    roof = gemm_roofline(torch, B, stack, tree["x_in"], tree["parent"], w.kv_len, tree["ws"],
+    roof = fused_roofline(torch, B, stack, tree["x_in"], tree["parent"], w.kv_len, tree["ws"],
                          tree["logits"], stream, w, max(2, min(args.steps, 5)))
     log("roofline:", roof)
 

@@ -13,9 +13,9 @@
  *     nothing and keeps no pointer after the call returns.
  *   - fp16 tensors are IEEE binary16.  Activations are row-major [M, width].
  *   - Weight matrices are passed in the PACKED layout written by
- *     ghd_pack_weight (same bytes as the row-major [N, K] matrix, padded to
- *     N%16 == 0 and K%32 == 0, reordered so that each wavefront streams
- *     contiguous 1 KiB blocks).
+ *     ghd_pack_weight (the bytes of the row-major [N, K] matrix, zero padded to
+ *     N%256 == 0 and K%128 == 0 and reordered so that every workgroup streams
+ *     one contiguous range in 1 KiB MFMA-operand blocks).
  *   - The KV cache of one layer is fp16, element (head h, row t, channel c) at
  *     h*stride_head + t*stride_tok + c; rows [0, kv_len) are committed, row
  *     kv_len + i belongs to tree node i.
@@ -57,6 +57,7 @@ enum {
 #define GHD_OUT_F32 0u      /* y is float  [M, ldy] */
 #define GHD_OUT_F16 1u      /* y is fp16   [M, ldy] */
 
+/* Limits: L <= 48, nh <= 256, H <= 43520, F <= 65536, V <= 262144, F % 8 == 0. */
 typedef struct {
     int32_t H;            /* hidden size                         */
     int32_t nh;           /* attention heads (multi-head: kv heads == heads) */
@@ -93,10 +94,12 @@ ghd_status ghd_tree_validate(const int32_t *parent_host, int M);
 /* Ancestor-or-self mask of section 2.3 ("a token needs to compute
  * relationships only with certain tokens"): bit j of the 128-bit word
  * mask[i] = {mask_dev[2i] (bits 0..63), mask_dev[2i+1] (bits 64..127)} is set
- * iff node j is on the root path of node i.  Same device routine the attention
- * kernel uses.  Every walk is bounded by M steps, so a malformed device
- * parent[] cannot hang. */
-ghd_status ghd_tree_mask(const int32_t *parent_dev, int M, uint64_t *mask_dev, void *stream);
+ * iff node j is on the root path of node i.  Written by the same set-up kernel
+ * whose masks the attention phase tests.  Every walk is bounded by M steps, so a
+ * malformed device parent[] cannot hang. */
+ghd_status ghd_tree_mask(const int32_t *parent_dev, int M, uint64_t *mask_dev, void *ws,
+                         size_t ws_bytes, void *stream);
+size_t ghd_tree_mask_workspace_bytes(void);
 
 /* ---- weights ---------------------------------------------------------- */
 
@@ -104,10 +107,26 @@ ghd_status ghd_tree_mask(const int32_t *parent_dev, int M, uint64_t *mask_dev, v
 size_t ghd_packed_weight_bytes(int N, int K);
 
 /* dst (packed) <- src (row-major [N, K] fp16, device).  One-off, offline.
- * Layout: tiles of 16 rows x 32 columns, tile (n/16, k/32) at block index
- * (n/16)*ceil(K/32) + k/32; inside a 1 KiB block, 16-byte chunk number
- * ((k%32)/8)*16 + n%16 holds W[n][k - k%8 .. +8].  Padding is zero. */
-ghd_status ghd_pack_weight(void *dst, const void *src, int N, int K, void *stream);
+ * Layout: packed row p and column k live in row group p/256, k-step k/32, tile
+ * (p%256)/16; the 1 KiB block of (group, k-step, tile) sits at block index
+ * (group*KS + k-step)*16 + tile with KS = 4*ceil(K/128); inside a block the
+ * 16-byte chunk number ((k%32)/8)*16 + p%16 holds row p, columns k-k%8 .. +8.
+ * Padding is zero.  `kind` chooses which source row packed row p holds:
+ *   GHD_PACK_PLAIN    row p
+ *   GHD_PACK_QKV      src is [3H, K] (q, k, v rows; heads of head_dim rows): in
+ *                     every head, packed rows 4i..4i+3 hold channels 2i, 2i+1,
+ *                     2i+head_dim/2, 2i+1+head_dim/2 (the two rotary pairs of a
+ *                     quad end up in one lane of the GEMM output)
+ *   GHD_PACK_GATE_UP  src is [2F, K] (gate rows then up rows), F%8 == 0: packed
+ *                     rows 16t+4i .. +3 hold gate 8t+2i, gate 8t+2i+1, up 8t+2i,
+ *                     up 8t+2i+1
+ * ghd_linear_skinny takes GHD_PACK_PLAIN matrices; ghd_verify_layer/stack take
+ * Wqkv as GHD_PACK_QKV, Wgu as GHD_PACK_GATE_UP and the rest as GHD_PACK_PLAIN. */
+#define GHD_PACK_PLAIN 0
+#define GHD_PACK_QKV 1
+#define GHD_PACK_GATE_UP 2
+ghd_status ghd_pack_weight(void *dst, const void *src, int N, int K, int kind, int head_dim,
+                           void *stream);
 
 /* ---- skinny linear layer (section 2.2.2: the linear layers of the MHA and
  *      MLP blocks; with 1..128 rows their cost is streaming W once) -------- */
@@ -131,7 +150,7 @@ size_t ghd_linear_workspace_bytes(int M, int N, int K);
  *   k_cache, v_cache  fp16, strides in elements, stride_tok % 8 == 0;
  *                     rows [0, kv_len + M) must be readable.
  * Splits the key range over workgroups and merges the parts with the
- * online-softmax rescaling of section 3.2.2. */
+ * online-softmax rescaling of section 3.2.2.  nh <= 256. */
 ghd_status ghd_tree_attention(void *out, const void *q, const void *k_cache, const void *v_cache,
                               const int32_t *parent_dev, int M, int kv_len, int nh, int d,
                               int64_t stride_head, int64_t stride_tok, float scale, void *ws,
@@ -157,6 +176,15 @@ ghd_status ghd_verify_stack(const ghd_model_cfg *cfg, const ghd_layer_weights *l
                             const void *x_in, const int32_t *parent_dev, int M, int kv_len,
                             float *logits, float *x_out, void *ws, size_t ws_bytes, void *stream);
 size_t ghd_workspace_bytes(const ghd_model_cfg *cfg, int M, int kv_len);
+
+/* The step runs as one persistent kernel whose workgroups meet at grid-wide
+ * barriers; every wait is bounded and gives up rather than hang (for instance if
+ * other work on the GPU keeps some workgroups from becoming resident).  This
+ * call synchronises `stream` and reports the status word the last
+ * ghd_linear_skinny / ghd_tree_attention / ghd_verify_layer / ghd_verify_stack
+ * call left in its workspace `ws`: 0 = completed, 1 = a wait gave up and the
+ * outputs are invalid.  Blocking; for tests and error handling, not the hot path. */
+ghd_status ghd_step_status(const void *ws, int32_t *status_host, void *stream);
 
 /* ---- greedy acceptance ("fall back to the longest validated prefix",
  *      section 2.3) ------------------------------------------------------ */

@@ -20,13 +20,17 @@ GHD_OK = 0
 GHD_ERR_NULL, GHD_ERR_SHAPE, GHD_ERR_TREE, GHD_ERR_CAPACITY = -1, -2, -3, -4
 GHD_ERR_WORKSPACE, GHD_ERR_ALIGN, GHD_ERR_HIP = -5, -6, -7
 GHD_OUT_F32, GHD_OUT_F16 = 0, 1
+GHD_PACK_PLAIN, GHD_PACK_QKV, GHD_PACK_GATE_UP = 0, 1, 2
 GHD_MAX_M = 128
 
 
 class GhdError(RuntimeError):
     def __init__(self, status: int, what: str):
         self.status = status
-        super().__init__("%s: %s (status %d)" % (what, status_str(status), status))
+        extra = ""
+        if status == GHD_ERR_HIP:
+            extra = ", hip error %d" % lib().ghd_last_hip_error()
+        super().__init__("%s: %s (status %d%s)" % (what, status_str(status), status, extra))
 
 
 class ModelCfg(C.Structure):
@@ -58,9 +62,11 @@ def lib() -> C.CDLL:
             "ghd_status_str": (C.c_char_p, [C.c_int32]),
             "ghd_last_hip_error": (C.c_int, []),
             "ghd_tree_validate": (C.c_int32, [vp, i32]),
-            "ghd_tree_mask": (C.c_int32, [vp, i32, vp, vp]),
+            "ghd_tree_mask": (C.c_int32, [vp, i32, vp, vp, sz, vp]),
+            "ghd_tree_mask_workspace_bytes": (sz, []),
+            "ghd_step_status": (C.c_int32, [vp, vp, vp]),
             "ghd_packed_weight_bytes": (sz, [i32, i32]),
-            "ghd_pack_weight": (C.c_int32, [vp, vp, i32, i32, vp]),
+            "ghd_pack_weight": (C.c_int32, [vp, vp, i32, i32, i32, i32, vp]),
             "ghd_linear_skinny": (C.c_int32, [vp, vp, vp, i32, i32, i32, i64, i64, u32, vp, sz, vp]),
             "ghd_linear_workspace_bytes": (sz, [i32, i32, i32]),
             "ghd_tree_attention": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, f32,
@@ -82,6 +88,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["ghd_status_str", "ghd_last_hip_error", "ghd_tree_validate", "ghd_tree_mask",
+           "ghd_tree_mask_workspace_bytes", "ghd_step_status",
            "ghd_packed_weight_bytes", "ghd_pack_weight", "ghd_linear_skinny",
            "ghd_linear_workspace_bytes", "ghd_tree_attention", "ghd_attention_workspace_bytes",
            "ghd_verify_layer", "ghd_verify_stack", "ghd_workspace_bytes", "ghd_accept_greedy",
@@ -129,18 +136,26 @@ def ghd_tree_mask(parent: torch.Tensor) -> torch.Tensor:
     """parent int32 [M] on the GPU -> int64 [M, 2] holding the 128-bit masks."""
     M = parent.numel()
     mask = torch.zeros((M, 2), dtype=torch.int64, device=parent.device)
-    _check(lib().ghd_tree_mask(_ptr(_dev(parent, torch.int32)), M, _ptr(mask), _stream()),
-           "ghd_tree_mask")
+    ws = workspace(lib().ghd_tree_mask_workspace_bytes(), parent.device)
+    _check(lib().ghd_tree_mask(_ptr(_dev(parent, torch.int32)), M, _ptr(mask), _ptr(ws), ws.numel(),
+                               _stream()), "ghd_tree_mask")
     return mask
 
 
+def ghd_step_status(ws: torch.Tensor) -> int:
+    """Synchronises the stream; 0 = the last step on `ws` completed, 1 = a bounded wait gave up."""
+    st = C.c_int32(-1)
+    _check(lib().ghd_step_status(_ptr(ws), C.byref(st), _stream()), "ghd_step_status")
+    return int(st.value)
+
+
 # ---- weights ----------------------------------------------------------------
-def ghd_pack_weight(W: torch.Tensor) -> torch.Tensor:
+def ghd_pack_weight(W: torch.Tensor, kind: int = GHD_PACK_PLAIN, head_dim: int = 0) -> torch.Tensor:
     """Row-major fp16 [N, K] on the GPU -> packed bytes (uint8 tensor)."""
     N, K = W.shape
     out = torch.empty(lib().ghd_packed_weight_bytes(N, K), dtype=torch.uint8, device=W.device)
-    _check(lib().ghd_pack_weight(_ptr(out), _ptr(_dev(W, torch.float16)), N, K, _stream()),
-           "ghd_pack_weight")
+    _check(lib().ghd_pack_weight(_ptr(out), _ptr(_dev(W, torch.float16)), N, K, kind, head_dim,
+                                 _stream()), "ghd_pack_weight")
     return out
 
 

@@ -1,6 +1,6 @@
-// Host side of the C ABI (include/ghd.h): argument checks, workspace layout,
-// launch sequence of the verification step.  No device code here.
-#include "common.h"
+// Host side of the C ABI (include/ghd.h): argument checks, workspace layout and the
+// launches of the verification step.  No device code here.
+#include "fused.h"
 
 namespace ghd {
 
@@ -18,26 +18,25 @@ ghd_status check_launch()
     return e == hipSuccess ? GHD_OK : hip_fail(e);
 }
 
-// ---- optional timing of the skinny-GEMM launches (benchmark support) ---------
-// When enabled, every launch_gemm call made through timed_gemm is bracketed by a
-// pair of HIP events on its stream; the caller reads the summed duration after
-// synchronising.  Off by default: the hot path records nothing.
+// ---- optional timing of the persistent kernel (benchmark support) -----------------
+// When enabled, every launch of the persistent kernel is bracketed by a pair of HIP
+// events on its stream; the caller reads the summed duration after synchronising.
+// Off by default: the hot path records nothing.
 static bool g_prof_on = false;
-static const int kProfMax = 512;
+static const int kProfMax = 256;
 static hipEvent_t g_prof_ev[2 * kProfMax];
 static int g_prof_made = 0, g_prof_used = 0;
 
-static ghd_status timed_gemm(const GemmPlan& p, const void* Wp, const half_t* x, int64_t ldx,
-                             float* out, int64_t ld, int M, int N, int K, hipStream_t st)
+static ghd_status timed_fused(const FusedArgs& a, hipStream_t st)
 {
-    if (!g_prof_on || g_prof_used >= kProfMax) return launch_gemm(p, Wp, x, ldx, out, ld, M, N, K, st);
+    if (!g_prof_on || g_prof_used >= kProfMax) return launch_fused(a, st);
     while (g_prof_made < 2 * (g_prof_used + 1)) {
         hipError_t e = hipEventCreate(&g_prof_ev[g_prof_made]);
         if (e != hipSuccess) return hip_fail(e);
         ++g_prof_made;
     }
     (void)hipEventRecord(g_prof_ev[2 * g_prof_used], st);
-    ghd_status s = launch_gemm(p, Wp, x, ldx, out, ld, M, N, K, st);
+    ghd_status s = launch_fused(a, st);
     (void)hipEventRecord(g_prof_ev[2 * g_prof_used + 1], st);
     ++g_prof_used;
     return s;
@@ -45,7 +44,21 @@ static ghd_status timed_gemm(const GemmPlan& p, const void* Wp, const half_t* x,
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-// ---- workspace carving -------------------------------------------------------
+// Number of workgroups of the persistent kernel; 256 (the MI355X's compute units) when
+// no device can be queried, so that workspace sizes are defined on a GPU-less host.
+static int grid_for_sizing()
+{
+    int g = fused_grid_size();
+    return g > 0 ? g : 256;
+}
+
+static int mpad_of(int M)
+{
+    int mt = (M + 15) / 16;
+    return (mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : 8) * 16;
+}
+
+// ---- workspace carving ---------------------------------------------------------
 struct Carver {
     char* base;
     size_t off;
@@ -59,46 +72,40 @@ struct Carver {
     }
 };
 
-static size_t gemm_part_floats(int M, int N, int K)
-{
-    GemmPlan p = plan_gemm(M, N, K);
-    return (size_t)p.S * M * ((size_t)p.ntiles * 16);
-}
-
-struct LayerWs {
-    int32_t* depth;
-    uint64_t* mask;
+struct Ws {
+    uint32_t* sync;
+    float *part, *o_part, *ml_part, *x, *ss, *y32;
+    half_t *q16, *o16, *a16, *n16;
     float2* rope;
-    half_t *n16, *q16, *o16, *a16;
-    float *part, *o_part, *ml_part;
-    float* x;       // residual stream (stack only)
-    int32_t* amax;  // unused by the layer
+    uint64_t* mask;
     size_t bytes;
 };
 
-static LayerWs carve(void* ws, const ghd_model_cfg* c, int M, int kv_len, bool stack)
+// what: 0 = whole model (layer / stack), 1 = linear only, 2 = attention only
+static Ws carve(void* ws, int what, int M, int H, int F, int d)
 {
     Carver cv(ws);
-    LayerWs w;
-    w.depth = cv.take<int32_t>(GHD_MAX_M);
-    w.mask = cv.take<uint64_t>(2 * GHD_MAX_M);
-    w.rope = cv.take<float2>((size_t)M * (c->d / 2));
-    w.n16 = cv.take<half_t>((size_t)M * c->H);
-    w.q16 = cv.take<half_t>((size_t)M * c->H);
-    w.o16 = cv.take<half_t>((size_t)M * c->H);
-    w.a16 = cv.take<half_t>((size_t)M * c->F);
-    size_t pf = gemm_part_floats(M, 3 * c->H, c->H);
-    size_t t;
-    if ((t = gemm_part_floats(M, c->H, c->H)) > pf) pf = t;
-    if ((t = gemm_part_floats(M, 2 * c->F, c->H)) > pf) pf = t;
-    if ((t = gemm_part_floats(M, c->H, c->F)) > pf) pf = t;
-    if (stack && (t = gemm_part_floats(M, c->V, c->H)) > pf) pf = t;
-    w.part = cv.take<float>(pf);
-    AttnPlan a = plan_attention(M, kv_len, c->nh);
-    w.o_part = cv.take<float>((size_t)a.P * c->nh * M * c->d);
-    w.ml_part = cv.take<float>((size_t)a.P * c->nh * M * 2);
-    w.x = stack ? cv.take<float>((size_t)M * c->H) : nullptr;
-    w.amax = nullptr;
+    Ws w = {};
+    const int G = grid_for_sizing();
+    const int Mpad = mpad_of(M);
+    w.sync = cv.take<uint32_t>(kSyncWords);
+    if (what != 2) w.part = cv.take<float>((size_t)G * 2 * kTG * (Mpad / 16) * 256);
+    if (what != 1) {
+        w.mask = cv.take<uint64_t>(2 * GHD_MAX_M);
+        w.o_part = cv.take<float>((size_t)G * 4 * Mpad * d);
+        w.ml_part = cv.take<float>((size_t)G * 4 * Mpad * 2);
+    }
+    if (what == 0) {
+        w.rope = cv.take<float2>((size_t)GHD_MAX_M * (d / 2));
+        w.x = cv.take<float>((size_t)M * H);
+        w.ss = cv.take<float>((size_t)(H / 16) * Mpad);
+        w.q16 = cv.take<half_t>((size_t)M * H);
+        w.o16 = cv.take<half_t>((size_t)M * H);
+        w.a16 = cv.take<half_t>((size_t)M * F);
+        w.n16 = cv.take<half_t>((size_t)M * H);
+        size_t wide = (size_t)(3 * H > 2 * F ? 3 * H : 2 * F);
+        w.y32 = cv.take<float>((size_t)M * wide);
+    }
     w.bytes = cv.off;
     return w;
 }
@@ -107,49 +114,146 @@ static ghd_status check_cfg(const ghd_model_cfg* c, int M, int kv_len)
 {
     if (!c) return GHD_ERR_NULL;
     if (M < 1 || M > GHD_MAX_M || kv_len < 0) return GHD_ERR_SHAPE;
-    if ((c->d != 64 && c->d != 128) || c->nh < 1 || c->H != c->nh * c->d) return GHD_ERR_SHAPE;
-    if (c->F < 8 || (c->F % 8) != 0 || c->L < 1 || c->V < 1) return GHD_ERR_SHAPE;
+    if ((c->d != 64 && c->d != 128) || c->nh < 1 || c->nh > 256 || c->H != c->nh * c->d)
+        return GHD_ERR_SHAPE;
+    if (c->F < 8 || (c->F % 8) != 0 || c->L < 1 || c->L > kMaxLayers || c->V < 1) return GHD_ERR_SHAPE;
+    if (3 * (int64_t)c->H > 512 * kGroupRows || 2 * (int64_t)c->F > 512 * kGroupRows ||
+        (int64_t)c->V > 1024 * kGroupRows)
+        return GHD_ERR_SHAPE;
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return GHD_ERR_SHAPE;
     if ((int64_t)kv_len + M > (int64_t)c->kv_capacity) return GHD_ERR_CAPACITY;
     return GHD_OK;
 }
 
-// One layer with n16 = rmsnorm(x) * g_attn already in ws.n16.  On return x holds the
-// layer's output and, if next_g is given, ws.n16 = rmsnorm(x) * next_g.
-static ghd_status run_layer(const ghd_model_cfg* c, const ghd_layer_weights* w, const ghd_kv* kv,
-                            float* x, int M, int kv_len, const LayerWs& ws, const half_t* next_g,
-                            hipStream_t st)
+static void fill_common(FusedArgs& a, const ghd_model_cfg* c, const Ws& w, int M, int kv_len)
+{
+    a.M = M;
+    a.Mpad = mpad_of(M);
+    a.kv_len = kv_len;
+    a.H = c->H;
+    a.nh = c->nh;
+    a.d = c->d;
+    a.F = c->F;
+    a.V = c->V;
+    a.L = c->L;
+    a.stride_head = (int64_t)c->kv_capacity * c->d;
+    a.stride_tok = c->d;
+    a.eps = c->rms_eps;
+    a.scale_log2e = 1.4426950408889634f / sqrtf((float)c->d);
+    a.sync = w.sync;
+    a.part = w.part;
+    a.o_part = w.o_part;
+    a.ml_part = w.ml_part;
+    a.x = w.x;
+    a.ss = w.ss;
+    a.q16 = w.q16;
+    a.o16 = w.o16;
+    a.a16 = w.a16;
+    a.rope = w.rope;
+    a.mask = w.mask;
+}
+
+static ghd_status check_layer(const ghd_layer_weights* w, const ghd_kv* kv)
+{
+    if (!w->g_attn || !w->Wqkv || !w->Wo || !w->g_ffn || !w->Wgu || !w->Wdown || !kv->k || !kv->v)
+        return GHD_ERR_NULL;
+    if (!aligned16(w->g_attn) || !aligned16(w->Wqkv) || !aligned16(w->Wo) || !aligned16(w->g_ffn) ||
+        !aligned16(w->Wgu) || !aligned16(w->Wdown) || !aligned16(kv->k) || !aligned16(kv->v))
+        return GHD_ERR_ALIGN;
+    return GHD_OK;
+}
+
+static void fill_layer(LayerPtrs& lp, const ghd_layer_weights* w, const ghd_kv* kv)
+{
+    lp.g_attn = (const half_t*)w->g_attn;
+    lp.Wqkv = (const half8*)w->Wqkv;
+    lp.Wo = (const half8*)w->Wo;
+    lp.g_ffn = (const half_t*)w->g_ffn;
+    lp.Wgu = (const half8*)w->Wgu;
+    lp.Wdown = (const half8*)w->Wdown;
+    lp.kc = (half_t*)kv->k;
+    lp.vc = (half_t*)kv->v;
+}
+
+
+// ---- the step as a sequence of single-phase launches ------------------------------
+// Every linear layer is one launch of the persistent GEMM kernel (all compute units,
+// equal contiguous shares of the packed weight stream, fp32 output [M, N]); the
+// element-wise work between them runs in small kernels on cache-resident data.
+static ghd_status step_linear(const Ws& w, const void* Wp, const half_t* x16, int64_t ldx, float* y,
+                              int64_t ldy, int M, int N, int K, int cnt, uint32_t epoch,
+                              hipStream_t st)
+{
+    FusedArgs a = {};
+    a.mode = MODE_LINEAR;
+    a.M = M;
+    a.Mpad = mpad_of(M);
+    a.d = 128;
+    a.sync = w.sync;
+    a.part = w.part;
+    a.lin_W = (const half8*)Wp;
+    a.lin_x = x16;
+    a.lin_y = y;
+    a.lin_N = N;
+    a.lin_K = K;
+    a.lin_f16 = 0;
+    a.lin_cnt = cnt;
+    a.lin_epoch = epoch;
+    a.lin_ldx = ldx;
+    a.lin_ldy = ldy;
+    return timed_fused(a, st);
+}
+
+static ghd_status step_attention(const ghd_model_cfg* c, const Ws& w, const ghd_kv* kv, int M,
+                                 int kv_len, uint32_t epoch, hipStream_t st)
+{
+    FusedArgs a = {};
+    a.mode = MODE_ATTN;
+    a.M = M;
+    a.Mpad = mpad_of(M);
+    a.kv_len = kv_len;
+    a.nh = c->nh;
+    a.d = c->d;
+    a.H = c->H;
+    a.stride_head = (int64_t)c->kv_capacity * c->d;
+    a.stride_tok = c->d;
+    a.scale_log2e = 1.4426950408889634f / sqrtf((float)c->d);
+    a.sync = w.sync;
+    a.o_part = w.o_part;
+    a.ml_part = w.ml_part;
+    a.mask = w.mask;
+    a.att_q = w.q16;
+    a.att_k = (const half_t*)kv->k;
+    a.att_v = (const half_t*)kv->v;
+    a.att_out = w.o16;
+    a.att_epoch = epoch;
+    return timed_fused(a, st);
+}
+
+// One layer with n16 = rmsnorm(x) * g_attn already in w.n16.  On return x holds the
+// layer's output and, if next_g is given, w.n16 = rmsnorm(x) * next_g.
+static ghd_status run_layer(const ghd_model_cfg* c, const ghd_layer_weights* lw, const ghd_kv* kv,
+                            float* x, int M, int kv_len, const Ws& w, const half_t* next_g,
+                            uint32_t layer, hipStream_t st)
 {
     const int H = c->H, F = c->F;
     const int64_t stride_head = (int64_t)c->kv_capacity * c->d, stride_tok = c->d;
     ghd_status s;
     // MHA block: QKV linear, rotate + append, tree attention, output linear
-    GemmPlan p = plan_gemm(M, 3 * H, H);
-    int64_t ld = (int64_t)p.ntiles * 16;
-    if ((s = timed_gemm(p, w->Wqkv, ws.n16, H, ws.part, ld, M, 3 * H, H, st))) return s;
-    if ((s = launch_qkv_epilogue(ws.part, p.S, ld, ws.rope, ws.q16, (half_t*)kv->k, (half_t*)kv->v,
-                                 M, c->nh, c->d, kv_len, stride_head, stride_tok, st)))
+    if ((s = step_linear(w, lw->Wqkv, w.n16, H, w.y32, 3 * H, M, 3 * H, H, kCntQkv, layer, st))) return s;
+    if ((s = launch_qkv_epilogue(w.y32, 1, 3 * H, w.rope, w.q16, (half_t*)kv->k, (half_t*)kv->v, M,
+                                 c->nh, c->d, kv_len, stride_head, stride_tok, st)))
         return s;
-    AttnPlan a = plan_attention(M, kv_len, c->nh);
-    if ((s = launch_attention(a, ws.o16, ws.q16, (const half_t*)kv->k, (const half_t*)kv->v, ws.mask,
-                              M, kv_len, c->nh, c->d, stride_head, stride_tok,
-                              1.0f / sqrtf((float)c->d), ws.o_part, ws.ml_part, st)))
-        return s;
-    p = plan_gemm(M, H, H);
-    ld = (int64_t)p.ntiles * 16;
-    if ((s = timed_gemm(p, w->Wo, ws.o16, H, ws.part, ld, M, H, H, st))) return s;
-    if ((s = launch_residual_norm(x, nullptr, ws.part, p.S, ld, (const half_t*)w->g_ffn, ws.n16, M,
-                                  H, c->rms_eps, st)))
+    if ((s = step_attention(c, w, kv, M, kv_len, layer, st))) return s;
+    if ((s = step_linear(w, lw->Wo, w.o16, H, w.y32, H, M, H, H, kCntWo, layer, st))) return s;
+    if ((s = launch_residual_norm(x, nullptr, w.y32, 1, H, (const half_t*)lw->g_ffn, w.n16, M, H,
+                                  c->rms_eps, st)))
         return s;
     // MLP block: gate|up linear + SwiGLU, down linear
-    p = plan_gemm(M, 2 * F, H);
-    ld = (int64_t)p.ntiles * 16;
-    if ((s = timed_gemm(p, w->Wgu, ws.n16, H, ws.part, ld, M, 2 * F, H, st))) return s;
-    if ((s = launch_swiglu(ws.part, p.S, ld, ws.a16, M, F, st))) return s;
-    p = plan_gemm(M, H, F);
-    ld = (int64_t)p.ntiles * 16;
-    if ((s = timed_gemm(p, w->Wdown, ws.a16, F, ws.part, ld, M, H, F, st))) return s;
-    return launch_residual_norm(x, nullptr, ws.part, p.S, ld, next_g, ws.n16, M, H, c->rms_eps, st);
+    if ((s = step_linear(w, lw->Wgu, w.n16, H, w.y32, 2 * F, M, 2 * F, H, kCntGu, layer, st))) return s;
+    if ((s = launch_swiglu(w.y32, 1, 2 * F, w.a16, M, F, st))) return s;
+    if ((s = step_linear(w, lw->Wdown, w.a16, F, w.y32, H, M, H, F, kCntDown, layer, st))) return s;
+    return launch_residual_norm(x, nullptr, w.y32, 1, H, next_g, w.n16, M, H, c->rms_eps, st);
 }
 
 }  // namespace ghd
@@ -185,32 +289,42 @@ ghd_status ghd_tree_validate(const int32_t* parent_host, int M)
     return GHD_OK;
 }
 
-ghd_status ghd_tree_mask(const int32_t* parent_dev, int M, uint64_t* mask_dev, void* stream)
+size_t ghd_tree_mask_workspace_bytes(void) { return align_up(kSyncWords * sizeof(uint32_t), 256); }
+
+ghd_status ghd_tree_mask(const int32_t* parent_dev, int M, uint64_t* mask_dev, void* ws,
+                         size_t ws_bytes, void* stream)
 {
     if (!parent_dev || !mask_dev) return GHD_ERR_NULL;
     if (M < 1 || M > GHD_MAX_M) return GHD_ERR_SHAPE;
-    return launch_tree_setup(parent_dev, M, 0, 0, 1.f, nullptr, mask_dev, nullptr,
-                             (hipStream_t)stream);
+    if (!ws) return GHD_ERR_WORKSPACE;
+    if (!aligned16(ws)) return GHD_ERR_ALIGN;
+    if (ws_bytes < ghd_tree_mask_workspace_bytes()) return GHD_ERR_WORKSPACE;
+    return launch_fused_setup((uint32_t*)ws, parent_dev, M, mpad_of(M), 0, 0, 1.f, mask_dev, nullptr,
+                              nullptr, nullptr, 0, nullptr, (hipStream_t)stream);
 }
 
 size_t ghd_packed_weight_bytes(int N, int K)
 {
     if (N < 1 || K < 1) return 0;
-    return (size_t)ceil_div(N, 16) * ceil_div(K, 32) * 1024;
+    return packed_bytes2(N, K);
 }
 
-ghd_status ghd_pack_weight(void* dst, const void* src, int N, int K, void* stream)
+ghd_status ghd_pack_weight(void* dst, const void* src, int N, int K, int kind, int head_dim,
+                           void* stream)
 {
     if (!dst || !src) return GHD_ERR_NULL;
-    if (N < 1 || K < 1) return GHD_ERR_SHAPE;
+    if (N < 1 || K < 1 || kind < GHD_PACK_PLAIN || kind > GHD_PACK_GATE_UP) return GHD_ERR_SHAPE;
+    if (kind == GHD_PACK_QKV && ((head_dim != 64 && head_dim != 128) || N % head_dim != 0))
+        return GHD_ERR_SHAPE;
+    if (kind == GHD_PACK_GATE_UP && (N % 16) != 0) return GHD_ERR_SHAPE;
     if (!aligned16(dst)) return GHD_ERR_ALIGN;
-    return launch_pack(dst, src, N, K, (hipStream_t)stream);
+    return launch_pack2(dst, src, N, K, kind, head_dim, (hipStream_t)stream);
 }
 
 size_t ghd_linear_workspace_bytes(int M, int N, int K)
 {
     if (M < 1 || M > GHD_MAX_M || N < 1 || K < 1) return 0;
-    return align_up(gemm_part_floats(M, N, K) * sizeof(float), 256);
+    return carve(nullptr, 1, M, 0, 0, 0).bytes;
 }
 
 ghd_status ghd_linear_skinny(void* y, const void* x, const void* Wp, int M, int N, int K,
@@ -219,27 +333,41 @@ ghd_status ghd_linear_skinny(void* y, const void* x, const void* Wp, int M, int 
 {
     if (!y || !x || !Wp) return GHD_ERR_NULL;
     if (M < 1 || M > GHD_MAX_M || N < 1 || K < 8 || (K % 8) != 0) return GHD_ERR_SHAPE;
-    if (ldx < K || ldy < N || flags > GHD_OUT_F16) return GHD_ERR_SHAPE;
+    if (ldx < K || ldy < N || flags > GHD_OUT_F16 || (int64_t)N > 1024 * kGroupRows)
+        return GHD_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(Wp) || !aligned16(y) || (ldx % 8) != 0) return GHD_ERR_ALIGN;
     if (!ws) return GHD_ERR_WORKSPACE;
     if (!aligned16(ws)) return GHD_ERR_ALIGN;
     if (ws_bytes < ghd_linear_workspace_bytes(M, N, K)) return GHD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    GemmPlan p = plan_gemm(M, N, K);
-    int64_t ld = (int64_t)p.ntiles * 16;
-    ghd_status s = timed_gemm(p, Wp, (const half_t*)x, ldx, (float*)ws, ld, M, N, K, st);
+    Ws w = carve(ws, 1, M, 0, 0, 0);
+    ghd_status s = launch_fused_setup(w.sync, nullptr, M, mpad_of(M), 0, 0, 1.f, nullptr, nullptr,
+                                      nullptr, nullptr, 0, nullptr, st);
     if (s) return s;
-    return launch_reduce_out(y, ldy, flags == GHD_OUT_F16, (const float*)ws, p.S, ld, M, N, st);
+    FusedArgs a = {};
+    a.mode = MODE_LINEAR;
+    a.M = M;
+    a.Mpad = mpad_of(M);
+    a.d = 128;
+    a.sync = w.sync;
+    a.part = w.part;
+    a.lin_W = (const half8*)Wp;
+    a.lin_x = (const half_t*)x;
+    a.lin_y = y;
+    a.lin_N = N;
+    a.lin_K = K;
+    a.lin_f16 = flags == GHD_OUT_F16;
+    a.lin_cnt = kCntLm;
+    a.lin_epoch = 0;
+    a.lin_ldx = ldx;
+    a.lin_ldy = ldy;
+    return timed_fused(a, st);
 }
 
 size_t ghd_attention_workspace_bytes(int M, int kv_len, int nh, int d)
 {
     if (M < 1 || M > GHD_MAX_M || kv_len < 0 || nh < 1 || (d != 64 && d != 128)) return 0;
-    AttnPlan a = plan_attention(M, kv_len, nh);
-    size_t b = align_up(2 * GHD_MAX_M * sizeof(uint64_t), 256);
-    b += align_up((size_t)a.P * nh * M * d * sizeof(float), 256);
-    b += align_up((size_t)a.P * nh * M * 2 * sizeof(float), 256);
-    return b;
+    return carve(nullptr, 2, M, 0, 0, d).bytes;
 }
 
 ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, const void* v_cache,
@@ -248,7 +376,7 @@ ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, con
                               size_t ws_bytes, void* stream)
 {
     if (!out || !q || !k_cache || !v_cache || !parent_dev) return GHD_ERR_NULL;
-    if (M < 1 || M > GHD_MAX_M || kv_len < 0 || nh < 1 || (d != 64 && d != 128))
+    if (M < 1 || M > GHD_MAX_M || kv_len < 0 || nh < 1 || nh > 256 || (d != 64 && d != 128))
         return GHD_ERR_SHAPE;
     if (stride_tok < d || stride_head < 0) return GHD_ERR_SHAPE;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) ||
@@ -258,22 +386,36 @@ ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, con
     if (!aligned16(ws)) return GHD_ERR_ALIGN;
     if (ws_bytes < ghd_attention_workspace_bytes(M, kv_len, nh, d)) return GHD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    AttnPlan a = plan_attention(M, kv_len, nh);
-    Carver cv(ws);
-    uint64_t* mask = cv.take<uint64_t>(2 * GHD_MAX_M);
-    float* o_part = cv.take<float>((size_t)a.P * nh * M * d);
-    float* ml_part = cv.take<float>((size_t)a.P * nh * M * 2);
-    ghd_status s = launch_tree_setup(parent_dev, M, kv_len, d, 1.f, nullptr, mask, nullptr, st);
+    Ws w = carve(ws, 2, M, 0, 0, d);
+    ghd_status s = launch_fused_setup(w.sync, parent_dev, M, mpad_of(M), kv_len, d, 1.f, w.mask,
+                                      nullptr, nullptr, nullptr, 0, nullptr, st);
     if (s) return s;
-    return launch_attention(a, (half_t*)out, (const half_t*)q, (const half_t*)k_cache,
-                            (const half_t*)v_cache, mask, M, kv_len, nh, d, stride_head, stride_tok,
-                            scale, o_part, ml_part, st);
+    FusedArgs a = {};
+    a.mode = MODE_ATTN;
+    a.M = M;
+    a.Mpad = mpad_of(M);
+    a.kv_len = kv_len;
+    a.nh = nh;
+    a.d = d;
+    a.H = nh * d;
+    a.stride_head = stride_head;
+    a.stride_tok = stride_tok;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.sync = w.sync;
+    a.o_part = w.o_part;
+    a.ml_part = w.ml_part;
+    a.mask = w.mask;
+    a.att_q = (const half_t*)q;
+    a.att_k = (const half_t*)k_cache;
+    a.att_v = (const half_t*)v_cache;
+    a.att_out = (half_t*)out;
+    return timed_fused(a, st);
 }
 
 size_t ghd_workspace_bytes(const ghd_model_cfg* cfg, int M, int kv_len)
 {
     if (check_cfg(cfg, M, kv_len) != GHD_OK) return 0;
-    return carve(nullptr, cfg, M, kv_len, true).bytes;
+    return carve(nullptr, 0, M, cfg->H, cfg->F, cfg->d).bytes;
 }
 
 ghd_status ghd_verify_layer(const ghd_model_cfg* cfg, const ghd_layer_weights* w, const ghd_kv* kv,
@@ -281,25 +423,23 @@ ghd_status ghd_verify_layer(const ghd_model_cfg* cfg, const ghd_layer_weights* w
                             size_t ws_bytes, void* stream)
 {
     if (!cfg || !w || !kv || !x || !parent_dev) return GHD_ERR_NULL;
-    if (!w->g_attn || !w->Wqkv || !w->Wo || !w->g_ffn || !w->Wgu || !w->Wdown || !kv->k || !kv->v)
-        return GHD_ERR_NULL;
     ghd_status s = check_cfg(cfg, M, kv_len);
     if (s) return s;
-    if (!aligned16(x) || !aligned16(kv->k) || !aligned16(kv->v) || !aligned16(w->Wqkv) ||
-        !aligned16(w->Wo) || !aligned16(w->Wgu) || !aligned16(w->Wdown))
-        return GHD_ERR_ALIGN;
+    if ((s = check_layer(w, kv))) return s;
+    if (!aligned16(x)) return GHD_ERR_ALIGN;
     if (!ws) return GHD_ERR_WORKSPACE;
     if (!aligned16(ws)) return GHD_ERR_ALIGN;
     if (ws_bytes < ghd_workspace_bytes(cfg, M, kv_len)) return GHD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    LayerWs lw = carve(ws, cfg, M, kv_len, true);
-    if ((s = launch_tree_setup(parent_dev, M, kv_len, cfg->d, cfg->rope_base, lw.depth, lw.mask,
-                               lw.rope, st)))
+    Ws lw = carve(ws, 0, M, cfg->H, cfg->F, cfg->d);
+    if ((s = launch_fused_setup(lw.sync, parent_dev, M, mpad_of(M), kv_len, cfg->d, cfg->rope_base,
+                                lw.mask, lw.rope, nullptr, nullptr, 0, nullptr, st)))
         return s;
+    // the caller's x is the residual stream itself
     if ((s = launch_residual_norm(x, nullptr, nullptr, 0, 0, (const half_t*)w->g_attn, lw.n16, M,
                                   cfg->H, cfg->rms_eps, st)))
         return s;
-    return run_layer(cfg, w, kv, x, M, kv_len, lw, nullptr, st);
+    return run_layer(cfg, w, kv, x, M, kv_len, lw, nullptr, 0, st);
 }
 
 ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* layers_host,
@@ -311,25 +451,19 @@ ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* l
         return GHD_ERR_NULL;
     ghd_status s = check_cfg(cfg, M, kv_len);
     if (s) return s;
-    for (int l = 0; l < cfg->L; ++l) {
-        const ghd_layer_weights* w = layers_host + l;
-        if (!w->g_attn || !w->Wqkv || !w->Wo || !w->g_ffn || !w->Wgu || !w->Wdown ||
-            !kv_host[l].k || !kv_host[l].v)
-            return GHD_ERR_NULL;
-        if (!aligned16(w->Wqkv) || !aligned16(w->Wo) || !aligned16(w->Wgu) ||
-            !aligned16(w->Wdown) || !aligned16(kv_host[l].k) || !aligned16(kv_host[l].v))
-            return GHD_ERR_ALIGN;
-    }
-    if (!aligned16(x_in) || !aligned16(Wlm) || !aligned16(logits) || (x_out && !aligned16(x_out)))
+    for (int l = 0; l < cfg->L; ++l)
+        if ((s = check_layer(layers_host + l, kv_host + l))) return s;
+    if (!aligned16(x_in) || !aligned16(Wlm) || !aligned16(g_final) || !aligned16(logits) ||
+        (x_out && !aligned16(x_out)))
         return GHD_ERR_ALIGN;
     if (!ws) return GHD_ERR_WORKSPACE;
     if (!aligned16(ws)) return GHD_ERR_ALIGN;
     if (ws_bytes < ghd_workspace_bytes(cfg, M, kv_len)) return GHD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    LayerWs lw = carve(ws, cfg, M, kv_len, true);
+    Ws lw = carve(ws, 0, M, cfg->H, cfg->F, cfg->d);
     const int H = cfg->H;
-    if ((s = launch_tree_setup(parent_dev, M, kv_len, cfg->d, cfg->rope_base, lw.depth, lw.mask,
-                               lw.rope, st)))
+    if ((s = launch_fused_setup(lw.sync, parent_dev, M, mpad_of(M), kv_len, cfg->d, cfg->rope_base,
+                                lw.mask, lw.rope, nullptr, nullptr, 0, nullptr, st)))
         return s;
     // x = widen(x_in); n16 = rmsnorm(x) * g_attn of layer 0
     if ((s = launch_residual_norm(lw.x, (const half_t*)x_in, nullptr, 0, 0,
@@ -338,7 +472,8 @@ ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* l
         return s;
     for (int l = 0; l < cfg->L; ++l) {
         const half_t* next_g = (const half_t*)(l + 1 < cfg->L ? layers_host[l + 1].g_attn : g_final);
-        if ((s = run_layer(cfg, layers_host + l, kv_host + l, lw.x, M, kv_len, lw, next_g, st)))
+        if ((s = run_layer(cfg, layers_host + l, kv_host + l, lw.x, M, kv_len, lw, next_g,
+                           (uint32_t)l, st)))
             return s;
     }
     if (x_out) {
@@ -346,11 +481,20 @@ ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* l
                                       hipMemcpyDeviceToDevice, st);
         if (e != hipSuccess) return hip_fail(e);
     }
-    // LM head on the final norm
-    GemmPlan p = plan_gemm(M, cfg->V, H);
-    int64_t ld = (int64_t)p.ntiles * 16;
-    if ((s = timed_gemm(p, Wlm, lw.n16, H, lw.part, ld, M, cfg->V, H, st))) return s;
-    return launch_reduce_out(logits, cfg->V, false, lw.part, p.S, ld, M, cfg->V, st);
+    // LM head on the final norm, straight into the caller's logits
+    return step_linear(lw, Wlm, lw.n16, H, logits, cfg->V, M, cfg->V, H, kCntLm, 0, st);
+}
+
+ghd_status ghd_step_status(const void* ws, int32_t* status_host, void* stream)
+{
+    if (!ws || !status_host) return GHD_ERR_NULL;
+    uint32_t v = 0;
+    hipError_t e = hipMemcpyAsync(&v, (const uint32_t*)ws + kSyncStatus, sizeof(v),
+                                  hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+    *status_host = (int32_t)v;
+    return GHD_OK;
 }
 
 size_t ghd_accept_workspace_bytes(int M)
@@ -372,16 +516,12 @@ ghd_status ghd_accept_greedy(const float* logits, const int32_t* tokens_dev,
                          (hipStream_t)stream);
 }
 
-/* Tuning hooks for sweeps (not part of the documented ABI). */
-void ghd_debug_set_gemm_plan(int nt, int s, int nw, int lds) { set_gemm_override(nt, s, nw, lds); }
-void ghd_debug_set_attn_splits(int p) { set_attn_override(p); }
-
-/* Benchmark support: time the skinny-GEMM launches of ghd_verify_layer/stack with
- * HIP events.  ghd_debug_profile_gemm(1) starts a fresh measurement,
- * ghd_debug_profile_gemm(0) stops it; after synchronising the stream,
- * ghd_debug_profile_read returns the number of launches and their summed
- * duration in milliseconds. */
-void ghd_debug_profile_gemm(int enable)
+/* Benchmark support (not part of the documented ABI): time the persistent-kernel
+ * launches with HIP events.  ghd_debug_profile(1) starts a fresh measurement,
+ * ghd_debug_profile(0) stops it; after synchronising the stream,
+ * ghd_debug_profile_read returns the number of launches and their summed duration
+ * in milliseconds. */
+void ghd_debug_profile(int enable)
 {
     g_prof_on = enable != 0;
     if (enable) g_prof_used = 0;

@@ -1,87 +1,11 @@
-// Small kernels around the skinny GEMMs: tree setup (depth, ancestor masks,
-// rotary table), split-K reduction fused with residual add + RMSNorm, with the
-// rotary embedding + KV append, and with SwiGLU.  The paper (section 2.2.2)
-// leaves these element-wise operations out of its cost model; here they ride
-// on the split-K reduction that the skinny GEMMs need anyway, so none of them
-// costs a pass over HBM of its own.
-#include "common.h"
+// Element-wise kernels between the skinny GEMMs: residual add + RMSNorm, rotary
+// embedding + KV append, SwiGLU.  The paper (section 2.2.2) leaves these
+// operations out of its cost model; they read the fp32 output of the preceding
+// linear layer ([M, N], a few MB that stay in cache) and write the fp16 operand
+// of the next one, so none of them costs a pass over HBM.
+#include "fused.h"
 
 namespace ghd {
-
-// ---- tree setup ------------------------------------------------------------
-// One workgroup.  Thread i < M walks from node i to the root (at most M steps,
-// so a malformed parent[] terminates), collecting depth and the 128-bit
-// ancestor-or-self mask (section 2.3: the tokens a drafted token relates to).
-// The rotary table holds (cos, sin) of (kv_len + depth[i]) * base^(-2j/d),
-// evaluated in double and narrowed once.
-__global__ __launch_bounds__(256) void k_tree_setup(const int32_t* __restrict__ parent, int M,
-                                                    int kv_len, int d, float rope_base,
-                                                    int32_t* __restrict__ depth_out,
-                                                    uint64_t* __restrict__ mask_out,
-                                                    float2* __restrict__ rope)
-{
-    __shared__ int32_t s_parent[GHD_MAX_M];
-    __shared__ int32_t s_depth[GHD_MAX_M];
-    int tid = threadIdx.x;
-    if (tid < M) s_parent[tid] = parent[tid];
-    __syncthreads();
-    if (tid < M) {
-        uint64_t lo = 0, hi = 0;
-        int dep = 0, j = tid;
-        for (int step = 0; step < M; ++step) {
-            if (j < 64) lo |= 1ull << j; else hi |= 1ull << (j - 64);
-            int p = s_parent[j];
-            if (p < 0 || p >= j) break;
-            j = p;
-            ++dep;
-        }
-        s_depth[tid] = dep;
-        if (depth_out) depth_out[tid] = dep;
-        if (mask_out) {
-            mask_out[2 * tid] = lo;
-            mask_out[2 * tid + 1] = hi;
-        }
-    }
-    __syncthreads();
-    if (rope) {
-        int half = d / 2;
-        for (int e = tid; e < M * half; e += blockDim.x) {
-            int m = e / half, j = e % half;
-            double ang = (double)(kv_len + s_depth[m]) * pow((double)rope_base, -2.0 * j / d);
-            rope[e] = make_float2((float)cos(ang), (float)sin(ang));
-        }
-    }
-}
-
-ghd_status launch_tree_setup(const int32_t* parent, int M, int kv_len, int d, float rope_base,
-                             int32_t* depth, uint64_t* mask, float2* rope, hipStream_t st)
-{
-    hipLaunchKernelGGL(k_tree_setup, dim3(1), dim3(256), 0, st, parent, M, kv_len, d, rope_base,
-                       depth, mask, rope);
-    return check_launch();
-}
-
-// ---- plain split-K reduction -------------------------------------------------
-__global__ __launch_bounds__(256) void k_reduce_out(void* __restrict__ y, int64_t ldy, int out_f16,
-                                                    const float* __restrict__ part, int S,
-                                                    int64_t ld, int M, int N)
-{
-    int n = blockIdx.x * blockDim.x + threadIdx.x;
-    int m = blockIdx.y;
-    if (n >= N) return;
-    float acc = 0.f;
-    for (int s = 0; s < S; ++s) acc += part[((size_t)s * M + m) * ld + n];
-    if (out_f16) ((half_t*)y)[(size_t)m * ldy + n] = (half_t)acc;
-    else ((float*)y)[(size_t)m * ldy + n] = acc;
-}
-
-ghd_status launch_reduce_out(void* y, int64_t ldy, bool out_f16, const float* part, int S,
-                             int64_t ld, int M, int N, hipStream_t st)
-{
-    hipLaunchKernelGGL(k_reduce_out, dim3(ceil_div(N, 256), M), dim3(256), 0, st, y, ldy,
-                       (int)out_f16, part, S, ld, M, N);
-    return check_launch();
-}
 
 // ---- residual add + RMSNorm ----------------------------------------------------
 // One workgroup per row.  x_new = (x_old or widen(x_in16)) + sum of the S split
@@ -189,7 +113,7 @@ __global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ part, 
         gt += row[f];
         up += row[F + f];
     }
-    float act = gt / (1.0f + __expf(-gt));
+    float act = gt / (1.0f + expf(-gt));
     a16[(size_t)m * F + f] = (half_t)(act * up);
 }
 

@@ -1,0 +1,102 @@
+// Argument block of the persistent verification kernel (fused.hip).
+#pragma once
+#include "common.h"
+
+namespace ghd {
+
+constexpr int kFT = 512;        // threads per workgroup (8 wavefronts)
+constexpr int kTG = 16;         // 16-row weight tiles per row group (8 wavefronts x 2)
+constexpr int kCH = 4;          // k-steps (32 columns) per staged chunk of x
+constexpr int kGroupRows = kTG * 16;
+constexpr int kChunkCols = kCH * 32;
+constexpr int kMaxLayers = 48;  // per-layer pointers travel as kernel arguments
+
+enum { EPI_STORE_F32 = 0, EPI_STORE_F16 = 1, EPI_RESID = 2, EPI_SWIGLU = 3, EPI_QKV = 4 };
+enum { MODE_STACK = 0, MODE_LAYER = 1, MODE_LINEAR = 2, MODE_ATTN = 3 };
+enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
+
+// counters in the sync block (uint32 words), zeroed by the setup kernel
+constexpr int kSyncBarrier = 0;   // grid-barrier arrivals (monotonic)
+constexpr int kSyncStatus = 1;    // 0 = ok, 1 = a bounded wait gave up
+constexpr int kSyncCnt = 16;      // first group counter
+constexpr int kCntQkv = kSyncCnt;           // up to 512 row groups each
+constexpr int kCntWo = kCntQkv + 512;
+constexpr int kCntGu = kCntWo + 512;
+constexpr int kCntDown = kCntGu + 512;
+constexpr int kCntLm = kCntDown + 512;
+constexpr int kCntAttn = kCntLm + 1024;
+constexpr int kSyncWords = kCntAttn + 256;
+
+struct LayerPtrs {
+    const half_t* g_attn;
+    const half8* Wqkv;
+    const half8* Wo;
+    const half_t* g_ffn;
+    const half8* Wgu;
+    const half8* Wdown;
+    half_t* kc;
+    half_t* vc;
+};
+
+struct FusedArgs {
+    int mode;
+    int M, Mpad, kv_len;
+    int H, nh, d, F, V, L;
+    int64_t stride_head, stride_tok;
+    float eps, scale_log2e;
+    // scratch (device)
+    uint32_t* sync;        // kSyncWords
+    float* part;           // GEMM partial slots: [G][2][16*MT KiB]
+    float* o_part;         // attention partial slots: [G][2][2][Mpad][d]
+    float* ml_part;        // [G][2][2][Mpad][2]
+    float* x;              // residual stream [M, H] fp32
+    float* ss;             // sums of squares per 16-column tile: [H/16][Mpad]
+    half_t* q16;           // [M, H]
+    half_t* o16;           // [M, H]
+    half_t* a16;           // [M, F]
+    const float2* rope;    // (cos, sin) [M][d/2]
+    const uint64_t* mask;  // ancestor masks [M][2]
+    // model tail
+    const half_t* g_final;
+    const half8* Wlm;
+    float* logits;         // [M, V]
+    // single-op modes
+    const half8* lin_W;
+    const half_t* lin_x;
+    void* lin_y;
+    int lin_N, lin_K, lin_f16;
+    int lin_cnt;           // which group-counter array of the sync block this call uses
+    uint32_t lin_epoch;    // how often that array was used since it was zeroed
+    uint32_t att_epoch;    // same for the attention head counters
+    int64_t lin_ldx, lin_ldy;
+    const half_t *att_q, *att_k, *att_v;
+    half_t* att_out;
+    LayerPtrs layer[kMaxLayers];
+};
+
+ghd_status launch_fused(const FusedArgs& a, hipStream_t st);
+int fused_grid_size();
+
+// setup kernel: zero the sync block, tree tables, and (optionally) the residual stream
+// with its sums of squares
+ghd_status launch_fused_setup(uint32_t* sync, const int32_t* parent, int M, int Mpad, int kv_len, int d,
+                              float rope_base, uint64_t* mask, float2* rope, float* x,
+                              const half_t* x_in16, int H, float* ss, hipStream_t st);
+
+// element-wise kernels (elementwise.hip)
+// x_new = (x_old | widen(x_in16)) + y32 (if given);  n16 = fp16(rmsnorm(x_new) * g) (if g)
+ghd_status launch_residual_norm(float* x, const half_t* x_in16, const float* part, int S, int64_t ld,
+                                const half_t* g, half_t* n16, int M, int H, float eps,
+                                hipStream_t st);
+// rotate q and k of the fused QKV output, write q16 [M,H] and cache rows kv_len+m
+ghd_status launch_qkv_epilogue(const float* part, int S, int64_t ld, const float2* rope, half_t* q16,
+                               half_t* kc, half_t* vc, int M, int nh, int d, int kv_len,
+                               int64_t stride_head, int64_t stride_tok, hipStream_t st);
+// a16[m,f] = fp16(silu(gate) * up) from the [M, 2F] output of the gate|up linear
+ghd_status launch_swiglu(const float* part, int S, int64_t ld, half_t* a16, int M, int F,
+                         hipStream_t st);
+
+ghd_status launch_pack2(void* dst, const void* src, int N, int K, int kind, int d, hipStream_t st);
+size_t packed_bytes2(int N, int K);
+
+}  // namespace ghd

@@ -1,0 +1,999 @@
+// The verification step as ONE persistent kernel.
+//
+// Why: the step is a chain of short, strictly dependent, bandwidth-bound
+// operations (Ghidorah, section 2.1: every decoding step re-reads all weights;
+// section 2.2.2: per layer QKV linear, attention, output linear, two MLP
+// linears).  At HBM speed one 7B layer lasts about 60 us, so launch gaps and
+// drain/refill at every dependency would cost as much as the streaming itself.
+// Here one workgroup per compute unit stays resident for the whole step; the
+// operations are phases separated by grid-wide barriers, and before waiting at a
+// barrier every wavefront already has the first weight blocks of the next phase
+// in flight (weights do not depend on activations).
+//
+// Skinny linear layers.  W is packed in row groups of 256 output features
+// (16 tiles of 16 rows), inside a group k-step major: one k-step of a group is
+// 16 KiB, tile t of it is the 1 KiB A operand of v_mfma_f32_16x16x32_f16.  The
+// chunks (4 k-steps of one group) of a matrix form one linear sequence that is
+// cut into equal contiguous ranges, one per workgroup, whatever the shape
+// (no tile quantisation).  Wavefront w owns tiles 2w, 2w+1 of the group; x is
+// staged through LDS in B-operand order, double buffered, shared by all eight
+// wavefronts.  A group whose K range is split over several workgroups is
+// finished cooperatively: every part stores its fp32 partial tile sums, bumps
+// the group's counter, waits (bounded) for the other parts, then reduces and
+// post-processes its own share of the group's fragments in a fixed order, so
+// results do not depend on timing.  The post-processing is the layer's
+// element-wise work: residual add + sums of squares for the next RMSNorm,
+// rotary embedding + KV append, SwiGLU.  RMSNorm itself is applied while x is
+// staged (x * rsqrt(mean x^2 + eps) * g, rounded to fp16).
+//
+// Tree attention.  The (head, 64-key tile) pairs form the same kind of linear
+// sequence.  A workgroup streams its tiles through LDS; wavefronts 0-3 take the
+// first 32 keys of a tile, 4-7 the last 32, each for its own 16 (or 32) query
+// rows.  S^T = K q^T puts one query row in each lane column, so softmax
+// statistics are per-lane scalars, the fp16 probabilities are already in
+// B-operand layout for O^T += V^T P^T, and the ancestor mask (section 2.3) is a
+// 128-bit register per lane.  Sub-tiles no row can see are skipped.  Parts of a
+// head are merged with the online-softmax rescale of section 3.2.2.
+#include "fused.h"
+
+namespace ghd {
+
+constexpr int kFrag = 4 * 272;              // LDS bytes of one padded 16x32 B fragment
+constexpr long long kWaitTicks = 2000000;   // bounded waits give up after 20 ms (100 MHz clock)
+
+struct GemmOp {
+    const half8* W;
+    int N, K;            // logical output features (packed order) and input features
+    int ngroups, ncpg;   // row groups, chunks per group
+    int epi;
+    const half_t* in16;  // fp16 input [M, ld_in]   (gain == nullptr)
+    int64_t ld_in;
+    const float* in32;   // fp32 input [M, K] to be RMS-normalised (gain != nullptr)
+    const half_t* gain;
+    void* out;           // STORE: y;  RESID: x;  SWIGLU: a16
+    int64_t ldo;
+    half_t *kc, *vc;     // QKV: this layer's cache
+    uint32_t* cnt;       // the operation's group counters
+    uint32_t epoch;      // how many times these counters were used before (layer index)
+};
+
+struct Ctx {
+    int j, G;            // logical workgroup index, number of workgroups
+    uint32_t nbar;       // barriers passed so far
+    char* lds;           // dynamic LDS: phase buffers, then one status word at lds_bytes - 16
+    uint32_t* s_status;  // LDS word used to hand a decision of thread 0 to the workgroup
+};
+
+__device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Partial results cross workgroups (and XCDs, whose L2 caches are not coherent with one
+// another) through device-scope relaxed atomic accesses: such a store is written through
+// to memory and such a load is served from memory, access by access.  The alternative, a
+// device-scope fence, writes back and invalidates a whole L2 (about 4 us each here, and
+// every other workgroup of that XCD loses its cached operands).  Order is kept by the
+// pipeline: a wavefront's stores have been acknowledged when it passes __syncthreads(),
+// and only then does thread 0 bump the counter the readers poll.
+__device__ __forceinline__ void st_coherent(float* p, floatx4 v)
+{
+    union { floatx4 f; unsigned long long u[2]; } c;
+    c.f = v;
+    __hip_atomic_store((unsigned long long*)p, c.u[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store((unsigned long long*)p + 1, c.u[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Reading side.  A slot is written once and read once per launch, after the counter says
+// it is complete; caches are invalidated when a kernel starts, so no cache of the reading
+// XCD can hold an older copy of the line and a plain (pipelined) load fetches it from
+// memory, or from the L2 it shares with the writer.  (A kernel that reused slots within
+// one launch would have to read them with device-scope loads instead.)
+__device__ __forceinline__ floatx4 ld_exchange(const float* p) { return *(const floatx4*)p; }
+__device__ __forceinline__ float ld_exchange1(const float* p) { return *p; }
+__device__ __forceinline__ void st_coherent1(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Waits until *p >= target.  Gives up (and raises the status word to `code`) after
+// kWaitTicks of wall-clock time, or as soon as another workgroup has given up, so that a
+// grid that is not fully resident ends with an error instead of hanging.  One thread calls.
+__device__ __forceinline__ void bounded_wait(uint32_t* sync, const uint32_t* p, uint32_t target,
+                                             uint32_t code)
+{
+    if (ld_relaxed(p) >= target) return;
+    const long long t0 = wall_clock64();
+    while (ld_relaxed(p) < target) {
+        if (wall_clock64() - t0 > kWaitTicks || ld_relaxed(sync + kSyncStatus) != 0) {
+            atomicCAS(sync + kSyncStatus, 0u, code);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+    }
+}
+
+// Grid-wide barrier.  All of this workgroup's stores have reached L2 once its threads
+// pass the first __syncthreads(); thread 0 then publishes them device-wide (release
+// fence: the cache write-back acts on the whole L2, so one thread does it for all),
+// counts the arrival, waits (bounded) for all G workgroups, and makes the other
+// workgroups' stores visible (acquire fence: invalidates this compute unit's view) before
+// the second __syncthreads() lets the rest of the workgroup go on.  Returns false (to
+// every thread alike) once any wait in the grid has given up, so the grid winds down.
+__device__ __forceinline__ bool grid_barrier(const FusedArgs& a, Ctx& cx)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        atomicAdd(a.sync + kSyncBarrier, 1u);
+        bounded_wait(a.sync, a.sync + kSyncBarrier, (uint32_t)cx.G * (cx.nbar + 1), 100u + cx.nbar);
+        __threadfence();
+        *cx.s_status = ld_relaxed(a.sync + kSyncStatus);
+    }
+    cx.nbar += 1;
+    __syncthreads();
+    return *cx.s_status == 0;
+}
+
+__device__ inline long chunk_begin(long U, int j, int G) { return U * j / G; }
+__device__ inline int chunk_owner(long U, long x, int G) { return (int)(((x + 1) * G - 1) / U); }
+
+// ---------------------------------------------------------------------------
+// epilogue of one 16x16 output fragment: lane (c, g4) holds y[m][n0 .. n0+3]
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, floatx4 v, int m, int n0,
+                                int lane)
+{
+    const bool mok = m < a.M;
+    if (op.epi == EPI_STORE_F32) {
+        if (!mok) return;
+        float* o = (float*)op.out + (size_t)m * op.ldo + n0;
+        if (n0 + 3 < op.N && (op.ldo & 3) == 0) *(floatx4*)o = v;
+        else
+            for (int r = 0; r < 4; ++r)
+                if (n0 + r < op.N) o[r] = v[r];
+    } else if (op.epi == EPI_STORE_F16) {
+        if (!mok) return;
+        half_t* o = (half_t*)op.out + (size_t)m * op.ldo + n0;
+        for (int r = 0; r < 4; ++r)
+            if (n0 + r < op.N) o[r] = (half_t)v[r];
+    } else if (op.epi == EPI_RESID) {
+        // x += y; sums of squares of the new x over this tile's 16 columns, per row
+        float s = 0.f;
+        if (mok && n0 < op.N) {
+            floatx4* xp = (floatx4*)((float*)op.out + (size_t)m * op.ldo + n0);
+            floatx4 xn = *xp + v;
+            *xp = xn;
+            s = xn[0] * xn[0] + xn[1] * xn[1] + xn[2] * xn[2] + xn[3] * xn[3];
+        }
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if (lane < 16 && n0 < op.N) a.ss[(size_t)(n0 >> 4) * a.Mpad + m] = s;
+    } else if (op.epi == EPI_SWIGLU) {
+        // packed rows: (gate f, gate f+1, up f, up f+1)
+        if (!mok) return;
+        int f = (n0 >> 4) * 8 + ((n0 & 15) >> 2) * 2;
+        if (f >= a.F) return;
+        float a0 = v[0] / (1.0f + expf(-v[0])) * v[2];
+        float a1 = v[1] / (1.0f + expf(-v[1])) * v[3];
+        half2_ h = {(half_t)a0, (half_t)a1};
+        *(half2_*)((half_t*)op.out + (size_t)m * op.ldo + f) = h;
+    } else {   // EPI_QKV: packed rows of a head: (j, j+1, j+d/2, j+1+d/2)
+        if (!mok || n0 >= op.N) return;
+        const int H = a.H, d = a.d, hd = a.d >> 1;
+        int part = n0 / H, hn = n0 - part * H;
+        int head = hn / d, ph = hn - head * d;
+        int jj = (ph >> 2) * 2;
+        float o0 = v[0], o1 = v[1], o2 = v[2], o3 = v[3];
+        if (part < 2) {
+            float2 cs0 = a.rope[(size_t)m * hd + jj], cs1 = a.rope[(size_t)m * hd + jj + 1];
+            o0 = v[0] * cs0.x - v[2] * cs0.y;
+            o2 = v[2] * cs0.x + v[0] * cs0.y;
+            o1 = v[1] * cs1.x - v[3] * cs1.y;
+            o3 = v[3] * cs1.x + v[1] * cs1.y;
+        }
+        half_t* dst;
+        if (part == 0) dst = a.q16 + (size_t)m * H + head * d + jj;
+        else {
+            half_t* base = (part == 1) ? op.kc : op.vc;
+            dst = base + (size_t)head * a.stride_head + (size_t)(a.kv_len + m) * a.stride_tok + jj;
+        }
+        half2_ lo = {(half_t)o0, (half_t)o1}, hi = {(half_t)o2, (half_t)o3};
+        *(half2_*)dst = lo;
+        *(half2_*)(dst + hd) = hi;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// one skinny linear layer
+// ---------------------------------------------------------------------------
+template <int MT>
+__device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op, Ctx& cx, bool barrier_first)
+{
+    constexpr int CHUNK = kCH * MT * kFrag;        // LDS bytes of one staged x chunk
+    constexpr int PIECES = kCH * MT * 64;          // 16-byte pieces per chunk
+    constexpr int PPT = (PIECES + kFT - 1) / kFT;
+    constexpr int NF = kTG * MT;                   // fragments of one row group
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c = lane & 15, g4 = lane >> 4;
+    char* xs = cx.lds;                             // 2 * CHUNK
+    float* s_rinv = (float*)(cx.lds + 2 * CHUNK);  // Mpad floats
+    float* s_tmp = s_rinv + 128;                   // 512 floats
+
+    // U chunks are dealt to the first Ge workgroups in equal contiguous ranges (every one
+    // of them non-empty); with fewer chunks than workgroups the rest have nothing to do.
+    const long U = (long)op.ngroups * op.ncpg;
+    const int Ge = (int)(U < (long)cx.G ? U : (long)cx.G);
+    const bool has_work = cx.j < Ge;
+    const long c0 = has_work ? chunk_begin(U, cx.j, Ge) : 0, c1 = has_work ? chunk_begin(U, cx.j + 1, Ge) : 0;
+    const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    // ---- weight stream: linear in the chunk index
+    const half8* wbase = op.W + (size_t)(wave * 2) * 64 + lane;
+    half8 wb[kCH][2];
+    auto w_fetch = [&](int s, long cu) {
+        if (cu < c1) {
+            const half8* p = wbase + ((size_t)cu * kCH + s) * (kTG * 64);
+            wb[s][0] = p[0];
+            wb[s][1] = p[64];
+        } else {
+            wb[s][0] = zero8;
+            wb[s][1] = zero8;
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < kCH; ++s) w_fetch(s, c0);
+
+    if (barrier_first && !grid_barrier(a, cx)) return false;
+
+    // ---- RMSNorm scale per row from the per-tile sums of squares
+    if (op.gain) {
+        const int n_ss = op.K >> 4;
+        const int tpr = kFT / a.Mpad;              // threads per row
+        int m = tid % a.Mpad, part = tid / a.Mpad;
+        float s = 0.f;
+        for (int t = part; t < n_ss; t += tpr) s += a.ss[(size_t)t * a.Mpad + m];
+        s_tmp[tid] = s;
+        __syncthreads();
+        if (tid < a.Mpad) {
+            float tot = 0.f;
+            for (int p = 0; p < tpr; ++p) tot += s_tmp[p * a.Mpad + tid];
+            s_rinv[tid] = 1.0f / sqrtf(tot / (float)op.K + a.eps);
+        }
+        __syncthreads();
+    }
+
+    // ---- x staging: piece p -> fragment f = p/64 (k-step s = f/MT, row tile f%MT),
+    //      row (p/4)%16, k group p%4
+    int p_row[PPT], p_koff[PPT], p_dst[PPT];
+    bool p_ok[PPT];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) {
+        int p = tid + i * kFT;
+        int f = p >> 6, pc = (p >> 2) & 15, pg = p & 3;
+        int s = f / MT, mt = f % MT;
+        int m = mt * 16 + pc;
+        p_ok[i] = (p < PIECES) && (m < a.M);
+        p_row[i] = min(m, a.M - 1);
+        p_koff[i] = s * 32 + pg * 8;
+        p_dst[i] = f * kFrag + pg * 272 + pc * 16;
+    }
+    half8 xr[PPT];
+    auto x_fetch = [&](long cu) {
+        int kbase = (int)(cu % op.ncpg) * kChunkCols;
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            int k = kbase + p_koff[i];
+            bool ok = p_ok[i] && k < op.K && cu < c1;
+            half8 v = zero8;
+            if (ok) {
+                if (op.gain) {
+                    const float* src = op.in32 + (size_t)p_row[i] * op.K + k;
+                    floatx4 lo = *(const floatx4*)src, hi = *(const floatx4*)(src + 4);
+                    half8 gv = *(const half8*)(op.gain + k);
+                    float r = s_rinv[p_row[i]];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = (half_t)(lo[e] * r * (float)gv[e]);
+                        v[e + 4] = (half_t)(hi[e] * r * (float)gv[e + 4]);
+                    }
+                } else {
+                    v = *(const half8*)(op.in16 + (size_t)p_row[i] * op.ld_in + k);
+                }
+            }
+            xr[i] = v;
+        }
+    };
+    auto x_store = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < PPT; ++i)
+            if (tid + i * kFT < PIECES) *(half8*)(xs + buf * CHUNK + p_dst[i]) = xr[i];
+    };
+
+    floatx4 acc[2][MT];
+    auto acc_zero = [&]() {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int b = 0; b < MT; ++b) acc[t][b] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    };
+    acc_zero();
+
+    // A group's parts: workgroups first..last own pieces of its K range.
+    auto group_first = [&](int grp) { return chunk_owner(U, (long)grp * op.ncpg, Ge); };
+    auto group_last = [&](int grp) { return chunk_owner(U, (long)(grp + 1) * op.ncpg - 1, Ge); };
+    auto slot_of = [&](int wg, int grp) -> float* {
+        int gf = (int)(chunk_begin(U, wg, Ge) / op.ncpg);
+        return a.part + ((size_t)wg * 2 + (grp == gf ? 0 : 1)) * (size_t)(NF * 256);
+    };
+
+    // Ends the accumulation of row group `grp`: direct epilogue when this workgroup
+    // owns the whole K range, otherwise store the partial and signal.
+    auto flush = [&](int grp) {
+        int first = group_first(grp), last = group_last(grp);
+        if (first == last) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int b = 0; b < MT; ++b)
+                    epilogue(a, op, acc[t][b], b * 16 + c, (grp * kTG + wave * 2 + t) * 16 + g4 * 4,
+                             lane);
+        } else {
+            float* slot = slot_of(cx.j, grp);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int b = 0; b < MT; ++b)
+                    st_coherent(slot + ((size_t)((wave * 2 + t) * MT + b) * 64 + lane) * 4, acc[t][b]);
+            __syncthreads();            // every wavefront's partial has been acknowledged
+            if (tid == 0) atomicAdd(op.cnt + grp, 1u);
+        }
+        acc_zero();
+    };
+
+    if (c0 < c1) {
+        x_fetch(c0);
+        x_store(0);
+        x_fetch(c0 + 1);
+        __syncthreads();
+        int cur = (int)(c0 / op.ncpg);
+        for (long cu = c0; cu < c1; ++cu) {
+            int grp = (int)(cu / op.ncpg);
+            if (grp != cur) {
+                flush(cur);
+                cur = grp;
+            }
+            const char* xb = xs + (int)((cu - c0) & 1) * CHUNK + g4 * 272 + c * 16;
+#pragma unroll
+            for (int s = 0; s < kCH; ++s) {
+                half8 xf[MT];
+#pragma unroll
+                for (int b = 0; b < MT; ++b) xf[b] = *(const half8*)(xb + (s * MT + b) * kFrag);
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int b = 0; b < MT; ++b)
+                        acc[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wb[s][t], xf[b], acc[t][b],
+                                                                          0, 0, 0);
+                w_fetch(s, cu + 1);
+            }
+            if (cu + 1 < c1) {
+                x_store((int)((cu + 1 - c0) & 1));
+                x_fetch(cu + 2);
+            }
+            __syncthreads();
+        }
+        flush(cur);
+
+        // ---- cooperative finish of the split groups this workgroup took part in
+        int gfirst = (int)(c0 / op.ncpg), glast = (int)((c1 - 1) / op.ncpg);
+        for (int grp = gfirst; grp <= glast; ++grp) {
+            int first = group_first(grp), last = group_last(grp);
+            if (first == last) continue;
+            int np = last - first + 1, me = cx.j - first;
+            if (tid == 0) bounded_wait(a.sync, op.cnt + grp, (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
+            __syncthreads();
+            int f0 = NF * me / np, f1 = NF * (me + 1) / np;
+            for (int f = f0 + wave; f < f1; f += 8) {
+                floatx4 v = {0.f, 0.f, 0.f, 0.f};
+                for (int p = 0; p < np; ++p)
+                    v += ld_exchange(slot_of(first + p, grp) + ((size_t)f * 64 + lane) * 4);
+                int tile = f / MT, b = f % MT;
+                epilogue(a, op, v, b * 16 + c, (grp * kTG + tile) * 16 + g4 * 4, lane);
+            }
+        }
+    }
+    return true;
+}
+
+// ---------------------------------------------------------------------------
+// tree attention
+// ---------------------------------------------------------------------------
+template <int D>
+struct AttnLds {
+    static constexpr int KS = D + 8;    // halves per K row (padded)
+    static constexpr int VS = 64 + 4;   // halves per V^T row (padded)
+    half_t k[64 * KS];
+    half_t vt[D * VS];
+};
+
+template <int MT, int D>
+__device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const half_t* q, const half_t* kc,
+                           const half_t* vc, half_t* out, uint32_t epoch, bool barrier_first)
+{
+    constexpr int MTW = (MT + 3) / 4;   // 16-row tiles per wavefront
+    constexpr int DS = D / 32, DT = D / 16, CPR = D / 8;
+    constexpr int NLD = 64 * CPR / kFT; // 16-byte chunks per thread per tile
+    using L = AttnLds<D>;
+    L& sm = *reinterpret_cast<L*>(cx.lds);
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c = lane & 15, g4 = lane >> 4;
+    const int kh = wave >> 2, wq = wave & 3;   // key half of the tile, row-tile slot
+    const int M = a.M, nh = a.nh, T = a.kv_len + a.M;
+    const int ntile = (T + 63) >> 6;
+    const long U = (long)nh * ntile;
+    const int Ge = (int)(U < (long)cx.G ? U : (long)cx.G);
+    const bool has_work = cx.j < Ge;
+    const long u0 = has_work ? chunk_begin(U, cx.j, Ge) : 0, u1 = has_work ? chunk_begin(U, cx.j + 1, Ge) : 0;
+
+    half8 kreg[NLD], vreg[NLD];
+    auto load_tile = [&](long u, bool committed_only) {
+        int head = (int)(u / ntile), tile = (int)(u % ntile);
+        const half_t* kh_ = kc + (size_t)head * a.stride_head;
+        const half_t* vh_ = vc + (size_t)head * a.stride_head;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            int id = tid + kFT * i;
+            int row = id / CPR, ch = id % CPR;
+            int key = min(tile * 64 + row, committed_only ? a.kv_len - 1 : T - 1);
+            kreg[i] = *(const half8*)(kh_ + (size_t)key * a.stride_tok + ch * 8);
+            vreg[i] = *(const half8*)(vh_ + (size_t)key * a.stride_tok + ch * 8);
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            int id = tid + kFT * i;
+            int row = id / CPR, ch = id % CPR;
+            *(half8*)(&sm.k[row * L::KS + ch * 8]) = kreg[i];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sm.vt[(ch * 8 + e) * L::VS + row] = vreg[i][e];
+        }
+    };
+
+    // The first tile can be requested before the barrier when it lies entirely in the
+    // committed cache (those rows do not depend on this step).
+    bool prefetched = false;
+    if (u0 < u1 && barrier_first) {
+        int tile = (int)(u0 % ntile);
+        if (tile * 64 + 64 <= a.kv_len) {
+            load_tile(u0, true);
+            prefetched = true;
+        }
+    }
+    if (barrier_first && !grid_barrier(a, cx)) return false;
+    if (u0 >= u1) return true;
+
+    // per-wave query rows
+    int mrow[MTW];
+    bool mok[MTW];
+    uint64_t alo[MTW], ahi[MTW];
+    bool wave_active = false;
+#pragma unroll
+    for (int t = 0; t < MTW; ++t) {
+        int mt = wq * MTW + t;
+        mrow[t] = mt * 16 + c;
+        mok[t] = mrow[t] < M;
+        wave_active = wave_active || (mt * 16 < M);
+        alo[t] = mok[t] ? a.mask[2 * mrow[t]] : 0;
+        ahi[t] = mok[t] ? a.mask[2 * mrow[t] + 1] : 0;
+    }
+    half8 qf[MTW][DS];
+    float mrun[MTW], lrun[MTW];
+    floatx4 oacc[MTW][DT];
+    auto head_begin = [&](int head) {
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (mok[t]) v = *(const half8*)(q + ((size_t)mrow[t] * nh + head) * D + s * 32 + g4 * 8);
+                qf[t][s] = v;
+            }
+            mrun[t] = -INFINITY;
+            lrun[t] = 0.f;
+#pragma unroll
+            for (int e = 0; e < DT; ++e) oacc[t][e] = (floatx4){0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    // parts of a head: workgroups first..last, two key halves each
+    auto head_first = [&](int head) { return chunk_owner(U, (long)head * ntile, Ge); };
+    auto head_last = [&](int head) { return chunk_owner(U, (long)(head + 1) * ntile - 1, Ge); };
+    auto slot_index = [&](int wg, int head, int half) -> size_t {
+        int hf = (int)(chunk_begin(U, wg, Ge) / ntile);
+        return ((size_t)wg * 2 + (head == hf ? 0 : 1)) * 2 + half;
+    };
+    auto head_flush = [&](int head) {
+        if (!wave_active) return;
+        size_t slot = slot_index(cx.j, head, kh);
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+            float l = lrun[t];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            if (!mok[t]) continue;
+            size_t row = slot * a.Mpad + mrow[t];
+#pragma unroll
+            for (int e = 0; e < DT; ++e)
+                st_coherent(a.o_part + row * D + e * 16 + g4 * 4, oacc[t][e]);
+            if (g4 == 0) {
+                st_coherent1(a.ml_part + row * 2, mrun[t]);
+                st_coherent1(a.ml_part + row * 2 + 1, l);
+            }
+        }
+    };
+
+    if (!prefetched) load_tile(u0, false);
+    int cur = (int)(u0 / ntile);
+    head_begin(cur);
+    for (long u = u0; u < u1; ++u) {
+        int head = (int)(u / ntile), tile = (int)(u % ntile);
+        __syncthreads();            // previous tile fully consumed
+        store_tile();
+        __syncthreads();
+        if (u + 1 < u1) load_tile(u + 1, false);
+        if (head != cur) {
+            head_flush(cur);
+            cur = head;
+            head_begin(cur);
+        }
+        if (!wave_active) continue;
+        const int key0 = tile * 64 + kh * 32;    // this wavefront's 32 keys
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+            floatx4 s[2];
+            bool sub_any[2];
+#pragma unroll
+            for (int jx = 0; jx < 2; ++jx) {
+                const int kbase = key0 + jx * 16;
+                bool vis_any;
+                if (kbase + 16 <= a.kv_len) {
+                    vis_any = true;
+                } else {
+                    bool mine = false;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        int key = kbase + g4 * 4 + r;
+                        bool vis = key < a.kv_len;
+                        if (key >= a.kv_len && key < T) {
+                            int jn = key - a.kv_len;
+                            vis = (jn < 64 ? (alo[t] >> jn) : (ahi[t] >> (jn - 64))) & 1ull;
+                        }
+                        mine = mine || (vis && mok[t]);
+                    }
+                    vis_any = __ballot(mine) != 0ull;
+                }
+                sub_any[jx] = vis_any;
+                s[jx] = (floatx4){0.f, 0.f, 0.f, 0.f};
+                if (vis_any) {
+#pragma unroll
+                    for (int ds = 0; ds < DS; ++ds) {
+                        half8 kf = *(const half8*)(&sm.k[(kh * 32 + jx * 16 + c) * L::KS + ds * 32 + g4 * 8]);
+                        s[jx] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[t][ds], s[jx], 0, 0, 0);
+                    }
+                }
+            }
+            if (!(sub_any[0] || sub_any[1])) continue;
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int jx = 0; jx < 2; ++jx) {
+                const int kbase = key0 + jx * 16;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    int key = kbase + g4 * 4 + r;
+                    bool vis = sub_any[jx] && key < a.kv_len;
+                    if (sub_any[jx] && key >= a.kv_len && key < T) {
+                        int jn = key - a.kv_len;
+                        vis = (jn < 64 ? (alo[t] >> jn) : (ahi[t] >> (jn - 64))) & 1ull;
+                    }
+                    float v = vis ? s[jx][r] * a.scale_log2e : -INFINITY;
+                    s[jx][r] = v;
+                    tmax = fmaxf(tmax, v);
+                }
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            float mnew = fmaxf(mrun[t], tmax);
+            float muse = (mnew == -INFINITY) ? 0.f : mnew;
+            float alpha = exp2f(mrun[t] - muse);
+            mrun[t] = mnew;
+            float lsum = 0.f;
+            half8 pf;
+#pragma unroll
+            for (int jx = 0; jx < 2; ++jx)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float pv = exp2f(s[jx][r] - muse);
+                    lsum += pv;
+                    pf[jx * 4 + r] = (half_t)pv;
+                }
+            lrun[t] = lrun[t] * alpha + lsum;
+#pragma unroll
+            for (int e = 0; e < DT; ++e) {
+                oacc[t][e] *= alpha;
+                const half_t* vrow = &sm.vt[(e * 16 + c) * L::VS + kh * 32];
+                half4 a0 = *(const half4*)(vrow + g4 * 4);
+                half4 a1 = *(const half4*)(vrow + 16 + g4 * 4);
+                half8 vf = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                oacc[t][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pf, oacc[t][e], 0, 0, 0);
+            }
+        }
+    }
+    head_flush(cur);
+    __syncthreads();
+    int hfirst = (int)(u0 / ntile), hlast = (int)((u1 - 1) / ntile);
+    if (tid == 0)
+        for (int head = hfirst; head <= hlast; ++head) atomicAdd(a.sync + kCntAttn + head, 1u);
+
+    // ---- merge: every workgroup of a head combines its share of the rows
+    for (int head = hfirst; head <= hlast; ++head) {
+        int first = head_first(head), last = head_last(head);
+        int np = last - first + 1, me = cx.j - first;
+        if (tid == 0) bounded_wait(a.sync, a.sync + kCntAttn + head, (uint32_t)np * (epoch + 1), 2000u);
+        __syncthreads();
+        int r0 = M * me / np, r1 = M * (me + 1) / np;
+        for (int m = r0 + wave; m < r1; m += 8) {
+            float mx = -INFINITY;
+            for (int p = 0; p < np; ++p)
+                for (int hf = 0; hf < 2; ++hf)
+                    mx = fmaxf(mx, ld_exchange1(a.ml_part + (slot_index(first + p, head, hf) * a.Mpad + m) * 2));
+            float num[D / 64], den = 0.f;
+#pragma unroll
+            for (int e = 0; e < D / 64; ++e) num[e] = 0.f;
+            for (int p = 0; p < np; ++p)
+                for (int hf = 0; hf < 2; ++hf) {
+                    size_t row = slot_index(first + p, head, hf) * a.Mpad + m;
+                    float mp = ld_exchange1(a.ml_part + row * 2);
+                    float w = (mp == -INFINITY) ? 0.f : exp2f(mp - mx);
+                    den += w * ld_exchange1(a.ml_part + row * 2 + 1);
+#pragma unroll
+                    for (int e = 0; e < D / 64; ++e)
+                        num[e] += w * ld_exchange1(a.o_part + row * D + e * 64 + lane);
+                }
+#pragma unroll
+            for (int e = 0; e < D / 64; ++e)
+                out[((size_t)m * nh + head) * D + e * 64 + lane] = (half_t)(num[e] / den);
+        }
+    }
+    return true;
+}
+
+// ---------------------------------------------------------------------------
+// the kernel
+// ---------------------------------------------------------------------------
+template <int MT, int D, int MODE>
+__global__ __launch_bounds__(kFT) void k_fused(const FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    Ctx cx;
+    // Workgroups are dealt round-robin to the 8 XCDs; give neighbours in the work
+    // sequence (which share row groups and exchange partial sums) the same XCD.
+    const int G = gridDim.x, i = blockIdx.x;
+    cx.G = G;
+    cx.j = (G % 8 == 0) ? (i % 8) * (G / 8) + i / 8 : i;
+    cx.nbar = 0;
+    cx.s_status = (uint32_t*)lds;      // first 16 bytes of LDS: barrier status hand-over
+    cx.lds = lds + 16;
+
+    // The step as a flat list of phases, decoded here so that each phase routine has a
+    // single (inlined) call site and the argument block stays in scalar registers.
+    //   stack / layer: per layer  0 QKV linear  1 attention  2 output linear
+    //                             3 gate|up linear  4 down linear;  then the LM head
+    const int H = a.H, F = a.F;
+    int nph = 1;
+    if (MODE == MODE_LAYER) nph = 5 * a.L;
+    if (MODE == MODE_STACK) nph = 5 * a.L + 1;
+    for (int ph = 0; ph < nph; ++ph) {
+        const int l = ph / 5, kind = ph % 5;
+        const bool is_lm = (MODE == MODE_STACK) && ph == 5 * a.L;
+        const bool first = ph == 0;
+        if (MODE == MODE_ATTN || (MODE != MODE_LINEAR && !is_lm && kind == 1)) {
+            const half_t* q = MODE == MODE_ATTN ? a.att_q : a.q16;
+            const half_t* kc = MODE == MODE_ATTN ? a.att_k : a.layer[l].kc;
+            const half_t* vc = MODE == MODE_ATTN ? a.att_v : a.layer[l].vc;
+            half_t* out = MODE == MODE_ATTN ? a.att_out : a.o16;
+            if (!attn_phase<MT, D>(a, cx, q, kc, vc, out, MODE == MODE_ATTN ? a.att_epoch : (uint32_t)l, !first)) return;
+            continue;
+        }
+        GemmOp op;
+        op.in16 = nullptr;
+        op.ld_in = 0;
+        op.in32 = nullptr;
+        op.gain = nullptr;
+        op.out = nullptr;
+        op.ldo = 0;
+        op.kc = nullptr;
+        op.vc = nullptr;
+        op.epoch = (uint32_t)l;
+        if (MODE == MODE_LINEAR) {
+            op.W = a.lin_W;
+            op.N = a.lin_N;
+            op.K = a.lin_K;
+            op.epi = a.lin_f16 ? EPI_STORE_F16 : EPI_STORE_F32;
+            op.in16 = a.lin_x;
+            op.ld_in = a.lin_ldx;
+            op.out = a.lin_y;
+            op.ldo = a.lin_ldy;
+            op.cnt = a.sync + a.lin_cnt;
+            op.epoch = a.lin_epoch;
+        } else if (is_lm) {
+            op.W = a.Wlm;
+            op.N = a.V;
+            op.K = H;
+            op.epi = EPI_STORE_F32;
+            op.in32 = a.x;
+            op.gain = a.g_final;
+            op.out = a.logits;
+            op.ldo = a.V;
+            op.cnt = a.sync + kCntLm;
+            op.epoch = 0;
+        } else if (kind == 0) {
+            op.W = a.layer[l].Wqkv;
+            op.N = 3 * H;
+            op.K = H;
+            op.epi = EPI_QKV;
+            op.in32 = a.x;
+            op.gain = a.layer[l].g_attn;
+            op.kc = a.layer[l].kc;
+            op.vc = a.layer[l].vc;
+            op.cnt = a.sync + kCntQkv;
+        } else if (kind == 2) {
+            op.W = a.layer[l].Wo;
+            op.N = H;
+            op.K = H;
+            op.epi = EPI_RESID;
+            op.in16 = a.o16;
+            op.ld_in = H;
+            op.out = a.x;
+            op.ldo = H;
+            op.cnt = a.sync + kCntWo;
+        } else if (kind == 3) {
+            op.W = a.layer[l].Wgu;
+            op.N = 2 * F;
+            op.K = H;
+            op.epi = EPI_SWIGLU;
+            op.in32 = a.x;
+            op.gain = a.layer[l].g_ffn;
+            op.out = a.a16;
+            op.ldo = F;
+            op.cnt = a.sync + kCntGu;
+        } else {
+            op.W = a.layer[l].Wdown;
+            op.N = H;
+            op.K = F;
+            op.epi = EPI_RESID;
+            op.in16 = a.a16;
+            op.ld_in = F;
+            op.out = a.x;
+            op.ldo = H;
+            op.cnt = a.sync + kCntDown;
+        }
+        op.ngroups = (op.N + kGroupRows - 1) / kGroupRows;
+        op.ncpg = (op.K + kChunkCols - 1) / kChunkCols;
+        if (!gemm_phase<MT>(a, op, cx, !first)) return;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+static int g_num_cu = 0;
+
+int fused_grid_size()
+{
+    if (g_num_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return 0;
+        g_num_cu = prop.multiProcessorCount;
+    }
+    return g_num_cu;
+}
+
+template <int MT, int D>
+static size_t fused_lds_bytes()
+{
+    size_t gemm = 2 * (size_t)kCH * MT * kFrag + (128 + 512) * sizeof(float);
+    size_t attn = sizeof(AttnLds<D>);
+    return 16 + (gemm > attn ? gemm : attn);
+}
+
+template <int MT, int D, int MODE>
+static ghd_status launch_fused_m(const FusedArgs& a, hipStream_t st)
+{
+    static bool checked = false;
+    size_t lds = fused_lds_bytes<MT, D>();
+    int G = fused_grid_size();
+    if (G <= 0) return hip_fail(hipErrorInvalidDevice);
+    if (!checked) {
+        // all workgroups must be resident at once: one per compute unit
+        hipError_t e = hipFuncSetAttribute((const void*)k_fused<MT, D, MODE>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return hip_fail(e);
+        int per_cu = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<MT, D, MODE>, kFT, lds);
+        if (e != hipSuccess) return hip_fail(e);
+        if (per_cu < 1) return hip_fail(hipErrorLaunchOutOfResources);
+        checked = true;
+    }
+    hipLaunchKernelGGL((k_fused<MT, D, MODE>), dim3(G), dim3(kFT), lds, st, a);
+    return check_launch();
+}
+
+// The whole-step modes (one launch for all phases, grid barriers in between) are
+// switched off: their first runs on hardware ended in a GPU fault whose cause is not
+// yet known, although the same code is clean under a CPU emulation with address
+// checking.  Until it is understood, a step is a sequence of single-phase launches.
+constexpr bool kWholeStepKernel = false;
+
+template <int MT, int D>
+static ghd_status launch_fused_t(const FusedArgs& a, hipStream_t st)
+{
+    if (a.mode == MODE_LINEAR) return launch_fused_m<MT, 128, MODE_LINEAR>(a, st);
+    if (a.mode == MODE_ATTN) return launch_fused_m<MT, D, MODE_ATTN>(a, st);
+    if constexpr (kWholeStepKernel) {
+        if (a.mode == MODE_STACK) return launch_fused_m<MT, D, MODE_STACK>(a, st);
+        return launch_fused_m<MT, D, MODE_LAYER>(a, st);
+    }
+    return hip_fail(hipErrorNotSupported);
+}
+
+template <int D>
+static ghd_status launch_fused_d(const FusedArgs& a, hipStream_t st)
+{
+    int mt = (a.M + 15) / 16;
+    if (mt <= 1) return launch_fused_t<1, D>(a, st);
+    if (mt <= 2) return launch_fused_t<2, D>(a, st);
+    if (mt <= 4) return launch_fused_t<4, D>(a, st);
+    return launch_fused_t<8, D>(a, st);
+}
+
+ghd_status launch_fused(const FusedArgs& a, hipStream_t st)
+{
+    return a.d == 64 ? launch_fused_d<64>(a, st) : launch_fused_d<128>(a, st);
+}
+
+// ---- setup kernel ------------------------------------------------------------
+// One workgroup per 16-column tile of the residual stream (blockIdx.x >= 1) plus
+// block 0 for the tree tables and the sync block.
+__global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync,
+                                                     const int32_t* __restrict__ parent, int M,
+                                                     int Mpad, int kv_len, int d, float rope_base,
+                                                     uint64_t* __restrict__ mask,
+                                                     float2* __restrict__ rope, float* __restrict__ x,
+                                                     const half_t* __restrict__ x_in16, int H,
+                                                     float* __restrict__ ss)
+{
+    int tid = threadIdx.x;
+    if (blockIdx.x == 0) {
+        __shared__ int32_t s_parent[GHD_MAX_M];
+        __shared__ int32_t s_depth[GHD_MAX_M];
+        for (int i = tid; i < kSyncWords; i += 256) sync[i] = 0;
+        if (!parent) return;
+        if (tid < M) s_parent[tid] = parent[tid];
+        __syncthreads();
+        if (tid < M) {
+            uint64_t lo = 0, hi = 0;
+            int dep = 0, j = tid;
+            for (int step = 0; step < M; ++step) {
+                if (j < 64) lo |= 1ull << j; else hi |= 1ull << (j - 64);
+                int p = s_parent[j];
+                if (p < 0 || p >= j) break;
+                j = p;
+                ++dep;
+            }
+            s_depth[tid] = dep;
+            mask[2 * tid] = lo;
+            mask[2 * tid + 1] = hi;
+        }
+        __syncthreads();
+        if (rope) {
+            int half = d / 2;
+            for (int e = tid; e < M * half; e += 256) {
+                int m = e / half, j = e % half;
+                double ang = (double)(kv_len + s_depth[m]) * pow((double)rope_base, -2.0 * j / d);
+                rope[e] = make_float2((float)cos(ang), (float)sin(ang));
+            }
+        }
+        return;
+    }
+    // residual stream tiles: thread -> (row m, column within the 16-wide tile)
+    int tile = blockIdx.x - 1;
+    for (int e = tid; e < Mpad * 16; e += 256) {
+        int m = e >> 4, col = tile * 16 + (e & 15);
+        float v = 0.f;
+        if (m < M) {
+            v = x_in16 ? (float)x_in16[(size_t)m * H + col] : x[(size_t)m * H + col];
+            if (x_in16) x[(size_t)m * H + col] = v;
+        }
+        float s = v * v;
+        s += __shfl_xor(s, 1);
+        s += __shfl_xor(s, 2);
+        s += __shfl_xor(s, 4);
+        s += __shfl_xor(s, 8);
+        if ((e & 15) == 0) ss[(size_t)tile * Mpad + m] = s;
+    }
+}
+
+ghd_status launch_fused_setup(uint32_t* sync, const int32_t* parent, int M, int Mpad, int kv_len, int d,
+                              float rope_base, uint64_t* mask, float2* rope, float* x,
+                              const half_t* x_in16, int H, float* ss, hipStream_t st)
+{
+    int blocks = 1 + (ss ? H / 16 : 0);
+    hipLaunchKernelGGL(k_fused_setup, dim3(blocks), dim3(256), 0, st, sync, parent, M, Mpad, kv_len, d,
+                       rope_base, mask, rope, x, x_in16, H, ss);
+    return check_launch();
+}
+
+// ---- weight packing ------------------------------------------------------------
+// One thread per 16-byte chunk of the packed image.  Packed row p of the matrix maps
+// to a source row through the permutation of its kind:
+//   PLAIN    p
+//   QKV      inside every head the rows are ordered (j, j+1, j+d/2, j+1+d/2), j even,
+//            so the two rotary pairs of a quad sit in one lane of the GEMM output
+//   GATE_UP  (gate f, gate f+1, up f, up f+1): source holds gate rows [0,F) then up rows
+__global__ void k_pack2(half8* __restrict__ dst, const half_t* __restrict__ src, int N, int K,
+                        int kind, int d, int ngroups, int ksteps)
+{
+    size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t total = (size_t)ngroups * ksteps * kTG * 64;
+    if (id >= total) return;
+    int lane = (int)(id & 63);
+    size_t blk = id >> 6;
+    int tile_in = (int)(blk % kTG);
+    size_t gk = blk / kTG;
+    int ks = (int)(gk % ksteps);
+    int grp = (int)(gk / ksteps);
+    int p = (grp * kTG + tile_in) * 16 + (lane & 15);
+    int k = ks * 32 + (lane >> 4) * 8;
+    int srow = -1;
+    if (kind == PACK_PLAIN) {
+        if (p < N) srow = p;
+    } else if (kind == PACK_QKV) {
+        if (p < N) {
+            int head = p / d, ph = p % d;
+            int r = ph & 3;
+            int ch = (ph >> 2) * 2 + (r & 1) + ((r >= 2) ? d / 2 : 0);
+            srow = head * d + ch;
+        }
+    } else {
+        int F = N / 2;
+        int f = (p >> 4) * 8 + ((p & 15) >> 2) * 2 + (p & 1);
+        bool up = (p & 3) >= 2;
+        if (f < F) srow = (up ? F : 0) + f;
+    }
+    half8 v;
+    for (int e = 0; e < 8; ++e)
+        v[e] = (srow >= 0 && k + e < K) ? src[(size_t)srow * K + k + e] : (half_t)0;
+    dst[id] = v;
+}
+
+size_t packed_bytes2(int N, int K)
+{
+    size_t ngroups = (N + kGroupRows - 1) / kGroupRows;
+    size_t ksteps = (size_t)((K + kChunkCols - 1) / kChunkCols) * kCH;
+    return ngroups * ksteps * kTG * 1024;
+}
+
+ghd_status launch_pack2(void* dst, const void* src, int N, int K, int kind, int d, hipStream_t st)
+{
+    int ngroups = (N + kGroupRows - 1) / kGroupRows;
+    int ksteps = ((K + kChunkCols - 1) / kChunkCols) * kCH;
+    size_t total = (size_t)ngroups * ksteps * kTG * 64;
+    hipLaunchKernelGGL(k_pack2, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (half8*)dst,
+                       (const half_t*)src, N, K, kind, d, ngroups, ksteps);
+    return check_launch();
+}
+
+}  // namespace ghd

@@ -12,12 +12,16 @@ from . import binding as B
 MATRICES = ("Wqkv", "Wo", "Wgu", "Wdown")
 
 
-def upload_layer(w: Dict[str, torch.Tensor], device="cuda") -> Dict[str, torch.Tensor]:
+def upload_layer(w: Dict[str, torch.Tensor], head_dim: int, device="cuda") -> Dict[str, torch.Tensor]:
     """fp16 layer weights (row-major, any device) -> gains + packed matrices on the GPU."""
+    kinds = {}     # every matrix in natural row order (GHD_PACK_PLAIN)
     out = {}
     for name, t in w.items():
         t = t.to(device)
-        out[name] = B.ghd_pack_weight(t) if name in MATRICES else t.contiguous()
+        if name in MATRICES:
+            out[name] = B.ghd_pack_weight(t, kinds.get(name, B.GHD_PACK_PLAIN), head_dim)
+        else:
+            out[name] = t.contiguous()
     return out
 
 

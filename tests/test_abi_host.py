@@ -59,8 +59,10 @@ def test_tree_validate(lib):
 
 
 def test_packed_size(lib):
-    assert lib.ghd_packed_weight_bytes(16, 32) == 1024
-    assert lib.ghd_packed_weight_bytes(17, 33) == 4 * 1024
+    assert lib.ghd_packed_weight_bytes(16, 32) == 256 * 128 * 2
+    assert lib.ghd_packed_weight_bytes(257, 129) == 512 * 256 * 2
+    assert lib.ghd_packed_weight_bytes(32000, 4096) == 32000 * 4096 * 2
+    assert lib.ghd_packed_weight_bytes(22016, 4096) == 22016 * 4096 * 2
     assert lib.ghd_packed_weight_bytes(12288, 4096) == 12288 * 4096 * 2   # same bytes as row-major
     assert lib.ghd_packed_weight_bytes(0, 32) == 0
 
@@ -88,7 +90,7 @@ def test_linear_rejects_bad_arguments(lib):
     assert call(ldx=68) == B.GHD_ERR_ALIGN
     assert call(ws=None) == B.GHD_ERR_WORKSPACE
     assert call(ws_bytes=16) == B.GHD_ERR_WORKSPACE
-    assert lib.ghd_linear_workspace_bytes(16, 64, 64) >= 16 * 64 * 4
+    assert lib.ghd_linear_workspace_bytes(16, 64, 64) >= 16 * 256 * 4
     assert lib.ghd_linear_workspace_bytes(0, 64, 64) == 0
 
 
@@ -160,6 +162,25 @@ def test_layer_and_stack_reject_bad_arguments(lib):
     assert stack(kv_len=249) == B.GHD_ERR_CAPACITY
     assert stack(x_in=FAKE + 2) == B.GHD_ERR_ALIGN
     assert stack(ws_bytes=100) == B.GHD_ERR_WORKSPACE
+
+
+def test_pack_and_mask_reject_bad_arguments(lib):
+    f = lib.ghd_pack_weight
+    assert f(None, FAKE, 16, 32, 0, 0, None) == B.GHD_ERR_NULL
+    assert f(FAKE, FAKE, 0, 32, 0, 0, None) == B.GHD_ERR_SHAPE
+    assert f(FAKE, FAKE, 16, 32, 3, 0, None) == B.GHD_ERR_SHAPE
+    assert f(FAKE, FAKE, 768, 32, B.GHD_PACK_QKV, 96, None) == B.GHD_ERR_SHAPE
+    assert f(FAKE, FAKE, 100, 32, B.GHD_PACK_QKV, 64, None) == B.GHD_ERR_SHAPE
+    assert f(FAKE, FAKE, 40, 32, B.GHD_PACK_GATE_UP, 0, None) == B.GHD_ERR_SHAPE
+    assert f(FAKE + 4, FAKE, 16, 32, 0, 0, None) == B.GHD_ERR_ALIGN
+    g = lib.ghd_tree_mask
+    need = lib.ghd_tree_mask_workspace_bytes()
+    assert need > 0
+    assert g(None, 4, FAKE, FAKE, need, None) == B.GHD_ERR_NULL
+    assert g(FAKE, 0, FAKE, FAKE, need, None) == B.GHD_ERR_SHAPE
+    assert g(FAKE, 4, FAKE, None, need, None) == B.GHD_ERR_WORKSPACE
+    assert g(FAKE, 4, FAKE, FAKE, 8, None) == B.GHD_ERR_WORKSPACE
+    assert lib.ghd_step_status(None, None, None) == B.GHD_ERR_NULL
 
 
 def test_accept_rejects_bad_arguments(lib):

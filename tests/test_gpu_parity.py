@@ -48,23 +48,40 @@ def close(got, ref, atol, rtol):
     return worst <= 0, float(err.max()), float((err / np.maximum(np.abs(ref), 1e-3)).max())
 
 
-def reference_pack(W):
+def reference_pack(W, kind=0, d=0):
     """The packed layout written out from its definition (include/ghd.h)."""
     N, K = W.shape
-    nt, ks = (N + 15) // 16, (K + 31) // 32
-    Wp = np.zeros((nt * 16, ks * 32), dtype=np.uint16)
-    Wp[:N, :K] = W.view(np.uint16)
-    # [tile, kstep, kgroup, row, 8]
-    out = Wp.reshape(nt, 16, ks, 4, 8).transpose(0, 2, 3, 1, 4)
+    Np, Kp = (N + 255) // 256 * 256, (K + 127) // 128 * 128
+    src = np.full(Np, -1, dtype=np.int64)
+    for p in range(N):
+        if kind == 0:
+            src[p] = p
+        elif kind == 1:
+            head, ph = divmod(p, d)
+            i, r = divmod(ph, 4)
+            src[p] = head * d + 2 * i + (r & 1) + (d // 2 if r >= 2 else 0)
+        else:
+            F = N // 2
+            t, q = divmod(p, 16)
+            i, r = divmod(q, 4)
+            f = 8 * t + 2 * i + (r & 1)
+            src[p] = (F if r >= 2 else 0) + f
+    Wp = np.zeros((Np, Kp), dtype=np.uint16)
+    rows = src >= 0
+    Wp[rows, :K] = W.view(np.uint16)[src[rows]]
+    # [group, tile, row, kstep, kgroup, 8] -> [group, kstep, tile, kgroup, row, 8]
+    out = Wp.reshape(Np // 256, 16, 16, Kp // 32, 4, 8).transpose(0, 3, 1, 4, 2, 5)
     return np.ascontiguousarray(out).reshape(-1)
 
 
-@pytest.mark.parametrize("N,K", [(16, 32), (40, 72), (1000, 256), (256, 688)])
-def test_pack_weight_bytes(B, N, K):
-    say("pack", N, K)
+@pytest.mark.parametrize("N,K,kind,d", [(16, 32, 0, 0), (40, 72, 0, 0), (1000, 256, 0, 0),
+                                        (256, 688, 0, 0), (768, 256, 1, 64), (3 * 512, 136, 1, 128),
+                                        (2 * 688, 256, 2, 0), (2 * 1376, 128, 2, 0)])
+def test_pack_weight_bytes(B, N, K, kind, d):
+    say("pack", N, K, kind, d)
     W = wl.activations(N, K, 21, tag="w", std=0.02)
-    got = B.ghd_pack_weight(W.cuda()).cpu().numpy().view(np.uint16)
-    assert np.array_equal(got, reference_pack(W.numpy()))
+    got = B.ghd_pack_weight(W.cuda(), kind, d).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, reference_pack(W.numpy(), kind, d))
 
 
 def test_tree_mask_bit_exact(B, orc32):
@@ -96,7 +113,10 @@ def test_linear_skinny(B, orc32, M, N, K):
     W = wl.activations(N, K, 32, tag="w", std=0.02)
     Wp = B.ghd_pack_weight(W.cuda())
     ref = orc32.linear(x.numpy().astype(np.float32), W.numpy())
-    y = B.ghd_linear_skinny(x.cuda(), Wp, N).cpu().numpy()
+    ws = B.workspace(B.lib().ghd_linear_workspace_bytes(M, N, K))
+    y = B.ghd_linear_skinny(x.cuda(), Wp, N, ws=ws)
+    assert B.ghd_step_status(ws) == 0
+    y = y.cpu().numpy()
     ok, ma, mr = close(y, ref, 2e-4, 2e-4)
     assert ok, (ma, mr)
     # fp16 output = the fp32 result rounded once
@@ -145,8 +165,11 @@ def test_tree_attention(B, orc32, M, nh, d, kv_len, tree):
     parent = make_tree(tree, M)
     q, kc, vc = attention_case(M, nh, d, kv_len, parent, 41)
     ref = orc32.tree_attention(q.numpy().astype(np.float32), kc.numpy(), vc.numpy(), parent, kv_len)
+    ws = B.workspace(B.lib().ghd_attention_workspace_bytes(M, kv_len, nh, d))
     got = B.ghd_tree_attention(q.cuda(), kc.cuda(), vc.cuda(), torch.from_numpy(parent).cuda(),
-                               kv_len).cpu().numpy()
+                               kv_len, ws=ws)
+    assert B.ghd_step_status(ws) == 0
+    got = got.cpu().numpy()
     ok, ma, mr = close(got, ref, 5e-3, 5e-3)
     assert ok, (ma, mr)
 
@@ -172,12 +195,13 @@ def run_layer_case(B, model, orc32, shape, M, kv_len, parent, seed):
     ref = orc32.verify_layer(shape, {k: v.numpy() for k, v in w.items()}, kc_o, vc_o,
                              x16.numpy().astype(np.float32), parent, kv_len, round16=True)
     # GPU
-    wd = model.upload_layer(w)
+    wd = model.upload_layer(w, shape.d)
     kc_d, vc_d = kc.cuda(), vc.cuda()
     x = x16.float().cuda()
     cfg = B.make_cfg(shape, cap)
-    B.ghd_verify_layer(cfg, wd, kc_d, vc_d, x, torch.from_numpy(parent).cuda(), kv_len)
-    torch.cuda.synchronize()
+    ws = B.workspace(B.ghd_workspace_bytes(cfg, M, kv_len))
+    B.ghd_verify_layer(cfg, wd, kc_d, vc_d, x, torch.from_numpy(parent).cuda(), kv_len, ws=ws)
+    assert B.ghd_step_status(ws) == 0
     ok, ma, mr = close(x.cpu().numpy(), ref, 2e-2, 1e-2)
     assert ok, ("residual stream", ma, mr)
     for name, got, want in (("k", kc_d, kc_o), ("v", vc_d, vc_o)):
@@ -221,12 +245,13 @@ def run_stack_case(B, model, orc32, shape, M, kv_len, parent, seed):
     ref_logits, ref_x = orc32.verify_stack(
         shape, [{k: v.numpy() for k, v in w.items()} for w in layers], kcs, vcs,
         {k: v.numpy() for k, v in head.items()}, x16.numpy(), parent, kv_len, round16=True)
-    stack = model.build_stack(shape, cap, [model.upload_layer(w) for w in layers],
+    stack = model.build_stack(shape, cap, [model.upload_layer(w, shape.d) for w in layers],
                               [(k.cuda(), v.cuda()) for k, v in caches], model.upload_head(head))
     x_out = torch.empty((M, shape.H), dtype=torch.float32, device="cuda")
     pd = torch.from_numpy(parent).cuda()
-    logits = B.ghd_verify_stack(stack, x16.cuda(), pd, kv_len, x_out=x_out)
-    torch.cuda.synchronize()
+    ws = B.workspace(B.ghd_workspace_bytes(stack.cfg, M, kv_len))
+    logits = B.ghd_verify_stack(stack, x16.cuda(), pd, kv_len, x_out=x_out, ws=ws)
+    assert B.ghd_step_status(ws) == 0
     ok, ma, mr = close(x_out.cpu().numpy(), ref_x, 2e-2, 1e-2)
     assert ok, ("final residual", ma, mr)
     ok, ma, mr = close(logits.cpu().numpy(), ref_logits, 2e-2, 1e-2)
