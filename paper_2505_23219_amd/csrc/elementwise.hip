@@ -8,43 +8,63 @@
 namespace ghd {
 
 // ---- residual add + RMSNorm ----------------------------------------------------
-// One workgroup per row.  x_new = (x_old or widen(x_in16)) + sum of the S split
-// partials (fixed order, so the result is run-to-run identical); then
+// One workgroup of 1024 threads per row, four consecutive columns per thread and pass, so
+// all loads of a row are in flight at once.  x_new = (x_old or widen(x_in16)) + y32 (the
+// preceding linear layer's output, if given); then
 // n16 = fp16(x_new * rsqrt(mean(x_new^2) + eps) * g).
-__global__ __launch_bounds__(256) void k_residual_norm(float* __restrict__ x,
-                                                       const half_t* __restrict__ x_in16,
-                                                       const float* __restrict__ part, int S,
-                                                       int64_t ld, const half_t* __restrict__ g,
-                                                       half_t* __restrict__ n16, int M, int H,
-                                                       float eps)
+__global__ __launch_bounds__(1024) void k_residual_norm(float* __restrict__ x,
+                                                        const half_t* __restrict__ x_in16,
+                                                        const float* __restrict__ part, int S,
+                                                        int64_t ld, const half_t* __restrict__ g,
+                                                        half_t* __restrict__ n16, int M, int H,
+                                                        float eps)
 {
-    extern __shared__ float s_row[];   // H floats
-    __shared__ float s_red[4];
-    int m = blockIdx.x, tid = threadIdx.x;
+    __shared__ float s_red[16];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    constexpr int kMaxPass = 11;               // H <= 1024 * 4 * 11 (H % 4 == 0)
+    floatx4 v[kMaxPass];
     float ss = 0.f;
-    for (int c = tid; c < H; c += 256) {
-        float v = x_in16 ? (float)x_in16[(size_t)m * H + c] : x[(size_t)m * H + c];
-        for (int s = 0; s < S; ++s) v += part[((size_t)s * M + m) * ld + c];
-        s_row[c] = v;
-        x[(size_t)m * H + c] = v;
-        ss += v * v;
+#pragma unroll
+    for (int p = 0; p < kMaxPass; ++p) {
+        const int c = tid * 4 + p * 4096;
+        if (c >= H) break;
+        floatx4 t;
+        if (x_in16) {
+            half4 h = *(const half4*)(x_in16 + (size_t)m * H + c);
+            t = (floatx4){(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
+        } else {
+            t = *(const floatx4*)(x + (size_t)m * H + c);
+        }
+        for (int s = 0; s < S; ++s) t += *(const floatx4*)(part + ((size_t)s * M + m) * ld + c);
+        *(floatx4*)(x + (size_t)m * H + c) = t;
+        ss += t[0] * t[0] + t[1] * t[1] + t[2] * t[2] + t[3] * t[3];
+        v[p] = t;
     }
+    if (!g) return;
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
     if ((tid & 63) == 0) s_red[tid >> 6] = ss;
     __syncthreads();
-    if (!g) return;
-    float tot = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+    float tot = 0.f;
+    for (int w = 0; w < 16; ++w) tot += s_red[w];
     float r = 1.0f / sqrtf(tot / (float)H + eps);
-    for (int c = tid; c < H; c += 256)
-        n16[(size_t)m * H + c] = (half_t)(s_row[c] * r * (float)g[c]);
+#pragma unroll
+    for (int p = 0; p < kMaxPass; ++p) {
+        const int c = tid * 4 + p * 4096;
+        if (c >= H) break;
+        half4 gv = *(const half4*)(g + c);
+        half4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (half_t)(v[p][e] * r * (float)gv[e]);
+        *(half4*)(n16 + (size_t)m * H + c) = o;
+    }
 }
 
 ghd_status launch_residual_norm(float* x, const half_t* x_in16, const float* part, int S, int64_t ld,
                                 const half_t* g, half_t* n16, int M, int H, float eps,
                                 hipStream_t st)
 {
-    hipLaunchKernelGGL(k_residual_norm, dim3(M), dim3(256), (size_t)H * sizeof(float), st, x, x_in16,
-                       part, S, ld, g, n16, M, H, eps);
+    hipLaunchKernelGGL(k_residual_norm, dim3(M), dim3(1024), 0, st, x, x_in16, part, S, ld, g, n16, M,
+                       H, eps);
     return check_launch();
 }
 

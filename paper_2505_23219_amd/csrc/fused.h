@@ -15,17 +15,20 @@ enum { EPI_STORE_F32 = 0, EPI_STORE_F16 = 1, EPI_RESID = 2, EPI_SWIGLU = 3, EPI_
 enum { MODE_STACK = 0, MODE_LAYER = 1, MODE_LINEAR = 2, MODE_ATTN = 3 };
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 
-// counters in the sync block (uint32 words), zeroed by the setup kernel
+// The sync block (uint32 words), zeroed by the set-up kernel.  Every item counter has a
+// 128-byte line of its own (kCntStride words apart): the workgroups of one item poll and
+// bump it without disturbing the others.
 constexpr int kSyncBarrier = 0;   // grid-barrier arrivals (monotonic)
-constexpr int kSyncStatus = 1;    // 0 = ok, 1 = a bounded wait gave up
-constexpr int kSyncCnt = 16;      // first group counter
-constexpr int kCntQkv = kSyncCnt;           // up to 512 row groups each
-constexpr int kCntWo = kCntQkv + 512;
-constexpr int kCntGu = kCntWo + 512;
-constexpr int kCntDown = kCntGu + 512;
-constexpr int kCntLm = kCntDown + 512;
-constexpr int kCntAttn = kCntLm + 1024;
-constexpr int kSyncWords = kCntAttn + 256;
+constexpr int kSyncStatus = 1;    // 0 = ok, else the code of the wait that gave up
+constexpr int kCntStride = 32;
+constexpr int kSyncCnt = 32;                          // first counter line
+constexpr int kCntQkv = kSyncCnt;                     // up to 512 row groups each
+constexpr int kCntWo = kCntQkv + 512 * kCntStride;
+constexpr int kCntGu = kCntWo + 512 * kCntStride;
+constexpr int kCntDown = kCntGu + 512 * kCntStride;
+constexpr int kCntLm = kCntDown + 512 * kCntStride;   // up to 1024 row groups
+constexpr int kCntAttn = kCntLm + 1024 * kCntStride;  // up to 256 heads
+constexpr int kSyncWords = kCntAttn + 256 * kCntStride;
 
 struct LayerPtrs {
     const half_t* g_attn;

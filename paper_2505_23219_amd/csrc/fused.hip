@@ -36,6 +36,8 @@
 // head are merged with the online-softmax rescale of section 3.2.2.
 #include "fused.h"
 
+#include <type_traits>
+
 namespace ghd {
 
 constexpr int kFrag = 4 * 272;              // LDS bytes of one padded 16x32 B fragment
@@ -69,46 +71,77 @@ __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Partial results cross workgroups (and XCDs, whose L2 caches are not coherent with one
-// another) through device-scope relaxed atomic accesses: such a store is written through
-// to memory and such a load is served from memory, access by access.  The alternative, a
-// device-scope fence, writes back and invalidates a whole L2 (about 4 us each here, and
-// every other workgroup of that XCD loses its cached operands).  Order is kept by the
-// pipeline: a wavefront's stores have been acknowledged when it passes __syncthreads(),
-// and only then does thread 0 bump the counter the readers poll.
-__device__ __forceinline__ void st_coherent(float* p, floatx4 v)
+// Work shares.  A phase has `items` (row groups, or heads) of `per_item` units (chunks,
+// or key tiles) each.  Items are dealt to the 8 XCDs in contiguous blocks, and the units
+// of an XCD's items to its workgroups in equal contiguous ranges.  Workgroup i runs on
+// XCD i % 8 (checked at kernel start), so the logical index j = (i % 8) * G/8 + i / 8
+// puts the G/8 workgroups of an XCD side by side.  An item that is split over several
+// workgroups is therefore always finished inside one XCD, and its partial results are
+// exchanged through that XCD's L2 with plain stores and loads: the writers' stores have
+// been acknowledged by the L2 when they pass __syncthreads(), only then does thread 0
+// bump the item's counter, and a reader's first access to a slot line in a launch cannot
+// hit in its L1.  No device-scope fence (a write-back and invalidate of a whole L2, about
+// 4 us here) is needed anywhere inside a phase.
+struct Share {
+    int U;        // units of this XCD (fits 32 bits together with the factor Ge)
+    long base;    // global index of its first unit
+    int Ge;       // workgroups of this XCD that get units
+    int wg0;      // logical index of its first workgroup
+    long c0, c1;  // this workgroup's range of global unit indices (empty if c0 == c1)
+    int per_item;
+    // local (within-XCD) unit index where workgroup wg's range begins
+    __device__ int lbegin(int wg) const { return (int)((unsigned)U * (unsigned)(wg - wg0) / (unsigned)Ge); }
+    __device__ int owner_local(int lunit) const
+    {
+        return wg0 + (int)(((unsigned)(lunit + 1) * (unsigned)Ge - 1u) / (unsigned)U);
+    }
+    __device__ int litem0(int item) const { return (int)((long)item * per_item - base); }
+    __device__ int first_of(int item) const { return owner_local(litem0(item)); }
+    __device__ int last_of(int item) const { return owner_local(litem0(item) + per_item - 1); }
+    // does workgroup wg's range begin inside `item` (and not in an earlier one)?
+    __device__ bool begins_in(int wg, int item) const { return lbegin(wg) >= litem0(item); }
+};
+
+__device__ __forceinline__ Share make_share(int items, int per_item, int j, int G)
 {
-    union { floatx4 f; unsigned long long u[2]; } c;
-    c.f = v;
-    __hip_atomic_store((unsigned long long*)p, c.u[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store((unsigned long long*)p + 1, c.u[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// Reading side.  A slot is written once and read once per launch, after the counter says
-// it is complete; caches are invalidated when a kernel starts, so no cache of the reading
-// XCD can hold an older copy of the line and a plain (pipelined) load fetches it from
-// memory, or from the L2 it shares with the writer.  (A kernel that reused slots within
-// one launch would have to read them with device-scope loads instead.)
-__device__ __forceinline__ floatx4 ld_exchange(const float* p) { return *(const floatx4*)p; }
-__device__ __forceinline__ float ld_exchange1(const float* p) { return *p; }
-__device__ __forceinline__ void st_coherent1(float* p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int nx = (G % 8 == 0) ? 8 : 1;
+    const int Gx = G / nx, x = j / Gx;
+    const int i0 = (int)((long)items * x / nx), i1 = (int)((long)items * (x + 1) / nx);
+    Share sh;
+    sh.per_item = per_item;
+    sh.U = (i1 - i0) * per_item;
+    sh.base = (long)i0 * per_item;
+    sh.wg0 = x * Gx;
+    sh.Ge = sh.U < Gx ? sh.U : Gx;
+    sh.c0 = sh.c1 = 0;
+    if (j - sh.wg0 < sh.Ge) {
+        sh.c0 = sh.base + sh.lbegin(j);
+        sh.c1 = sh.base + ((j + 1 - sh.wg0 < sh.Ge) ? sh.lbegin(j + 1) : sh.U);
+    }
+    return sh;
 }
 
 // Waits until *p >= target.  Gives up (and raises the status word to `code`) after
 // kWaitTicks of wall-clock time, or as soon as another workgroup has given up, so that a
 // grid that is not fully resident ends with an error instead of hanging.  One thread calls.
-__device__ __forceinline__ void bounded_wait(uint32_t* sync, const uint32_t* p, uint32_t target,
+__device__ __forceinline__ uint32_t poll(uint32_t* p)
+{
+    // a read-modify-write that changes nothing: it is served where the counting atomics
+    // are, so it sees them at once (a device-scope load lags them by several microseconds)
+    return atomicOr(p, 0u);
+}
+
+__device__ __forceinline__ void bounded_wait(uint32_t* sync, uint32_t* p, uint32_t target,
                                              uint32_t code)
 {
-    if (ld_relaxed(p) >= target) return;
+    if (poll(p) >= target) return;
     const long long t0 = wall_clock64();
-    while (ld_relaxed(p) < target) {
+    while (poll(p) < target) {
         if (wall_clock64() - t0 > kWaitTicks || ld_relaxed(sync + kSyncStatus) != 0) {
             atomicCAS(sync + kSyncStatus, 0u, code);
             break;
         }
-        __builtin_amdgcn_s_sleep(2);
+        __builtin_amdgcn_s_sleep(8);
     }
 }
 
@@ -134,8 +167,6 @@ __device__ __forceinline__ bool grid_barrier(const FusedArgs& a, Ctx& cx)
     return *cx.s_status == 0;
 }
 
-__device__ inline long chunk_begin(long U, int j, int G) { return U * j / G; }
-__device__ inline int chunk_owner(long U, long x, int G) { return (int)(((x + 1) * G - 1) / U); }
 
 // ---------------------------------------------------------------------------
 // epilogue of one 16x16 output fragment: lane (c, g4) holds y[m][n0 .. n0+3]
@@ -219,12 +250,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     float* s_rinv = (float*)(cx.lds + 2 * CHUNK);  // Mpad floats
     float* s_tmp = s_rinv + 128;                   // 512 floats
 
-    // U chunks are dealt to the first Ge workgroups in equal contiguous ranges (every one
-    // of them non-empty); with fewer chunks than workgroups the rest have nothing to do.
-    const long U = (long)op.ngroups * op.ncpg;
-    const int Ge = (int)(U < (long)cx.G ? U : (long)cx.G);
-    const bool has_work = cx.j < Ge;
-    const long c0 = has_work ? chunk_begin(U, cx.j, Ge) : 0, c1 = has_work ? chunk_begin(U, cx.j + 1, Ge) : 0;
+    const Share sh = make_share(op.ngroups, op.ncpg, cx.j, cx.G);
+    const long c0 = sh.c0, c1 = sh.c1;
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
     // ---- weight stream: linear in the chunk index
@@ -319,11 +346,12 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     acc_zero();
 
     // A group's parts: workgroups first..last own pieces of its K range.
-    auto group_first = [&](int grp) { return chunk_owner(U, (long)grp * op.ncpg, Ge); };
-    auto group_last = [&](int grp) { return chunk_owner(U, (long)(grp + 1) * op.ncpg - 1, Ge); };
+    auto group_first = [&](int grp) { return sh.first_of(grp); };
+    auto group_last = [&](int grp) { return sh.last_of(grp); };
+    // slot 0 of a workgroup holds the partial of the group its range begins in, slot 1 that
+    // of the group it ends in (when that is another one)
     auto slot_of = [&](int wg, int grp) -> float* {
-        int gf = (int)(chunk_begin(U, wg, Ge) / op.ncpg);
-        return a.part + ((size_t)wg * 2 + (grp == gf ? 0 : 1)) * (size_t)(NF * 256);
+        return a.part + ((size_t)wg * 2 + (sh.begins_in(wg, grp) ? 0 : 1)) * (size_t)(NF * 256);
     };
 
     // Ends the accumulation of row group `grp`: direct epilogue when this workgroup
@@ -343,9 +371,9 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int b = 0; b < MT; ++b)
-                    st_coherent(slot + ((size_t)((wave * 2 + t) * MT + b) * 64 + lane) * 4, acc[t][b]);
-            __syncthreads();            // every wavefront's partial has been acknowledged
-            if (tid == 0) atomicAdd(op.cnt + grp, 1u);
+                    *(floatx4*)(slot + ((size_t)((wave * 2 + t) * MT + b) * 64 + lane) * 4) = acc[t][b];
+            __syncthreads();            // every wavefront's partial has been acknowledged by the L2
+            if (tid == 0) atomicAdd(op.cnt + grp * kCntStride, 1u);
         }
         acc_zero();
     };
@@ -390,13 +418,25 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             int first = group_first(grp), last = group_last(grp);
             if (first == last) continue;
             int np = last - first + 1, me = cx.j - first;
-            if (tid == 0) bounded_wait(a.sync, op.cnt + grp, (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
+            if (tid == 0) bounded_wait(a.sync, op.cnt + grp * kCntStride, (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
             __syncthreads();
             int f0 = NF * me / np, f1 = NF * (me + 1) / np;
             for (int f = f0 + wave; f < f1; f += 8) {
-                floatx4 v = {0.f, 0.f, 0.f, 0.f};
-                for (int p = 0; p < np; ++p)
-                    v += ld_exchange(slot_of(first + p, grp) + ((size_t)f * 64 + lane) * 4);
+                // Sum the parts in index order (fixed order: the result does not depend on
+                // timing), eight loads in flight at a time.  Parts after the first begin
+                // inside this group, so their partial is in their slot 0.
+                const size_t foff = ((size_t)f * 64 + lane) * 4;
+                floatx4 v = *(const floatx4*)(slot_of(first, grp) + foff);
+                for (int p0 = 1; p0 < np; p0 += 8) {
+                    floatx4 t[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (p0 + q < np)
+                            t[q] = *(const floatx4*)(a.part + (size_t)(first + p0 + q) * 2 * (NF * 256) + foff);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (p0 + q < np) v += t[q];
+                }
                 int tile = f / MT, b = f % MT;
                 epilogue(a, op, v, b * 16 + c, (grp * kTG + tile) * 16 + g4 * 4, lane);
             }
@@ -431,13 +471,13 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
     const int kh = wave >> 2, wq = wave & 3;   // key half of the tile, row-tile slot
     const int M = a.M, nh = a.nh, T = a.kv_len + a.M;
     const int ntile = (T + 63) >> 6;
-    const long U = (long)nh * ntile;
-    const int Ge = (int)(U < (long)cx.G ? U : (long)cx.G);
-    const bool has_work = cx.j < Ge;
-    const long u0 = has_work ? chunk_begin(U, cx.j, Ge) : 0, u1 = has_work ? chunk_begin(U, cx.j + 1, Ge) : 0;
+    const Share sh = make_share(nh, ntile, cx.j, cx.G);
+    const long u0 = sh.c0, u1 = sh.c1;
 
-    half8 kreg[NLD], vreg[NLD];
-    auto load_tile = [&](long u, bool committed_only) {
+    // two tiles in flight: registers of set (u - u0) & 1 hold tile u until it is staged
+    half8 kreg[2][NLD], vreg[2][NLD];
+    auto load_tile = [&](auto set, long u, bool committed_only) {
+        constexpr int S = decltype(set)::value;
         int head = (int)(u / ntile), tile = (int)(u % ntile);
         const half_t* kh_ = kc + (size_t)head * a.stride_head;
         const half_t* vh_ = vc + (size_t)head * a.stride_head;
@@ -446,18 +486,19 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
             int id = tid + kFT * i;
             int row = id / CPR, ch = id % CPR;
             int key = min(tile * 64 + row, committed_only ? a.kv_len - 1 : T - 1);
-            kreg[i] = *(const half8*)(kh_ + (size_t)key * a.stride_tok + ch * 8);
-            vreg[i] = *(const half8*)(vh_ + (size_t)key * a.stride_tok + ch * 8);
+            kreg[S][i] = *(const half8*)(kh_ + (size_t)key * a.stride_tok + ch * 8);
+            vreg[S][i] = *(const half8*)(vh_ + (size_t)key * a.stride_tok + ch * 8);
         }
     };
-    auto store_tile = [&]() {
+    auto store_tile = [&](auto set) {
+        constexpr int S = decltype(set)::value;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             int id = tid + kFT * i;
             int row = id / CPR, ch = id % CPR;
-            *(half8*)(&sm.k[row * L::KS + ch * 8]) = kreg[i];
+            *(half8*)(&sm.k[row * L::KS + ch * 8]) = kreg[S][i];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sm.vt[(ch * 8 + e) * L::VS + row] = vreg[i][e];
+            for (int e = 0; e < 8; ++e) sm.vt[(ch * 8 + e) * L::VS + row] = vreg[S][i][e];
         }
     };
 
@@ -467,7 +508,7 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
     if (u0 < u1 && barrier_first) {
         int tile = (int)(u0 % ntile);
         if (tile * 64 + 64 <= a.kv_len) {
-            load_tile(u0, true);
+            load_tile(std::integral_constant<int, 0>{}, u0, true);
             prefetched = true;
         }
     }
@@ -507,11 +548,10 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
         }
     };
     // parts of a head: workgroups first..last, two key halves each
-    auto head_first = [&](int head) { return chunk_owner(U, (long)head * ntile, Ge); };
-    auto head_last = [&](int head) { return chunk_owner(U, (long)(head + 1) * ntile - 1, Ge); };
+    auto head_first = [&](int head) { return sh.first_of(head); };
+    auto head_last = [&](int head) { return sh.last_of(head); };
     auto slot_index = [&](int wg, int head, int half) -> size_t {
-        int hf = (int)(chunk_begin(U, wg, Ge) / ntile);
-        return ((size_t)wg * 2 + (head == hf ? 0 : 1)) * 2 + half;
+        return ((size_t)wg * 2 + (sh.begins_in(wg, head) ? 0 : 1)) * 2 + half;
     };
     auto head_flush = [&](int head) {
         if (!wave_active) return;
@@ -525,29 +565,30 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
             size_t row = slot * a.Mpad + mrow[t];
 #pragma unroll
             for (int e = 0; e < DT; ++e)
-                st_coherent(a.o_part + row * D + e * 16 + g4 * 4, oacc[t][e]);
+                *(floatx4*)(a.o_part + row * D + e * 16 + g4 * 4) = oacc[t][e];
             if (g4 == 0) {
-                st_coherent1(a.ml_part + row * 2, mrun[t]);
-                st_coherent1(a.ml_part + row * 2 + 1, l);
+                a.ml_part[row * 2] = mrun[t];
+                a.ml_part[row * 2 + 1] = l;
             }
         }
     };
 
-    if (!prefetched) load_tile(u0, false);
+    if (!prefetched) load_tile(std::integral_constant<int, 0>{}, u0, false);
+    if (u0 + 1 < u1) load_tile(std::integral_constant<int, 1>{}, u0 + 1, false);
     int cur = (int)(u0 / ntile);
     head_begin(cur);
-    for (long u = u0; u < u1; ++u) {
+    auto do_tile = [&](auto set, long u) {
         int head = (int)(u / ntile), tile = (int)(u % ntile);
         __syncthreads();            // previous tile fully consumed
-        store_tile();
+        store_tile(set);
         __syncthreads();
-        if (u + 1 < u1) load_tile(u + 1, false);
+        if (u + 2 < u1) load_tile(set, u + 2, false);
         if (head != cur) {
             head_flush(cur);
             cur = head;
             head_begin(cur);
         }
-        if (!wave_active) continue;
+        if (!wave_active) return;
         const int key0 = tile * 64 + kh * 32;    // this wavefront's 32 keys
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
@@ -628,38 +669,60 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
                 oacc[t][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pf, oacc[t][e], 0, 0, 0);
             }
         }
+    
+    };
+    for (long u = u0; u < u1; u += 2) {
+        do_tile(std::integral_constant<int, 0>{}, u);
+        if (u + 1 < u1) do_tile(std::integral_constant<int, 1>{}, u + 1);
     }
     head_flush(cur);
     __syncthreads();
     int hfirst = (int)(u0 / ntile), hlast = (int)((u1 - 1) / ntile);
     if (tid == 0)
-        for (int head = hfirst; head <= hlast; ++head) atomicAdd(a.sync + kCntAttn + head, 1u);
+        for (int head = hfirst; head <= hlast; ++head)
+            atomicAdd(a.sync + kCntAttn + head * kCntStride, 1u);
 
     // ---- merge: every workgroup of a head combines its share of the rows
     for (int head = hfirst; head <= hlast; ++head) {
         int first = head_first(head), last = head_last(head);
         int np = last - first + 1, me = cx.j - first;
-        if (tid == 0) bounded_wait(a.sync, a.sync + kCntAttn + head, (uint32_t)np * (epoch + 1), 2000u);
+        if (tid == 0) bounded_wait(a.sync, a.sync + kCntAttn + head * kCntStride, (uint32_t)np * (epoch + 1), 2000u);
         __syncthreads();
         int r0 = M * me / np, r1 = M * (me + 1) / np;
+        const int np2 = np * 2;      // parts: (workgroup, key half); at most 64
         for (int m = r0 + wave; m < r1; m += 8) {
-            float mx = -INFINITY;
-            for (int p = 0; p < np; ++p)
-                for (int hf = 0; hf < 2; ++hf)
-                    mx = fmaxf(mx, ld_exchange1(a.ml_part + (slot_index(first + p, head, hf) * a.Mpad + m) * 2));
-            float num[D / 64], den = 0.f;
+            // lane q holds the statistics of part q
+            float mq = -INFINITY, lq = 0.f;
+            size_t rowq = 0;
+            if (lane < np2) {
+                rowq = slot_index(first + (lane >> 1), head, lane & 1) * a.Mpad + m;
+                mq = a.ml_part[rowq * 2];
+                lq = a.ml_part[rowq * 2 + 1];
+            }
+            float mx = mq;
+            for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+            float wq = (mq == -INFINITY) ? 0.f : exp2f(mq - mx);
+            float den = wq * lq;
+            for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off);
+            // weighted sum of the parts' outputs, parts in index order, 8 loads in flight
+            float num[D / 64];
 #pragma unroll
             for (int e = 0; e < D / 64; ++e) num[e] = 0.f;
-            for (int p = 0; p < np; ++p)
-                for (int hf = 0; hf < 2; ++hf) {
-                    size_t row = slot_index(first + p, head, hf) * a.Mpad + m;
-                    float mp = ld_exchange1(a.ml_part + row * 2);
-                    float w = (mp == -INFINITY) ? 0.f : exp2f(mp - mx);
-                    den += w * ld_exchange1(a.ml_part + row * 2 + 1);
+            for (int q0 = 0; q0 < np2; q0 += 8) {
+                float t[8][D / 64], w8[8];
 #pragma unroll
-                    for (int e = 0; e < D / 64; ++e)
-                        num[e] += w * ld_exchange1(a.o_part + row * D + e * 64 + lane);
+                for (int q = 0; q < 8; ++q) {
+                    int qq = min(q0 + q, np2 - 1);
+                    size_t row = (size_t)__shfl((long long)rowq, qq);
+                    w8[q] = (q0 + q < np2) ? __shfl(wq, qq) : 0.f;
+#pragma unroll
+                    for (int e = 0; e < D / 64; ++e) t[q][e] = a.o_part[row * D + e * 64 + lane];
                 }
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+#pragma unroll
+                    for (int e = 0; e < D / 64; ++e) num[e] += w8[q] * t[q][e];
+            }
 #pragma unroll
             for (int e = 0; e < D / 64; ++e)
                 out[((size_t)m * nh + head) * D + e * 64 + lane] = (half_t)(num[e] / den);
@@ -684,6 +747,11 @@ __global__ __launch_bounds__(kFT) void k_fused(const FusedArgs a)
     cx.nbar = 0;
     cx.s_status = (uint32_t*)lds;      // first 16 bytes of LDS: barrier status hand-over
     cx.lds = lds + 16;
+    // The exchange of partial results relies on workgroup i running on XCD i % 8.
+    if (G % 8 == 0 && threadIdx.x == 0) {
+        unsigned xcc = __builtin_amdgcn_s_getreg(20 | (31 << 11)) & 15u;   // HW_REG_XCC_ID
+        if (xcc != (unsigned)(i % 8)) atomicCAS(a.sync + kSyncStatus, 0u, 3u);
+    }
 
     // The step as a flat list of phases, decoded here so that each phase routine has a
     // single (inlined) call site and the argument block stays in scalar registers.
@@ -865,8 +933,11 @@ ghd_status launch_fused(const FusedArgs& a, hipStream_t st)
 }
 
 // ---- setup kernel ------------------------------------------------------------
-// One workgroup per 16-column tile of the residual stream (blockIdx.x >= 1) plus
-// block 0 for the tree tables and the sync block.
+// Block 0: tree tables (depth, ancestor masks, rotary table).  Blocks 1..kZeroBlocks:
+// zero the sync block.  Further blocks (whole-step mode only): one per 16-column tile of
+// the residual stream, writing x = widen(x_in) and the tile's sums of squares.
+constexpr int kZeroBlocks = 32;
+
 __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync,
                                                      const int32_t* __restrict__ parent, int M,
                                                      int Mpad, int kv_len, int d, float rope_base,
@@ -879,7 +950,6 @@ __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync
     if (blockIdx.x == 0) {
         __shared__ int32_t s_parent[GHD_MAX_M];
         __shared__ int32_t s_depth[GHD_MAX_M];
-        for (int i = tid; i < kSyncWords; i += 256) sync[i] = 0;
         if (!parent) return;
         if (tid < M) s_parent[tid] = parent[tid];
         __syncthreads();
@@ -908,8 +978,12 @@ __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync
         }
         return;
     }
+    if (blockIdx.x <= kZeroBlocks) {
+        for (int i = (blockIdx.x - 1) * 256 + tid; i < kSyncWords; i += kZeroBlocks * 256) sync[i] = 0;
+        return;
+    }
     // residual stream tiles: thread -> (row m, column within the 16-wide tile)
-    int tile = blockIdx.x - 1;
+    int tile = blockIdx.x - 1 - kZeroBlocks;
     for (int e = tid; e < Mpad * 16; e += 256) {
         int m = e >> 4, col = tile * 16 + (e & 15);
         float v = 0.f;
@@ -930,7 +1004,7 @@ ghd_status launch_fused_setup(uint32_t* sync, const int32_t* parent, int M, int 
                               float rope_base, uint64_t* mask, float2* rope, float* x,
                               const half_t* x_in16, int H, float* ss, hipStream_t st)
 {
-    int blocks = 1 + (ss ? H / 16 : 0);
+    int blocks = 1 + kZeroBlocks + (ss ? H / 16 : 0);
     hipLaunchKernelGGL(k_fused_setup, dim3(blocks), dim3(256), 0, st, sync, parent, M, Mpad, kv_len, d,
                        rope_base, mask, rope, x, x_in16, H, ss);
     return check_launch();
