@@ -74,8 +74,8 @@ struct Carver {
 
 struct Ws {
     uint32_t* sync;
-    float *part, *o_part, *ml_part, *x, *ss, *y32;
-    half_t *q16, *o16, *a16, *n16;
+    float *part, *o_part, *ml_part, *x, *ss;
+    half_t *q16, *o16, *a16, *xg16;
     float2* rope;
     uint64_t* mask;
     size_t bytes;
@@ -102,9 +102,7 @@ static Ws carve(void* ws, int what, int M, int H, int F, int d)
         w.q16 = cv.take<half_t>((size_t)M * H);
         w.o16 = cv.take<half_t>((size_t)M * H);
         w.a16 = cv.take<half_t>((size_t)M * F);
-        w.n16 = cv.take<half_t>((size_t)M * H);
-        size_t wide = (size_t)(3 * H > 2 * F ? 3 * H : 2 * F);
-        w.y32 = cv.take<float>((size_t)M * wide);
+        w.xg16 = cv.take<half_t>((size_t)M * H);
     }
     w.bytes = cv.off;
     return w;
@@ -149,6 +147,7 @@ static void fill_common(FusedArgs& a, const ghd_model_cfg* c, const Ws& w, int M
     a.q16 = w.q16;
     a.o16 = w.o16;
     a.a16 = w.a16;
+    a.xg16 = w.xg16;
     a.rope = w.rope;
     a.mask = w.mask;
 }
@@ -178,29 +177,47 @@ static void fill_layer(LayerPtrs& lp, const ghd_layer_weights* w, const ghd_kv* 
 
 // ---- the step as a sequence of single-phase launches ------------------------------
 // Every linear layer is one launch of the persistent GEMM kernel (all compute units,
-// equal contiguous shares of the packed weight stream, fp32 output [M, N]); the
-// element-wise work between them runs in small kernels on cache-resident data.
-static ghd_status step_linear(const Ws& w, const void* Wp, const half_t* x16, int64_t ldx, float* y,
-                              int64_t ldy, int M, int N, int K, int cnt, uint32_t epoch,
-                              hipStream_t st)
+// equal contiguous shares of the packed weight stream).  The layer's element-wise work
+// rides on those launches: RMSNorm is applied while the fp32 residual stream is staged as
+// the GEMM's x operand (from per-tile sums of squares left by the producer), and the
+// finishing workgroups rotate q/k and append K/V (QKV), apply SwiGLU (gate|up), or add
+// into the residual stream and leave the new sums of squares (output and down linears).
+// A layer is five launches: QKV, attention, output, gate|up, down.
+struct LinearCall {
+    const void* Wp;
+    int N, K, epi;
+    const half_t* in16;   // fp16 input [M, ldx]
+    int64_t ldx;
+    bool rscale;          // the input is xg16: apply the RMSNorm row factor in the epilogue
+    const half_t* gnext;  // EPI_RESID: gain of the norm that follows, or nullptr
+    void* out;
+    int64_t ldo;
+    const ghd_kv* kv;     // EPI_QKV
+    int cnt;
+    uint32_t epoch;
+};
+
+static ghd_status step_linear(const ghd_model_cfg* c, const Ws& w, float* x, int M, int kv_len,
+                              const LinearCall& lc, hipStream_t st)
 {
     FusedArgs a = {};
+    fill_common(a, c, w, M, kv_len);
+    a.x = x;
     a.mode = MODE_LINEAR;
-    a.M = M;
-    a.Mpad = mpad_of(M);
-    a.d = 128;
-    a.sync = w.sync;
-    a.part = w.part;
-    a.lin_W = (const half8*)Wp;
-    a.lin_x = x16;
-    a.lin_y = y;
-    a.lin_N = N;
-    a.lin_K = K;
-    a.lin_f16 = 0;
-    a.lin_cnt = cnt;
-    a.lin_epoch = epoch;
-    a.lin_ldx = ldx;
-    a.lin_ldy = ldy;
+    a.lin_W = (const half8*)lc.Wp;
+    a.lin_N = lc.N;
+    a.lin_K = lc.K;
+    a.lin_epi = lc.epi;
+    a.lin_x = lc.in16;
+    a.lin_ldx = lc.ldx;
+    a.lin_rscale = lc.rscale;
+    a.lin_gnext = lc.gnext;
+    a.lin_y = lc.out;
+    a.lin_ldy = lc.ldo;
+    a.lin_kc = lc.kv ? (half_t*)lc.kv->k : nullptr;
+    a.lin_vc = lc.kv ? (half_t*)lc.kv->v : nullptr;
+    a.lin_cnt = lc.cnt;
+    a.lin_epoch = lc.epoch;
     return timed_fused(a, st);
 }
 
@@ -208,20 +225,8 @@ static ghd_status step_attention(const ghd_model_cfg* c, const Ws& w, const ghd_
                                  int kv_len, uint32_t epoch, hipStream_t st)
 {
     FusedArgs a = {};
+    fill_common(a, c, w, M, kv_len);
     a.mode = MODE_ATTN;
-    a.M = M;
-    a.Mpad = mpad_of(M);
-    a.kv_len = kv_len;
-    a.nh = c->nh;
-    a.d = c->d;
-    a.H = c->H;
-    a.stride_head = (int64_t)c->kv_capacity * c->d;
-    a.stride_tok = c->d;
-    a.scale_log2e = 1.4426950408889634f / sqrtf((float)c->d);
-    a.sync = w.sync;
-    a.o_part = w.o_part;
-    a.ml_part = w.ml_part;
-    a.mask = w.mask;
     a.att_q = w.q16;
     a.att_k = (const half_t*)kv->k;
     a.att_v = (const half_t*)kv->v;
@@ -230,30 +235,24 @@ static ghd_status step_attention(const ghd_model_cfg* c, const Ws& w, const ghd_
     return timed_fused(a, st);
 }
 
-// One layer with n16 = rmsnorm(x) * g_attn already in w.n16.  On return x holds the
-// layer's output and, if next_g is given, w.n16 = rmsnorm(x) * next_g.
+// One decoder layer on the residual stream x.  On entry (and again on return) w.ss holds
+// x's per-tile sums of squares and w.xg16 = fp16(x * g / 16) for the gain of the norm that
+// comes next: g_attn of this layer on entry, next_g on return (skipped if next_g is null).
 static ghd_status run_layer(const ghd_model_cfg* c, const ghd_layer_weights* lw, const ghd_kv* kv,
                             float* x, int M, int kv_len, const Ws& w, const half_t* next_g,
                             uint32_t layer, hipStream_t st)
 {
     const int H = c->H, F = c->F;
-    const int64_t stride_head = (int64_t)c->kv_capacity * c->d, stride_tok = c->d;
     ghd_status s;
-    // MHA block: QKV linear, rotate + append, tree attention, output linear
-    if ((s = step_linear(w, lw->Wqkv, w.n16, H, w.y32, 3 * H, M, 3 * H, H, kCntQkv, layer, st))) return s;
-    if ((s = launch_qkv_epilogue(w.y32, 1, 3 * H, w.rope, w.q16, (half_t*)kv->k, (half_t*)kv->v, M,
-                                 c->nh, c->d, kv_len, stride_head, stride_tok, st)))
-        return s;
+    LinearCall qkv = {lw->Wqkv, 3 * H, H, EPI_QKV, w.xg16, H, true, nullptr, nullptr, 0, kv, kCntQkv, layer};
+    if ((s = step_linear(c, w, x, M, kv_len, qkv, st))) return s;
     if ((s = step_attention(c, w, kv, M, kv_len, layer, st))) return s;
-    if ((s = step_linear(w, lw->Wo, w.o16, H, w.y32, H, M, H, H, kCntWo, layer, st))) return s;
-    if ((s = launch_residual_norm(x, nullptr, w.y32, 1, H, (const half_t*)lw->g_ffn, w.n16, M, H,
-                                  c->rms_eps, st)))
-        return s;
-    // MLP block: gate|up linear + SwiGLU, down linear
-    if ((s = step_linear(w, lw->Wgu, w.n16, H, w.y32, 2 * F, M, 2 * F, H, kCntGu, layer, st))) return s;
-    if ((s = launch_swiglu(w.y32, 1, 2 * F, w.a16, M, F, st))) return s;
-    if ((s = step_linear(w, lw->Wdown, w.a16, F, w.y32, H, M, H, F, kCntDown, layer, st))) return s;
-    return launch_residual_norm(x, nullptr, w.y32, 1, H, next_g, w.n16, M, H, c->rms_eps, st);
+    LinearCall wo = {lw->Wo, H, H, EPI_RESID, w.o16, H, false, (const half_t*)lw->g_ffn, x, H, nullptr, kCntWo, layer};
+    if ((s = step_linear(c, w, x, M, kv_len, wo, st))) return s;
+    LinearCall gu = {lw->Wgu, 2 * F, H, EPI_SWIGLU, w.xg16, H, true, nullptr, w.a16, F, nullptr, kCntGu, layer};
+    if ((s = step_linear(c, w, x, M, kv_len, gu, st))) return s;
+    LinearCall down = {lw->Wdown, H, F, EPI_RESID, w.a16, F, false, next_g, x, H, nullptr, kCntDown, layer};
+    return step_linear(c, w, x, M, kv_len, down, st);
 }
 
 }  // namespace ghd
@@ -300,7 +299,7 @@ ghd_status ghd_tree_mask(const int32_t* parent_dev, int M, uint64_t* mask_dev, v
     if (!aligned16(ws)) return GHD_ERR_ALIGN;
     if (ws_bytes < ghd_tree_mask_workspace_bytes()) return GHD_ERR_WORKSPACE;
     return launch_fused_setup((uint32_t*)ws, parent_dev, M, mpad_of(M), 0, 0, 1.f, mask_dev, nullptr,
-                              nullptr, nullptr, 0, nullptr, (hipStream_t)stream);
+                              nullptr, nullptr, 0, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
 size_t ghd_packed_weight_bytes(int N, int K)
@@ -342,7 +341,7 @@ ghd_status ghd_linear_skinny(void* y, const void* x, const void* Wp, int M, int 
     hipStream_t st = (hipStream_t)stream;
     Ws w = carve(ws, 1, M, 0, 0, 0);
     ghd_status s = launch_fused_setup(w.sync, nullptr, M, mpad_of(M), 0, 0, 1.f, nullptr, nullptr,
-                                      nullptr, nullptr, 0, nullptr, st);
+                                      nullptr, nullptr, 0, nullptr, nullptr, nullptr, st);
     if (s) return s;
     FusedArgs a = {};
     a.mode = MODE_LINEAR;
@@ -356,7 +355,7 @@ ghd_status ghd_linear_skinny(void* y, const void* x, const void* Wp, int M, int 
     a.lin_y = y;
     a.lin_N = N;
     a.lin_K = K;
-    a.lin_f16 = flags == GHD_OUT_F16;
+    a.lin_epi = flags == GHD_OUT_F16 ? EPI_STORE_F16 : EPI_STORE_F32;
     a.lin_cnt = kCntLm;
     a.lin_epoch = 0;
     a.lin_ldx = ldx;
@@ -388,7 +387,7 @@ ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, con
     hipStream_t st = (hipStream_t)stream;
     Ws w = carve(ws, 2, M, 0, 0, d);
     ghd_status s = launch_fused_setup(w.sync, parent_dev, M, mpad_of(M), kv_len, d, 1.f, w.mask,
-                                      nullptr, nullptr, nullptr, 0, nullptr, st);
+                                      nullptr, nullptr, nullptr, 0, nullptr, nullptr, nullptr, st);
     if (s) return s;
     FusedArgs a = {};
     a.mode = MODE_ATTN;
@@ -432,12 +431,10 @@ ghd_status ghd_verify_layer(const ghd_model_cfg* cfg, const ghd_layer_weights* w
     if (ws_bytes < ghd_workspace_bytes(cfg, M, kv_len)) return GHD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     Ws lw = carve(ws, 0, M, cfg->H, cfg->F, cfg->d);
+    // the caller's x is the residual stream itself; the set-up leaves its sums of squares
     if ((s = launch_fused_setup(lw.sync, parent_dev, M, mpad_of(M), kv_len, cfg->d, cfg->rope_base,
-                                lw.mask, lw.rope, nullptr, nullptr, 0, nullptr, st)))
-        return s;
-    // the caller's x is the residual stream itself
-    if ((s = launch_residual_norm(x, nullptr, nullptr, 0, 0, (const half_t*)w->g_attn, lw.n16, M,
-                                  cfg->H, cfg->rms_eps, st)))
+                                lw.mask, lw.rope, x, nullptr, cfg->H, lw.ss, (const half_t*)w->g_attn,
+                                lw.xg16, st)))
         return s;
     return run_layer(cfg, w, kv, x, M, kv_len, lw, nullptr, 0, st);
 }
@@ -462,13 +459,10 @@ ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* l
     hipStream_t st = (hipStream_t)stream;
     Ws lw = carve(ws, 0, M, cfg->H, cfg->F, cfg->d);
     const int H = cfg->H;
+    // x = widen(x_in) with its sums of squares
     if ((s = launch_fused_setup(lw.sync, parent_dev, M, mpad_of(M), kv_len, cfg->d, cfg->rope_base,
-                                lw.mask, lw.rope, nullptr, nullptr, 0, nullptr, st)))
-        return s;
-    // x = widen(x_in); n16 = rmsnorm(x) * g_attn of layer 0
-    if ((s = launch_residual_norm(lw.x, (const half_t*)x_in, nullptr, 0, 0,
-                                  (const half_t*)layers_host[0].g_attn, lw.n16, M, H, cfg->rms_eps,
-                                  st)))
+                                lw.mask, lw.rope, lw.x, (const half_t*)x_in, H, lw.ss,
+                                (const half_t*)layers_host[0].g_attn, lw.xg16, st)))
         return s;
     for (int l = 0; l < cfg->L; ++l) {
         const half_t* next_g = (const half_t*)(l + 1 < cfg->L ? layers_host[l + 1].g_attn : g_final);
@@ -482,7 +476,9 @@ ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* l
         if (e != hipSuccess) return hip_fail(e);
     }
     // LM head on the final norm, straight into the caller's logits
-    return step_linear(lw, Wlm, lw.n16, H, logits, cfg->V, M, cfg->V, H, kCntLm, 0, st);
+    LinearCall lm = {Wlm, cfg->V, H, EPI_STORE_F32, lw.xg16, H, true, nullptr,
+                     logits, cfg->V, nullptr, kCntLm, 0};
+    return step_linear(cfg, lw, lw.x, M, kv_len, lm, st);
 }
 
 ghd_status ghd_step_status(const void* ws, int32_t* status_host, void* stream)

@@ -53,6 +53,7 @@ struct FusedArgs {
     float* o_part;         // attention partial slots: [G][2][2][Mpad][d]
     float* ml_part;        // [G][2][2][Mpad][2]
     float* x;              // residual stream [M, H] fp32
+    half_t* xg16;          // fp16(x * gain of the next RMSNorm / 16) [M, H]: GEMM input
     float* ss;             // sums of squares per 16-column tile: [H/16][Mpad]
     half_t* q16;           // [M, H]
     half_t* o16;           // [M, H]
@@ -67,7 +68,10 @@ struct FusedArgs {
     const half8* lin_W;
     const half_t* lin_x;
     void* lin_y;
-    int lin_N, lin_K, lin_f16;
+    int lin_N, lin_K, lin_epi;
+    int lin_rscale;        // the input is xg16: scale output row m by the RMSNorm factor of x[m]
+    const half_t* lin_gnext;   // EPI_RESID: gain of the norm that follows (xg16 is rewritten)
+    half_t *lin_kc, *lin_vc;   // EPI_QKV: the layer's cache
     int lin_cnt;           // which group-counter array of the sync block this call uses
     uint32_t lin_epoch;    // how often that array was used since it was zeroed
     uint32_t att_epoch;    // same for the attention head counters
@@ -81,23 +85,11 @@ ghd_status launch_fused(const FusedArgs& a, hipStream_t st);
 int fused_grid_size();
 
 // setup kernel: zero the sync block, tree tables, and (optionally) the residual stream
-// with its sums of squares
+// with its sums of squares and its gain-scaled fp16 image
 ghd_status launch_fused_setup(uint32_t* sync, const int32_t* parent, int M, int Mpad, int kv_len, int d,
                               float rope_base, uint64_t* mask, float2* rope, float* x,
-                              const half_t* x_in16, int H, float* ss, hipStream_t st);
-
-// element-wise kernels (elementwise.hip)
-// x_new = (x_old | widen(x_in16)) + y32 (if given);  n16 = fp16(rmsnorm(x_new) * g) (if g)
-ghd_status launch_residual_norm(float* x, const half_t* x_in16, const float* part, int S, int64_t ld,
-                                const half_t* g, half_t* n16, int M, int H, float eps,
-                                hipStream_t st);
-// rotate q and k of the fused QKV output, write q16 [M,H] and cache rows kv_len+m
-ghd_status launch_qkv_epilogue(const float* part, int S, int64_t ld, const float2* rope, half_t* q16,
-                               half_t* kc, half_t* vc, int M, int nh, int d, int kv_len,
-                               int64_t stride_head, int64_t stride_tok, hipStream_t st);
-// a16[m,f] = fp16(silu(gate) * up) from the [M, 2F] output of the gate|up linear
-ghd_status launch_swiglu(const float* part, int S, int64_t ld, half_t* a16, int M, int F,
-                         hipStream_t st);
+                              const half_t* x_in16, int H, float* ss, const half_t* gain,
+                              half_t* xg16, hipStream_t st);
 
 ghd_status launch_pack2(void* dst, const void* src, int N, int K, int kind, int d, hipStream_t st);
 size_t packed_bytes2(int N, int K);

@@ -23,8 +23,11 @@
 // post-processes its own share of the group's fragments in a fixed order, so
 // results do not depend on timing.  The post-processing is the layer's
 // element-wise work: residual add + sums of squares for the next RMSNorm,
-// rotary embedding + KV append, SwiGLU.  RMSNorm itself is applied while x is
-// staged (x * rsqrt(mean x^2 + eps) * g, rounded to fp16).
+// rotary embedding + KV append, SwiGLU.  RMSNorm is split around the GEMM that
+// consumes it: the producer of the residual stream also leaves fp16(x * g / 16),
+// which is staged like any fp16 input, and the row factor 16 * rsqrt(mean x^2 + eps)
+// (a per-row scalar, so it commutes with the contraction) is applied to the fp32
+// sums in the epilogue.  The 1/16 keeps x * g inside the fp16 range.
 //
 // Tree attention.  The (head, 64-key tile) pairs form the same kind of linear
 // sequence.  A workgroup streams its tiles through LDS; wavefronts 0-3 take the
@@ -48,10 +51,10 @@ struct GemmOp {
     int N, K;            // logical output features (packed order) and input features
     int ngroups, ncpg;   // row groups, chunks per group
     int epi;
-    const half_t* in16;  // fp16 input [M, ld_in]   (gain == nullptr)
+    const half_t* in16;  // fp16 input [M, ld_in]
     int64_t ld_in;
-    const float* in32;   // fp32 input [M, K] to be RMS-normalised (gain != nullptr)
-    const half_t* gain;
+    bool rscale;         // input is xg16: multiply output row m by 16 * rsqrt(mean x[m]^2 + eps)
+    const half_t* gnext; // RESID: gain of the next RMSNorm (xg16 is rewritten), or nullptr
     void* out;           // STORE: y;  RESID: x;  SWIGLU: a16
     int64_t ldo;
     half_t *kc, *vc;     // QKV: this layer's cache
@@ -171,10 +174,13 @@ __device__ __forceinline__ bool grid_barrier(const FusedArgs& a, Ctx& cx)
 // ---------------------------------------------------------------------------
 // epilogue of one 16x16 output fragment: lane (c, g4) holds y[m][n0 .. n0+3]
 // ---------------------------------------------------------------------------
+constexpr float kXgScale = 0.0625f;   // xg16 = fp16(x * g * kXgScale)
+
 __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, floatx4 v, int m, int n0,
-                                int lane)
+                                int lane, const float* s_rinv)
 {
     const bool mok = m < a.M;
+    if (op.rscale) v *= s_rinv[m];
     if (op.epi == EPI_STORE_F32) {
         if (!mok) return;
         float* o = (float*)op.out + (size_t)m * op.ldo + n0;
@@ -195,6 +201,12 @@ __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, f
             floatx4 xn = *xp + v;
             *xp = xn;
             s = xn[0] * xn[0] + xn[1] * xn[1] + xn[2] * xn[2] + xn[3] * xn[3];
+            if (op.gnext) {
+                half4 gv = *(const half4*)(op.gnext + n0), o;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[r] = (half_t)(xn[r] * (float)gv[r] * kXgScale);
+                *(half4*)(a.xg16 + (size_t)m * op.ldo + n0) = o;
+            }
         }
         s += __shfl_xor(s, 16);
         s += __shfl_xor(s, 32);
@@ -248,7 +260,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     const int c = lane & 15, g4 = lane >> 4;
     char* xs = cx.lds;                             // 2 * CHUNK
     float* s_rinv = (float*)(cx.lds + 2 * CHUNK);  // Mpad floats
-    float* s_tmp = s_rinv + 128;                   // 512 floats
+    float* s_tmp = s_rinv + 128;                   // 1024 floats
 
     const Share sh = make_share(op.ngroups, op.ncpg, cx.j, cx.G);
     const long c0 = sh.c0, c1 = sh.c1;
@@ -272,19 +284,35 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
 
     if (barrier_first && !grid_barrier(a, cx)) return false;
 
-    // ---- RMSNorm scale per row from the per-tile sums of squares
-    if (op.gain) {
+    // ---- RMSNorm factor per row from the per-tile sums of squares ss[tile][Mpad]:
+    //      thread (rq, part) adds 4 rows of every P-th tile, lanes of a wavefront that share
+    //      rq are combined by shuffles, the 8 wavefronts through LDS; fixed order throughout
+    if (op.rscale) {
         const int n_ss = op.K >> 4;
-        const int tpr = kFT / a.Mpad;              // threads per row
-        int m = tid % a.Mpad, part = tid / a.Mpad;
-        float s = 0.f;
-        for (int t = part; t < n_ss; t += tpr) s += a.ss[(size_t)t * a.Mpad + m];
-        s_tmp[tid] = s;
+        const int RQ = a.Mpad >> 2, P = kFT / RQ;
+        const int rq = tid % RQ, part = tid / RQ;
+        floatx4 s4 = {0.f, 0.f, 0.f, 0.f};
+        for (int t0 = part; t0 < n_ss; t0 += 8 * P) {
+            floatx4 t[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                int tl = t0 + q * P;
+                t[q] = *(const floatx4*)(a.ss + (size_t)min(tl, n_ss - 1) * a.Mpad + rq * 4);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (t0 + q * P < n_ss) s4 += t[q];
+        }
+        for (int off = RQ; off < 64; off <<= 1) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s4[r] += __shfl_xor(s4[r], off);
+        }
+        if (lane < RQ) *(floatx4*)(s_tmp + (wave * RQ + lane) * 4) = s4;
         __syncthreads();
         if (tid < a.Mpad) {
             float tot = 0.f;
-            for (int p = 0; p < tpr; ++p) tot += s_tmp[p * a.Mpad + tid];
-            s_rinv[tid] = 1.0f / sqrtf(tot / (float)op.K + a.eps);
+            for (int w = 0; w < 8; ++w) tot += s_tmp[(w * RQ + (tid >> 2)) * 4 + (tid & 3)];
+            s_rinv[tid] = (1.0f / kXgScale) / sqrtf(tot / (float)op.K + a.eps);
         }
         __syncthreads();
     }
@@ -311,23 +339,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         for (int i = 0; i < PPT; ++i) {
             int k = kbase + p_koff[i];
             bool ok = p_ok[i] && k < op.K && cu < c1;
-            half8 v = zero8;
-            if (ok) {
-                if (op.gain) {
-                    const float* src = op.in32 + (size_t)p_row[i] * op.K + k;
-                    floatx4 lo = *(const floatx4*)src, hi = *(const floatx4*)(src + 4);
-                    half8 gv = *(const half8*)(op.gain + k);
-                    float r = s_rinv[p_row[i]];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        v[e] = (half_t)(lo[e] * r * (float)gv[e]);
-                        v[e + 4] = (half_t)(hi[e] * r * (float)gv[e + 4]);
-                    }
-                } else {
-                    v = *(const half8*)(op.in16 + (size_t)p_row[i] * op.ld_in + k);
-                }
-            }
-            xr[i] = v;
+            xr[i] = ok ? *(const half8*)(op.in16 + (size_t)p_row[i] * op.ld_in + k) : zero8;
         }
     };
     auto x_store = [&](int buf) {
@@ -364,7 +376,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
 #pragma unroll
                 for (int b = 0; b < MT; ++b)
                     epilogue(a, op, acc[t][b], b * 16 + c, (grp * kTG + wave * 2 + t) * 16 + g4 * 4,
-                             lane);
+                             lane, s_rinv);
         } else {
             float* slot = slot_of(cx.j, grp);
 #pragma unroll
@@ -438,7 +450,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
                         if (p0 + q < np) v += t[q];
                 }
                 int tile = f / MT, b = f % MT;
-                epilogue(a, op, v, b * 16 + c, (grp * kTG + tile) * 16 + g4 * 4, lane);
+                epilogue(a, op, v, b * 16 + c, (grp * kTG + tile) * 16 + g4 * 4, lane, s_rinv);
             }
         }
     }
@@ -776,8 +788,8 @@ __global__ __launch_bounds__(kFT) void k_fused(const FusedArgs a)
         GemmOp op;
         op.in16 = nullptr;
         op.ld_in = 0;
-        op.in32 = nullptr;
-        op.gain = nullptr;
+        op.rscale = false;
+        op.gnext = nullptr;
         op.out = nullptr;
         op.ldo = 0;
         op.kc = nullptr;
@@ -787,9 +799,13 @@ __global__ __launch_bounds__(kFT) void k_fused(const FusedArgs a)
             op.W = a.lin_W;
             op.N = a.lin_N;
             op.K = a.lin_K;
-            op.epi = a.lin_f16 ? EPI_STORE_F16 : EPI_STORE_F32;
+            op.epi = a.lin_epi;
             op.in16 = a.lin_x;
             op.ld_in = a.lin_ldx;
+            op.rscale = a.lin_rscale != 0;
+            op.gnext = a.lin_gnext;
+            op.kc = a.lin_kc;
+            op.vc = a.lin_vc;
             op.out = a.lin_y;
             op.ldo = a.lin_ldy;
             op.cnt = a.sync + a.lin_cnt;
@@ -799,8 +815,9 @@ __global__ __launch_bounds__(kFT) void k_fused(const FusedArgs a)
             op.N = a.V;
             op.K = H;
             op.epi = EPI_STORE_F32;
-            op.in32 = a.x;
-            op.gain = a.g_final;
+            op.in16 = a.xg16;
+            op.ld_in = H;
+            op.rscale = true;
             op.out = a.logits;
             op.ldo = a.V;
             op.cnt = a.sync + kCntLm;
@@ -810,8 +827,9 @@ __global__ __launch_bounds__(kFT) void k_fused(const FusedArgs a)
             op.N = 3 * H;
             op.K = H;
             op.epi = EPI_QKV;
-            op.in32 = a.x;
-            op.gain = a.layer[l].g_attn;
+            op.in16 = a.xg16;
+            op.ld_in = H;
+            op.rscale = true;
             op.kc = a.layer[l].kc;
             op.vc = a.layer[l].vc;
             op.cnt = a.sync + kCntQkv;
@@ -824,14 +842,16 @@ __global__ __launch_bounds__(kFT) void k_fused(const FusedArgs a)
             op.ld_in = H;
             op.out = a.x;
             op.ldo = H;
+            op.gnext = a.layer[l].g_ffn;
             op.cnt = a.sync + kCntWo;
         } else if (kind == 3) {
             op.W = a.layer[l].Wgu;
             op.N = 2 * F;
             op.K = H;
             op.epi = EPI_SWIGLU;
-            op.in32 = a.x;
-            op.gain = a.layer[l].g_ffn;
+            op.in16 = a.xg16;
+            op.ld_in = H;
+            op.rscale = true;
             op.out = a.a16;
             op.ldo = F;
             op.cnt = a.sync + kCntGu;
@@ -844,6 +864,7 @@ __global__ __launch_bounds__(kFT) void k_fused(const FusedArgs a)
             op.ld_in = F;
             op.out = a.x;
             op.ldo = H;
+            op.gnext = (l + 1 < a.L) ? a.layer[l + 1].g_attn : (MODE == MODE_STACK ? a.g_final : nullptr);
             op.cnt = a.sync + kCntDown;
         }
         op.ngroups = (op.N + kGroupRows - 1) / kGroupRows;
@@ -872,7 +893,7 @@ int fused_grid_size()
 template <int MT, int D>
 static size_t fused_lds_bytes()
 {
-    size_t gemm = 2 * (size_t)kCH * MT * kFrag + (128 + 512) * sizeof(float);
+    size_t gemm = 2 * (size_t)kCH * MT * kFrag + (128 + 1024) * sizeof(float);
     size_t attn = sizeof(AttnLds<D>);
     return 16 + (gemm > attn ? gemm : attn);
 }
@@ -934,8 +955,8 @@ ghd_status launch_fused(const FusedArgs& a, hipStream_t st)
 
 // ---- setup kernel ------------------------------------------------------------
 // Block 0: tree tables (depth, ancestor masks, rotary table).  Blocks 1..kZeroBlocks:
-// zero the sync block.  Further blocks (whole-step mode only): one per 16-column tile of
-// the residual stream, writing x = widen(x_in) and the tile's sums of squares.
+// zero the sync block.  Further blocks: one per 16-column tile of the residual stream,
+// writing x = widen(x_in), the tile's sums of squares and the gain-scaled fp16 image.
 constexpr int kZeroBlocks = 32;
 
 __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync,
@@ -944,7 +965,9 @@ __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync
                                                      uint64_t* __restrict__ mask,
                                                      float2* __restrict__ rope, float* __restrict__ x,
                                                      const half_t* __restrict__ x_in16, int H,
-                                                     float* __restrict__ ss)
+                                                     float* __restrict__ ss,
+                                                     const half_t* __restrict__ gain,
+                                                     half_t* __restrict__ xg16)
 {
     int tid = threadIdx.x;
     if (blockIdx.x == 0) {
@@ -990,6 +1013,7 @@ __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync
         if (m < M) {
             v = x_in16 ? (float)x_in16[(size_t)m * H + col] : x[(size_t)m * H + col];
             if (x_in16) x[(size_t)m * H + col] = v;
+            if (xg16) xg16[(size_t)m * H + col] = (half_t)(v * (float)gain[col] * kXgScale);
         }
         float s = v * v;
         s += __shfl_xor(s, 1);
@@ -1002,11 +1026,12 @@ __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync
 
 ghd_status launch_fused_setup(uint32_t* sync, const int32_t* parent, int M, int Mpad, int kv_len, int d,
                               float rope_base, uint64_t* mask, float2* rope, float* x,
-                              const half_t* x_in16, int H, float* ss, hipStream_t st)
+                              const half_t* x_in16, int H, float* ss, const half_t* gain,
+                              half_t* xg16, hipStream_t st)
 {
     int blocks = 1 + kZeroBlocks + (ss ? H / 16 : 0);
     hipLaunchKernelGGL(k_fused_setup, dim3(blocks), dim3(256), 0, st, sync, parent, M, Mpad, kv_len, d,
-                       rope_base, mask, rope, x, x_in16, H, ss);
+                       rope_base, mask, rope, x, x_in16, H, ss, gain, xg16);
     return check_launch();
 }
 

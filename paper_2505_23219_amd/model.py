@@ -14,7 +14,8 @@ MATRICES = ("Wqkv", "Wo", "Wgu", "Wdown")
 
 def upload_layer(w: Dict[str, torch.Tensor], head_dim: int, device="cuda") -> Dict[str, torch.Tensor]:
     """fp16 layer weights (row-major, any device) -> gains + packed matrices on the GPU."""
-    kinds = {}     # every matrix in natural row order (GHD_PACK_PLAIN)
+    # the row orders ghd_verify_layer / ghd_verify_stack expect
+    kinds = {"Wqkv": B.GHD_PACK_QKV, "Wgu": B.GHD_PACK_GATE_UP}
     out = {}
     for name, t in w.items():
         t = t.to(device)
