@@ -267,56 +267,19 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
     // ---- weight stream: linear in the chunk index
+    // kWR chunks of weights are in flight per wavefront (registers); slot (cu - c0) % kWR
     const half8* wbase = op.W + (size_t)(wave * 2) * 64 + lane;
-    half8 wb[kCH][2];
-    auto w_fetch = [&](int s, long cu) {
-        if (cu < c1) {
-            const half8* p = wbase + ((size_t)cu * kCH + s) * (kTG * 64);
-            wb[s][0] = p[0];
-            wb[s][1] = p[64];
-        } else {
-            wb[s][0] = zero8;
-            wb[s][1] = zero8;
-        }
+    constexpr int kWR = (MT <= 2) ? 2 : 1;
+    half8 wb[kWR][kCH][2];
+    // Loads inside the streaming loop are unconditional (addresses are clamped instead):
+    // a load that may or may not be issued makes the number of younger loads unknown, and
+    // every wait for an older one then has to drain the whole queue.
+    auto w_fetch = [&](auto slot, int s, long cu) {
+        constexpr int R = decltype(slot)::value;
+        const half8* p = wbase + ((size_t)cu * kCH + s) * (kTG * 64);
+        wb[R][s][0] = p[0];
+        wb[R][s][1] = p[64];
     };
-#pragma unroll
-    for (int s = 0; s < kCH; ++s) w_fetch(s, c0);
-
-    if (barrier_first && !grid_barrier(a, cx)) return false;
-
-    // ---- RMSNorm factor per row from the per-tile sums of squares ss[tile][Mpad]:
-    //      thread (rq, part) adds 4 rows of every P-th tile, lanes of a wavefront that share
-    //      rq are combined by shuffles, the 8 wavefronts through LDS; fixed order throughout
-    if (op.rscale) {
-        const int n_ss = op.K >> 4;
-        const int RQ = a.Mpad >> 2, P = kFT / RQ;
-        const int rq = tid % RQ, part = tid / RQ;
-        floatx4 s4 = {0.f, 0.f, 0.f, 0.f};
-        for (int t0 = part; t0 < n_ss; t0 += 8 * P) {
-            floatx4 t[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                int tl = t0 + q * P;
-                t[q] = *(const floatx4*)(a.ss + (size_t)min(tl, n_ss - 1) * a.Mpad + rq * 4);
-            }
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                if (t0 + q * P < n_ss) s4 += t[q];
-        }
-        for (int off = RQ; off < 64; off <<= 1) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) s4[r] += __shfl_xor(s4[r], off);
-        }
-        if (lane < RQ) *(floatx4*)(s_tmp + (wave * RQ + lane) * 4) = s4;
-        __syncthreads();
-        if (tid < a.Mpad) {
-            float tot = 0.f;
-            for (int w = 0; w < 8; ++w) tot += s_tmp[(w * RQ + (tid >> 2)) * 4 + (tid & 3)];
-            s_rinv[tid] = (1.0f / kXgScale) / sqrtf(tot / (float)op.K + a.eps);
-        }
-        __syncthreads();
-    }
-
     // ---- x staging: piece p -> fragment f = p/64 (k-step s = f/MT, row tile f%MT),
     //      row (p/4)%16, k group p%4
     int p_row[PPT], p_koff[PPT], p_dst[PPT];
@@ -333,20 +296,73 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         p_dst[i] = f * kFrag + pg * 272 + pc * 16;
     }
     half8 xr[PPT];
+    bool xok[PPT];
     auto x_fetch = [&](long cu) {
-        int kbase = (int)(cu % op.ncpg) * kChunkCols;
+        int kbase = (int)(min(cu, c1 - 1) % op.ncpg) * kChunkCols;
 #pragma unroll
         for (int i = 0; i < PPT; ++i) {
             int k = kbase + p_koff[i];
-            bool ok = p_ok[i] && k < op.K && cu < c1;
-            xr[i] = ok ? *(const half8*)(op.in16 + (size_t)p_row[i] * op.ld_in + k) : zero8;
+            xok[i] = p_ok[i] && k < op.K;
+            xr[i] = *(const half8*)(op.in16 + (size_t)p_row[i] * op.ld_in + (xok[i] ? k : 0));
         }
     };
     auto x_store = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < PPT; ++i)
-            if (tid + i * kFT < PIECES) *(half8*)(xs + buf * CHUNK + p_dst[i]) = xr[i];
+            if (tid + i * kFT < PIECES) *(half8*)(xs + buf * CHUNK + p_dst[i]) = xok[i] ? xr[i] : zero8;
     };
+
+    // Loads return in issue order.  In a launch of its own the first x chunk is requested
+    // ahead of the weight ring so that staging does not wait behind the ring; after a grid
+    // barrier x does not exist yet, and the ring (which does not depend on it) goes first.
+    auto w_first = [&]() {
+        if (c0 >= c1) return;
+#pragma unroll
+        for (int s = 0; s < kCH; ++s) w_fetch(std::integral_constant<int, 0>{}, s, c0);
+        if constexpr (kWR == 2) {
+#pragma unroll
+            for (int s = 0; s < kCH; ++s) w_fetch(std::integral_constant<int, 1>{}, s, min(c0 + 1, c1 - 1));
+        }
+    };
+    if (barrier_first) w_first();
+    else if (c0 < c1) x_fetch(c0);
+    if (barrier_first && !grid_barrier(a, cx)) return false;
+
+    // ---- RMSNorm factor per row from the per-tile sums of squares ss[tile][Mpad]:
+    //      thread (rq, part) adds 4 rows of every P-th tile, lanes of a wavefront that share
+    //      rq are combined by shuffles, the 8 wavefronts through LDS; fixed order throughout
+    const int n_ss = op.K >> 4;
+    const int RQ = a.Mpad >> 2, P = kFT / RQ;
+    const int rq = tid % RQ, part = tid / RQ;
+    floatx4 sst[8];
+    auto ss_fetch = [&](int t0) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            sst[q] = *(const floatx4*)(a.ss + (size_t)min(t0 + q * P, n_ss - 1) * a.Mpad + rq * 4);
+    };
+    if (op.rscale) ss_fetch(part);
+    if (!barrier_first) w_first();     // the ring queues up behind x and the first ss batch
+    if (op.rscale) {
+        floatx4 s4 = {0.f, 0.f, 0.f, 0.f};
+        for (int t0 = part; t0 < n_ss; t0 += 8 * P) {
+            if (t0 != part) ss_fetch(t0);
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (t0 + q * P < n_ss) s4 += sst[q];
+        }
+        for (int off = RQ; off < 64; off <<= 1) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s4[r] += __shfl_xor(s4[r], off);
+        }
+        if (lane < RQ) *(floatx4*)(s_tmp + (wave * RQ + lane) * 4) = s4;
+        __syncthreads();
+        if (tid < a.Mpad) {
+            float tot = 0.f;
+            for (int w = 0; w < 8; ++w) tot += s_tmp[(w * RQ + (tid >> 2)) * 4 + (tid & 3)];
+            s_rinv[tid] = (1.0f / kXgScale) / sqrtf(tot / (float)op.K + a.eps);
+        }
+        __syncthreads();
+    }
 
     floatx4 acc[2][MT];
     auto acc_zero = [&]() {
@@ -391,17 +407,16 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     };
 
     if (c0 < c1) {
-        x_fetch(c0);
+        if (barrier_first) x_fetch(c0);
         x_store(0);
         x_fetch(c0 + 1);
         __syncthreads();
-        int cur = (int)(c0 / op.ncpg);
-        for (long cu = c0; cu < c1; ++cu) {
-            int grp = (int)(cu / op.ncpg);
-            if (grp != cur) {
-                flush(cur);
-                cur = grp;
-            }
+        // One chunk: 4 k-steps of MFMAs on ring slot R, each followed (FW) by the request
+        // for the same k-step kWR chunks ahead; then the next x chunk goes to LDS and the
+        // one after it is requested.  No branches: the wait counts stay exact.
+        auto chunk_step = [&](auto slot, auto fw, long cu) {
+            constexpr int R = decltype(slot)::value;
+            constexpr bool FW = decltype(fw)::value;
             const char* xb = xs + (int)((cu - c0) & 1) * CHUNK + g4 * 272 + c * 16;
 #pragma unroll
             for (int s = 0; s < kCH; ++s) {
@@ -412,17 +427,40 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
                 for (int t = 0; t < 2; ++t)
 #pragma unroll
                     for (int b = 0; b < MT; ++b)
-                        acc[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wb[s][t], xf[b], acc[t][b],
+                        acc[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wb[R][s][t], xf[b], acc[t][b],
                                                                           0, 0, 0);
-                w_fetch(s, cu + 1);
+                if constexpr (FW) w_fetch(slot, s, cu + kWR);
             }
-            if (cu + 1 < c1) {
-                x_store((int)((cu + 1 - c0) & 1));
-                x_fetch(cu + 2);
-            }
+            x_store((int)((cu + 1 - c0) & 1));
+            x_fetch(cu + 2);
             __syncthreads();
+        };
+        // chunks [b0, b1) of one row group; the first one uses ring slot P
+        auto span_impl = [&](auto par, auto fw, long b0, long b1) {
+            constexpr int P = (kWR == 2) ? decltype(par)::value : 0;
+            constexpr int Q = (kWR == 2) ? 1 - P : 0;
+            long cu = b0;
+            for (; cu + 2 <= b1; cu += 2) {
+                chunk_step(std::integral_constant<int, P>{}, fw, cu);
+                chunk_step(std::integral_constant<int, Q>{}, fw, cu + 1);
+            }
+            if (cu < b1) chunk_step(std::integral_constant<int, P>{}, fw, cu);
+        };
+        auto span = [&](auto fw, long b0, long b1) {
+            if (b0 >= b1) return;
+            if ((b0 - c0) & 1) span_impl(std::integral_constant<int, 1>{}, fw, b0, b1);
+            else span_impl(std::integral_constant<int, 0>{}, fw, b0, b1);
+        };
+        const long fend = c1 - kWR;     // chunks from here on have nothing left to prefetch
+        for (long cu = c0; cu < c1;) {
+            int grp = (int)(cu / op.ncpg);
+            long se = min(c1, (long)(grp + 1) * op.ncpg);
+            long mid = min(se, max(fend, cu));
+            span(std::true_type{}, cu, mid);
+            span(std::false_type{}, mid, se);
+            flush(grp);
+            cu = se;
         }
-        flush(cur);
 
         // ---- cooperative finish of the split groups this workgroup took part in
         int gfirst = (int)(c0 / op.ncpg), glast = (int)((c1 - 1) / op.ncpg);
