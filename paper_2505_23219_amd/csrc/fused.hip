@@ -277,8 +277,10 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     auto w_fetch = [&](auto slot, int s, long cu) {
         constexpr int R = decltype(slot)::value;
         const half8* p = wbase + ((size_t)cu * kCH + s) * (kTG * 64);
-        wb[R][s][0] = p[0];
-        wb[R][s][1] = p[64];
+        // streamed once: non-temporal, so the weights do not push x and the partial sums
+        // out of the L2
+        wb[R][s][0] = __builtin_nontemporal_load(p);
+        wb[R][s][1] = __builtin_nontemporal_load(p + 64);
     };
     // ---- x staging: piece p -> fragment f = p/64 (k-step s = f/MT, row tile f%MT),
     //      row (p/4)%16, k group p%4
