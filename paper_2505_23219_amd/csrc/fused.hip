@@ -538,8 +538,8 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
             int id = tid + kFT * i;
             int row = id / CPR, ch = id % CPR;
             int key = min(tile * 64 + row, committed_only ? a.kv_len - 1 : T - 1);
-            kreg[S][i] = *(const half8*)(kh_ + (size_t)key * a.stride_tok + ch * 8);
-            vreg[S][i] = *(const half8*)(vh_ + (size_t)key * a.stride_tok + ch * 8);
+            kreg[S][i] = __builtin_nontemporal_load((const half8*)(kh_ + (size_t)key * a.stride_tok + ch * 8));
+            vreg[S][i] = __builtin_nontemporal_load((const half8*)(vh_ + (size_t)key * a.stride_tok + ch * 8));
         }
     };
     auto store_tile = [&](auto set) {
@@ -629,12 +629,12 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
     if (u0 + 1 < u1) load_tile(std::integral_constant<int, 1>{}, u0 + 1, false);
     int cur = (int)(u0 / ntile);
     head_begin(cur);
-    auto do_tile = [&](auto set, long u) {
+    auto do_tile = [&](auto set, auto prefetch, long u) {
         int head = (int)(u / ntile), tile = (int)(u % ntile);
         __syncthreads();            // previous tile fully consumed
         store_tile(set);
         __syncthreads();
-        if (u + 2 < u1) load_tile(set, u + 2, false);
+        if constexpr (decltype(prefetch)::value) load_tile(set, u + 2, false);
         if (head != cur) {
             head_flush(cur);
             cur = head;
@@ -723,9 +723,29 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
         }
     
     };
-    for (long u = u0; u < u1; u += 2) {
-        do_tile(std::integral_constant<int, 0>{}, u);
-        if (u + 1 < u1) do_tile(std::integral_constant<int, 1>{}, u + 1);
+    // Tile u requests tile u + 2 while one exists; the loads of the steady-state loop are
+    // unconditional, so the wait before a tile is staged counts exactly the younger loads.
+    {
+        const std::integral_constant<int, 0> s0;
+        const std::integral_constant<int, 1> s1;
+        const std::true_type pf;
+        const std::false_type nopf;
+        long u = u0;
+        for (; u + 3 < u1; u += 2) {
+            do_tile(s0, pf, u);
+            do_tile(s1, pf, u + 1);
+        }
+        const int rest = (int)(u1 - u);
+        if (rest == 3) {
+            do_tile(s0, pf, u);
+            do_tile(s1, nopf, u + 1);
+            do_tile(s0, nopf, u + 2);
+        } else if (rest == 2) {
+            do_tile(s0, nopf, u);
+            do_tile(s1, nopf, u + 1);
+        } else {
+            do_tile(s0, nopf, u);
+        }
     }
     head_flush(cur);
     __syncthreads();
