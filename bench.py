@@ -59,32 +59,67 @@ def time_steps(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, r
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
-def fused_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w, steps):
-    """Dominant kernel: the persistent verification kernel (one launch runs every
-    linear layer and every attention of the step).  Its launches are bracketed by HIP
-    events inside the library, on the launch stream; achieved = algorithmic bytes of
-    one step (all weights once + all cache rows once) / average launch duration."""
+def recorded_traffic():
+    """HBM bytes per launch of the linear-layer kernel from the committed counter
+    summary (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known
+    size); None when the kernel sources have changed since."""
+    path = os.path.join(ROOT, "profiles", "k_fused_linear_stack7b_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    from paper_2505_23219_amd.profile_summary import source_digest
+    vals = {}
+    for line in open(path):
+        if line.startswith(("traffic_bytes_per_launch:", "source_sha256:")):
+            k, v = line.split(":", 1)
+            vals[k] = v.strip()
+    if vals.get("source_sha256") != source_digest():
+        return None
+    try:
+        return int(vals["traffic_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, what, steps):
     lib = B.lib()
     lib.ghd_debug_profile_read.argtypes = [C.POINTER(C.c_float)]
     tot_ms, launches = 0.0, 0
     with torch.cuda.stream(stream):
         for _ in range(steps):
-            lib.ghd_debug_profile(1)
+            lib.ghd_debug_profile(what)
             B.ghd_verify_stack(stack, x_in, parent, kv_len, logits=logits, ws=ws)
             lib.ghd_debug_profile(0)
             torch.cuda.synchronize()
             ms = C.c_float(0)
-            n = lib.ghd_debug_profile_read(C.byref(ms))
+            launches += lib.ghd_debug_profile_read(C.byref(ms))
             tot_ms += ms.value
-            launches += n
-    per_launch_bytes = w.algorithmic_bytes()
+    return tot_ms, launches
+
+
+def linear_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w, steps):
+    """Dominant kernel: the persistent skinny-GEMM kernel (4 launches per layer + the LM
+    head; it streams every weight byte of the step).  Its launches are bracketed by HIP
+    events inside the library, on the launch stream.  achieved = algorithmic bytes per
+    launch (all weight bytes of the step / launches per step: every launch reads its
+    matrix exactly once) / average launch duration."""
+    s = w.shape
+    weight_bytes = 2 * (s.L * (3 * s.H * s.H + s.H * s.H + 2 * s.F * s.H + s.H * s.F) + s.V * s.H)
+    tot_ms, launches = timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, 1, steps)
+    per_step = launches // steps
+    per_launch_bytes = weight_bytes / per_step
     avg_ms = tot_ms / launches
     achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
-    return {"bound": "hbm", "kernel": "k_fused", "achieved": round(achieved, 1),
+    att_ms, att_n = timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, 2, steps)
+    kv_bytes = 2 * 2 * s.L * s.nh * s.d * (kv_len + w.M)
+    return {"bound": "hbm", "kernel": "k_fused<MT, 128, MODE_LINEAR>", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": None, "launches_per_step": launches // steps,
+            "traffic": recorded_traffic(), "launches_per_step": per_step,
             "avg_launch_us": round(avg_ms * 1e3, 2),
-            "algorithmic_bytes_per_launch": int(per_launch_bytes)}
+            "algorithmic_bytes_per_launch": int(per_launch_bytes),
+            "attention": {"kernel": "k_fused<MT, D, MODE_ATTN>", "launches_per_step": att_n // steps,
+                          "avg_launch_us": round(att_ms / att_n * 1e3, 2),
+                          "algorithmic_bytes_per_launch": int(kv_bytes / (att_n // steps)),
+                          "achieved": round(kv_bytes / (att_n // steps) / (att_ms / att_n * 1e-3) / 1e9, 1)}}
 
 
 def cpu_baseline(wl, w, sample_layers):
@@ -127,6 +162,8 @@ def main():
     ap.add_argument("--workload", default="stack7b")
     ap.add_argument("--cpu-sample-layers", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also launch one plain 1 GiB copy kernel (for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the verification step runs on a single MI355X and "
@@ -156,6 +193,15 @@ def main():
             res=torch.zeros(2 + M, dtype=torch.int32, device=dev),
             amax=torch.empty(M, dtype=torch.int32, device=dev))
 
+    if args.pmc_calibrate:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        rc = B.lib().ghd_debug_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
+                                    C.c_size_t(src.numel() * 4), C.c_void_p(0))
+        torch.cuda.synchronize()
+        log("calibration copy of %d bytes: rc=%d" % (src.numel() * 4, rc))
+        del src, dst
     tree = inputs(w.M, w.parent)
     ms, wall_ms = time_steps(torch, B, stack, tree["x_in"], tree["parent"], tree["tokens"], w.kv_len,
                              tree["ws"], tree["aws"], tree["logits"], tree["res"], tree["amax"],
@@ -167,8 +213,8 @@ def main():
                            dec["ws"], dec["aws"], dec["logits"], dec["res"], dec["amax"], stream,
                            args.steps, args.warmup)
     log("decode step: %.1f us" % (dec_ms * 1e3))
-    roof = fused_roofline(torch, B, stack, tree["x_in"], tree["parent"], w.kv_len, tree["ws"],
-                         tree["logits"], stream, w, max(2, min(args.steps, 5)))
+    roof = linear_roofline(torch, B, stack, tree["x_in"], tree["parent"], w.kv_len, tree["ws"],
+                           tree["logits"], stream, w, max(2, min(args.steps, 5)))
     log("roofline:", roof)
 
     step_bytes = w.algorithmic_bytes()

@@ -22,14 +22,14 @@ ghd_status check_launch()
 // When enabled, every launch of the persistent kernel is bracketed by a pair of HIP
 // events on its stream; the caller reads the summed duration after synchronising.
 // Off by default: the hot path records nothing.
-static bool g_prof_on = false;
+static int g_prof_mode = -1;   // -1 off, else the FusedArgs::mode whose launches are timed
 static const int kProfMax = 256;
 static hipEvent_t g_prof_ev[2 * kProfMax];
 static int g_prof_made = 0, g_prof_used = 0;
 
 static ghd_status timed_fused(const FusedArgs& a, hipStream_t st)
 {
-    if (!g_prof_on || g_prof_used >= kProfMax) return launch_fused(a, st);
+    if (g_prof_mode != a.mode || g_prof_used >= kProfMax) return launch_fused(a, st);
     while (g_prof_made < 2 * (g_prof_used + 1)) {
         hipError_t e = hipEventCreate(&g_prof_ev[g_prof_made]);
         if (e != hipSuccess) return hip_fail(e);
@@ -512,15 +512,32 @@ ghd_status ghd_accept_greedy(const float* logits, const int32_t* tokens_dev,
                          (hipStream_t)stream);
 }
 
-/* Benchmark support (not part of the documented ABI): time the persistent-kernel
- * launches with HIP events.  ghd_debug_profile(1) starts a fresh measurement,
- * ghd_debug_profile(0) stops it; after synchronising the stream,
- * ghd_debug_profile_read returns the number of launches and their summed duration
- * in milliseconds. */
-void ghd_debug_profile(int enable)
+/* Benchmark support (not part of the documented ABI): time the launches of one kind
+ * of the persistent kernel with HIP events on the launch stream.
+ * ghd_debug_profile(1) starts a fresh measurement of the linear-layer launches,
+ * ghd_debug_profile(2) of the attention launches, ghd_debug_profile(0) stops it; after
+ * synchronising the stream, ghd_debug_profile_read returns the number of launches and
+ * their summed duration in milliseconds.  ghd_debug_copy is a plain copy kernel of known
+ * traffic (bytes read + bytes written) used to calibrate the profiler's byte counters. */
+void ghd_debug_profile(int what)
 {
-    g_prof_on = enable != 0;
-    if (enable) g_prof_used = 0;
+    g_prof_mode = what == 1 ? MODE_LINEAR : what == 2 ? MODE_ATTN : -1;
+    if (what) g_prof_used = 0;
+}
+
+__global__ void k_debug_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
+int ghd_debug_copy(void* dst, const void* src, size_t bytes, void* stream)
+{
+    if (!dst || !src || (bytes % 16) != 0 || !aligned16(dst) || !aligned16(src)) return GHD_ERR_SHAPE;
+    hipLaunchKernelGGL(k_debug_copy, dim3(4096), dim3(256), 0, (hipStream_t)stream, (uint4*)dst,
+                       (const uint4*)src, bytes / 16);
+    return check_launch();
 }
 
 int ghd_debug_profile_read(float* total_ms)
