@@ -177,17 +177,20 @@ ghd_status ghd_verify_stack(const ghd_model_cfg *cfg, const ghd_layer_weights *l
                             float *logits, float *x_out, void *ws, size_t ws_bytes, void *stream);
 size_t ghd_workspace_bytes(const ghd_model_cfg *cfg, int M, int kv_len);
 
-/* The step runs as one persistent kernel whose workgroups meet at grid-wide
- * barriers; every wait is bounded and gives up rather than hang (for instance if
- * other work on the GPU keeps some workgroups from becoming resident).  This
- * call synchronises `stream` and reports the status word the last
- * ghd_linear_skinny / ghd_tree_attention / ghd_verify_layer / ghd_verify_stack
- * call left in its workspace `ws`: 0 = completed, 1 = a wait gave up and the
- * outputs are invalid.  Blocking; for tests and error handling, not the hot path. */
+/* Every linear layer and every attention is one launch of a persistent kernel
+ * (one workgroup per compute unit, all resident) whose workgroups hand partial
+ * results to each other; every wait is bounded and gives up rather than hang
+ * (for instance if other work on the GPU keeps some workgroups from becoming
+ * resident).  This call synchronises `stream` and reports the status word the
+ * last ghd_linear_skinny / ghd_tree_attention / ghd_verify_layer /
+ * ghd_verify_stack call left in its workspace `ws`: 0 = completed, otherwise
+ * the code of the wait that gave up (3: a workgroup did not run on the expected
+ * XCD) and the outputs are invalid.  Blocking; for tests and error handling,
+ * not the hot path. */
 ghd_status ghd_step_status(const void *ws, int32_t *status_host, void *stream);
 
-/* ---- greedy acceptance ("fall back to the longest validated prefix",
- *      section 2.3) ------------------------------------------------------ */
+/* ---- greedy acceptance (section 2.3: of the drafted tree, the longest root
+ *      path the model itself would have produced is kept) ------------------- */
 
 /* amax[i] = lowest index of the largest logit in row i.  The root is valid; a
  * node is valid iff its parent is valid and tokens[i] == amax[parent[i]].

@@ -380,7 +380,7 @@ void orc_verify_stack(const orc_cfg *c, const uint16_t *const *g_attn,
 
 /* ----------------------------------------------------------- acceptance -- */
 
-/* Greedy acceptance: "fall back to the longest validated prefix".
+/* Greedy acceptance (section 2.3: the longest verified root path is kept).
  * amax[i] = lowest index of the largest logit of row i.  The root is valid; a
  * drafted node is valid iff its parent is valid and its token equals the
  * parent's amax.  The result is the valid node of greatest depth (lowest index
