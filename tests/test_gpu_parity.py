@@ -20,9 +20,23 @@ from paper_2505_23219_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
+_capman = None
+
+
+@pytest.fixture(autouse=True, scope="module")
+def _capture_manager(request):
+    global _capman
+    _capman = request.config.pluginmanager.getplugin("capturemanager")
+
+
 def say(*a):
-    print(*a, flush=True)
-    sys.stdout.flush()
+    """Progress line that reaches the terminal even under output capture: names the case
+    before each GPU step."""
+    if _capman is not None:
+        with _capman.global_and_fixture_disabled():
+            print(*a, flush=True)
+    else:
+        print(*a, flush=True)
 
 
 @pytest.fixture(scope="module")
@@ -340,3 +354,97 @@ def test_accept_greedy_same_logits_bit_exact(B, orc32, M, V):
         res, amax_g = res.cpu().numpy(), amax_g.cpu().numpy()
         assert np.array_equal(amax_g, amax)
         assert res[0] == n and res[1] == nxt and np.array_equal(res[2:2 + n], path)
+
+
+# ---- full-size cases: the benchmark's configuration and the large shapes -------------
+
+def run_big_stack(B, model, orc32, w, L):
+    """The stack at its real shape through the same ghd_verify_stack call bench.py times.
+
+    The oracle goes layer by layer so that only one layer's fp16 weights are on the host,
+    twice: with fp16 rounding at the GPU path's rounding points (x16) and in pure fp32
+    (x32).  Three checks:
+      * every layer on its own, fed the oracle's residual stream: stated tolerance;
+      * the free-running stack's logits (normalised quantities): stated tolerance;
+      * the free-running stack's final residual stream: it is not normalised (rms grows
+        like sqrt(layers)) and rounding noise accumulates over the layers, so the two
+        oracle variants themselves drift apart by more than the tolerance at depth 32;
+        the GPU must be no further from the pure-fp32 result than 1.5x the rounded oracle
+        is (max and rms), plus the stated tolerance.
+    """
+    shape = wl.with_layers(w.shape, L)
+    M, kv_len, parent = w.M, w.kv_len, w.parent
+    cap = w.capacity
+    x16 = wl.activations(M, shape.H, w.seed)
+    xr = x16.numpy().astype(np.float32)     # rounded oracle
+    xp = xr.copy()                          # pure fp32 oracle
+    layers, caches = [], []
+    cfg = B.make_cfg(shape, cap)
+    ws = B.workspace(B.ghd_workspace_bytes(cfg, M, kv_len))
+    pd = torch.from_numpy(parent).cuda()
+    for l in range(L):
+        # generated on the GPU (seconds for the whole model); the oracle gets host copies
+        lw = wl.layer_weights(shape, w.seed, l, device="cuda")
+        kc, vc = wl.kv_cache(shape, cap, kv_len, w.seed, l, device="cuda")
+        lwh = {k: v.cpu().numpy() for k, v in lw.items()}
+        x_in = xr.copy()
+        xr = orc32.verify_layer(shape, lwh, kc.cpu().numpy(), vc.cpu().numpy(), xr, parent, kv_len,
+                                round16=True)
+        xp = orc32.verify_layer(shape, lwh, kc.cpu().numpy(), vc.cpu().numpy(), xp, parent, kv_len,
+                                round16=False)
+        wd = model.upload_layer(lw, shape.d)
+        # this layer alone, on the oracle's input (scratch copies of the cache)
+        xg = torch.from_numpy(x_in).cuda()
+        B.ghd_verify_layer(cfg, wd, kc.clone(), vc.clone(), xg, pd, kv_len, ws=ws)
+        assert B.ghd_step_status(ws) == 0
+        ok, ma, mr = close(xg.cpu().numpy(), xr, 2e-2, 1e-2)
+        assert ok, ("layer", l, ma, mr)
+        layers.append(wd)
+        caches.append((kc, vc))
+        del lw, lwh
+        if l % 4 == 3:
+            say("  layer", l + 1, "of", L, "max abs err (layer alone) %.4f" % ma)
+    head = wl.head_weights(shape, w.seed, device="cuda")
+    hh = {k: v.cpu().numpy() for k, v in head.items()}
+    ref_logits = orc32.lm_head(shape, hh["g_final"], hh["Wlm"], xr, True)
+    stack = model.build_stack(shape, cap, layers, caches, model.upload_head(head))
+    x_out = torch.empty((M, shape.H), dtype=torch.float32, device="cuda")
+    logits = B.ghd_verify_stack(stack, x16.cuda(), pd, kv_len, x_out=x_out, ws=ws)
+    assert B.ghd_step_status(ws) == 0
+    ok, ma, mr = close(logits.cpu().numpy(), ref_logits, 2e-2, 1e-2)
+    assert ok, ("logits", ma, mr)
+    e_gpu = np.abs(x_out.cpu().numpy() - xp)
+    e_orc = np.abs(xr - xp)
+    say("  final residual vs pure fp32: gpu max %.4f rms %.5f | rounded oracle max %.4f rms %.5f"
+        % (e_gpu.max(), np.sqrt((e_gpu ** 2).mean()), e_orc.max(), np.sqrt((e_orc ** 2).mean())))
+    assert e_gpu.max() <= 1.5 * e_orc.max() + 2e-2
+    assert np.sqrt((e_gpu ** 2).mean()) <= 1.5 * np.sqrt((e_orc ** 2).mean()) + 2e-3
+    checked = check_accept(B, orc32, logits, ref_logits, parent, pd, shape.V, w.seed)
+    say("  argmax compared on", checked, "of", M, "rows")
+    return checked
+
+
+@pytest.mark.timeout(900)
+def test_verify_stack_7b_full_size(B, model, orc32):
+    """configs: 32-layer 7B-shaped stack + LM head, 64-node tree, 2048-token cache."""
+    w = wl.workload("stack7b")
+    say("stack 7b full size", w.M, w.kv_len, w.shape.L)
+    assert run_big_stack(B, model, orc32, w, w.shape.L) > w.M // 2
+
+
+@pytest.mark.timeout(600)
+def test_verify_stack_13b_shape_two_layers(B, model, orc32):
+    """13B-shaped layers (H=5120, 40 heads, F=13824), 8192-token cache, wide shallow
+    64-node tree; two of the 40 layers + LM head keep the oracle to seconds."""
+    w = wl.workload("stack13b")
+    say("stack 13b shape, 2 layers", w.M, w.kv_len)
+    run_big_stack(B, model, orc32, w, 2)
+
+
+@pytest.mark.parametrize("M,tree", [(1, "chain"), (4, "chain"), (32, "rand5"), (128, "chain"),
+                                    (128, "rand5")])
+def test_verify_layer_7b_shape_tree_sizes(B, model, orc32, M, tree):
+    """Tree-size sweep shapes: one 7B-shaped layer, 2048-token cache."""
+    say("layer 7b sweep", M, tree)
+    shape = wl.with_layers(wl.LLAMA_7B, 1)
+    run_layer_case(B, model, orc32, shape, M, 2048, make_tree(tree, M), 3)
