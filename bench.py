@@ -30,7 +30,8 @@ def build_gpu_model(wl, B, model, w, device):
     layers, caches = [], []
     for l in range(s.L):
         layers.append(model.upload_layer(wl.layer_weights(s, w.seed, l, device=device), s.d, device))
-        caches.append(wl.kv_cache(s, w.capacity, w.kv_len, w.seed, l, device=device))
+        caches.append(model.upload_cache(*wl.kv_cache(s, w.capacity, w.kv_len, w.seed, l, device=device),
+                                         device=device))
         if l % 8 == 7:
             log("  built layer %d/%d" % (l + 1, s.L))
     head = model.upload_head(wl.head_weights(s, w.seed, device=device), device)

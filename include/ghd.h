@@ -16,8 +16,11 @@
  *     ghd_pack_weight (the bytes of the row-major [N, K] matrix, zero padded to
  *     N%256 == 0 and K%128 == 0 and reordered so that every workgroup streams
  *     one contiguous range in 1 KiB MFMA-operand blocks).
- *   - The KV cache of one layer is fp16, element (head h, row t, channel c) at
- *     h*stride_head + t*stride_tok + c; rows [0, kv_len) are committed, row
+ *   - The KV cache of one layer is fp16.  K is row-major per head: element
+ *     (head h, row t, channel c) at h*k_stride_head + t*k_stride_tok + c.  V is
+ *     kept channel-major, (h, c, t) at h*v_stride_head + c*v_stride_ch + t, so
+ *     that a tile of V^T (the operand of the P.V product, contiguous in the
+ *     key index) is read as it lies.  Rows [0, kv_len) are committed, row
  *     kv_len + i belongs to tree node i.
  *   - The tree is parent[M] (int32): parent[0] == -1 (node 0 is the root: the
  *     last committed token, whose K/V is not yet cached), 0 <= parent[i] < i.
@@ -77,7 +80,8 @@ typedef struct {
     const void *g_attn, *Wqkv, *Wo, *g_ffn, *Wgu, *Wdown;
 } ghd_layer_weights;
 
-/* One layer's cache, head-major [nh][kv_capacity][d] fp16. */
+/* One layer's cache, fp16: k [nh][kv_capacity][d], v [nh][d][kv_capacity]
+ * (channel-major); kv_capacity % 8 == 0. */
 typedef struct {
     void *k, *v;
 } ghd_kv;
@@ -147,14 +151,16 @@ size_t ghd_linear_workspace_bytes(int M, int N, int K);
 /* out[i, h, :] = softmax_t(scale * q[i, h, :] . K[h, t, :]) V[h, t, :], t over
  * rows [0, kv_len) and rows kv_len + j with j on the root path of i.
  *   q, out  fp16 [M, nh, d];  d in {64, 128}
- *   k_cache, v_cache  fp16, strides in elements, stride_tok % 8 == 0;
- *                     rows [0, kv_len + M) must be readable.
+ *   k_cache, v_cache  fp16, strides in elements, all multiples of 8;
+ *                     rows [0, kv_len + M) must be readable, and
+ *                     v_stride_ch >= kv_len + M.
  * Splits the key range over workgroups and merges the parts with the
  * online-softmax rescaling of section 3.2.2.  nh <= 256. */
 ghd_status ghd_tree_attention(void *out, const void *q, const void *k_cache, const void *v_cache,
                               const int32_t *parent_dev, int M, int kv_len, int nh, int d,
-                              int64_t stride_head, int64_t stride_tok, float scale, void *ws,
-                              size_t ws_bytes, void *stream);
+                              int64_t k_stride_head, int64_t k_stride_tok, int64_t v_stride_head,
+                              int64_t v_stride_ch, float scale, void *ws, size_t ws_bytes,
+                              void *stream);
 size_t ghd_attention_workspace_bytes(int M, int kv_len, int nh, int d);
 
 /* ---- decoder layer and stack (section 2.2.2; model details as in the

@@ -69,7 +69,7 @@ def lib() -> C.CDLL:
             "ghd_pack_weight": (C.c_int32, [vp, vp, i32, i32, i32, i32, vp]),
             "ghd_linear_skinny": (C.c_int32, [vp, vp, vp, i32, i32, i32, i64, i64, u32, vp, sz, vp]),
             "ghd_linear_workspace_bytes": (sz, [i32, i32, i32]),
-            "ghd_tree_attention": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, f32,
+            "ghd_tree_attention": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, i64, i64, f32,
                                                vp, sz, vp]),
             "ghd_attention_workspace_bytes": (sz, [i32, i32, i32, i32]),
             "ghd_verify_layer": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]),
@@ -179,7 +179,8 @@ def ghd_linear_skinny(x: torch.Tensor, Wp: torch.Tensor, N: int, out_dtype=torch
 def ghd_tree_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
                        parent: torch.Tensor, kv_len: int, scale: Optional[float] = None,
                        ws: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """q fp16 [M, nh, d]; caches fp16 [nh, cap, d] (head-major); returns fp16 [M, nh, d]."""
+    """q fp16 [M, nh, d]; k_cache fp16 [nh, cap, d]; v_cache fp16 [nh, d, cap]
+    (channel-major); returns fp16 [M, nh, d]."""
     M, nh, d = q.shape
     out = torch.empty_like(q)
     if scale is None:
@@ -190,7 +191,8 @@ def ghd_tree_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Te
                                     _ptr(_dev(k_cache, torch.float16)),
                                     _ptr(_dev(v_cache, torch.float16)),
                                     _ptr(_dev(parent, torch.int32)), M, kv_len, nh, d,
-                                    k_cache.stride(0), k_cache.stride(1), scale, _ptr(ws), ws.numel(),
+                                    k_cache.stride(0), k_cache.stride(1), v_cache.stride(0),
+                                    v_cache.stride(1), scale, _ptr(ws), ws.numel(),
                                     _stream()), "ghd_tree_attention")
     return out
 

@@ -92,8 +92,8 @@ static Ws carve(void* ws, int what, int M, int H, int F, int d)
     if (what != 2) w.part = cv.take<float>((size_t)G * 2 * kTG * (Mpad / 16) * 256);
     if (what != 1) {
         w.mask = cv.take<uint64_t>(2 * GHD_MAX_M);
-        w.o_part = cv.take<float>((size_t)G * 4 * Mpad * d);
-        w.ml_part = cv.take<float>((size_t)G * 4 * Mpad * 2);
+        w.o_part = cv.take<float>((size_t)G * 2 * Mpad * d);
+        w.ml_part = cv.take<float>((size_t)G * 2 * Mpad * 2);
     }
     if (what == 0) {
         w.rope = cv.take<float2>((size_t)GHD_MAX_M * (d / 2));
@@ -119,7 +119,7 @@ static ghd_status check_cfg(const ghd_model_cfg* c, int M, int kv_len)
         (int64_t)c->V > 1024 * kGroupRows)
         return GHD_ERR_SHAPE;
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return GHD_ERR_SHAPE;
-    if ((int64_t)kv_len + M > (int64_t)c->kv_capacity) return GHD_ERR_CAPACITY;
+    if ((int64_t)kv_len + M > (int64_t)c->kv_capacity || (c->kv_capacity % 8) != 0) return GHD_ERR_CAPACITY;
     return GHD_OK;
 }
 
@@ -136,6 +136,8 @@ static void fill_common(FusedArgs& a, const ghd_model_cfg* c, const Ws& w, int M
     a.L = c->L;
     a.stride_head = (int64_t)c->kv_capacity * c->d;
     a.stride_tok = c->d;
+    a.v_stride_head = (int64_t)c->kv_capacity * c->d;
+    a.v_stride_ch = c->kv_capacity;
     a.eps = c->rms_eps;
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)c->d);
     a.sync = w.sync;
@@ -371,15 +373,18 @@ size_t ghd_attention_workspace_bytes(int M, int kv_len, int nh, int d)
 
 ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, const void* v_cache,
                               const int32_t* parent_dev, int M, int kv_len, int nh, int d,
-                              int64_t stride_head, int64_t stride_tok, float scale, void* ws,
-                              size_t ws_bytes, void* stream)
+                              int64_t k_stride_head, int64_t k_stride_tok, int64_t v_stride_head,
+                              int64_t v_stride_ch, float scale, void* ws, size_t ws_bytes,
+                              void* stream)
 {
     if (!out || !q || !k_cache || !v_cache || !parent_dev) return GHD_ERR_NULL;
     if (M < 1 || M > GHD_MAX_M || kv_len < 0 || nh < 1 || nh > 256 || (d != 64 && d != 128))
         return GHD_ERR_SHAPE;
-    if (stride_tok < d || stride_head < 0) return GHD_ERR_SHAPE;
+    if (k_stride_tok < d || k_stride_head < 0 || v_stride_head < 0) return GHD_ERR_SHAPE;
+    if (v_stride_ch < (int64_t)kv_len + M) return GHD_ERR_CAPACITY;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) ||
-        (stride_tok % 8) != 0 || (stride_head % 8) != 0)
+        (k_stride_tok % 8) != 0 || (k_stride_head % 8) != 0 || (v_stride_ch % 8) != 0 ||
+        (v_stride_head % 8) != 0)
         return GHD_ERR_ALIGN;
     if (!ws) return GHD_ERR_WORKSPACE;
     if (!aligned16(ws)) return GHD_ERR_ALIGN;
@@ -397,8 +402,10 @@ ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, con
     a.nh = nh;
     a.d = d;
     a.H = nh * d;
-    a.stride_head = stride_head;
-    a.stride_tok = stride_tok;
+    a.stride_head = k_stride_head;
+    a.stride_tok = k_stride_tok;
+    a.v_stride_head = v_stride_head;
+    a.v_stride_ch = v_stride_ch;
     a.scale_log2e = scale * 1.4426950408889634f;
     a.sync = w.sync;
     a.o_part = w.o_part;

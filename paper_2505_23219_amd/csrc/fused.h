@@ -45,13 +45,14 @@ struct FusedArgs {
     int mode;
     int M, Mpad, kv_len;
     int H, nh, d, F, V, L;
-    int64_t stride_head, stride_tok;
+    int64_t stride_head, stride_tok;       // K cache: (head, row, channel) at h*sh + t*st + c
+    int64_t v_stride_head, v_stride_ch;    // V cache, channel-major: (head, channel, row) at h*vh + c*vc + t
     float eps, scale_log2e;
     // scratch (device)
     uint32_t* sync;        // kSyncWords
     float* part;           // GEMM partial slots: [G][2][16*MT KiB]
-    float* o_part;         // attention partial slots: [G][2][2][Mpad][d]
-    float* ml_part;        // [G][2][2][Mpad][2]
+    float* o_part;         // attention partial slots: [G][2][Mpad][d]
+    float* ml_part;        // [G][2][Mpad][2]
     float* x;              // residual stream [M, H] fp32
     half_t* xg16;          // fp16(x * gain of the next RMSNorm / 16) [M, H]: GEMM input
     float* ss;             // sums of squares per 16-column tile: [H/16][Mpad]

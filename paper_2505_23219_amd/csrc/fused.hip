@@ -30,9 +30,10 @@
 // sums in the epilogue.  The 1/16 keeps x * g inside the fp16 range.
 //
 // Tree attention.  The (head, 64-key tile) pairs form the same kind of linear
-// sequence.  A workgroup streams its tiles through LDS; wavefronts 0-3 take the
-// first 32 keys of a tile, 4-7 the last 32, each for its own 16 (or 32) query
-// rows.  S^T = K q^T puts one query row in each lane column, so softmax
+// sequence.  A workgroup streams its tiles through LDS (the V cache is kept
+// channel-major, so both K rows and V^T rows go to LDS as they are); wavefronts
+// 0-3 take the first 32 keys of a tile, 4-7 the last 32, each for its own 16 (or
+// 32) query rows.  S^T = K q^T puts one query row in each lane column, so softmax
 // statistics are per-lane scalars, the fp16 probabilities are already in
 // B-operand layout for O^T += V^T P^T, and the ancestor mask (section 2.3) is a
 // 128-bit register per lane.  Sub-tiles no row can see are skipped.  Parts of a
@@ -234,12 +235,18 @@ __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, f
             o1 = v[1] * cs1.x - v[3] * cs1.y;
             o3 = v[3] * cs1.x + v[1] * cs1.y;
         }
-        half_t* dst;
-        if (part == 0) dst = a.q16 + (size_t)m * H + head * d + jj;
-        else {
-            half_t* base = (part == 1) ? op.kc : op.vc;
-            dst = base + (size_t)head * a.stride_head + (size_t)(a.kv_len + m) * a.stride_tok + jj;
+        if (part == 2) {
+            // V is kept channel-major: row kv_len + m of channels jj, jj+1, jj+d/2, jj+1+d/2
+            half_t* col = op.vc + (size_t)head * a.v_stride_head + (size_t)(a.kv_len + m);
+            col[(size_t)jj * a.v_stride_ch] = (half_t)o0;
+            col[(size_t)(jj + 1) * a.v_stride_ch] = (half_t)o1;
+            col[(size_t)(jj + hd) * a.v_stride_ch] = (half_t)o2;
+            col[(size_t)(jj + 1 + hd) * a.v_stride_ch] = (half_t)o3;
+            return;
         }
+        half_t* dst = (part == 0)
+                          ? a.q16 + (size_t)m * H + head * d + jj
+                          : op.kc + (size_t)head * a.stride_head + (size_t)(a.kv_len + m) * a.stride_tok + jj;
         half2_ lo = {(half_t)o0, (half_t)o1}, hi = {(half_t)o2, (half_t)o3};
         *(half2_*)dst = lo;
         *(half2_*)(dst + hd) = hi;
@@ -500,12 +507,18 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
 // ---------------------------------------------------------------------------
 // tree attention
 // ---------------------------------------------------------------------------
-template <int D>
+template <int MT, int D>
 struct AttnLds {
+    static constexpr int MTW = (MT + 3) / 4;
     static constexpr int KS = D + 8;    // halves per K row (padded)
-    static constexpr int VS = 64 + 4;   // halves per V^T row (padded)
+    static constexpr int VS = 64 + 8;   // halves per V^T row (padded, rows stay 16-byte aligned)
     half_t k[64 * KS];
     half_t vt[D * VS];
+    // state of the wavefronts working on the second key half, handed to their partners on
+    // the first half when a head ends: [row-tile slot][tile][fragment][lane]
+    floatx4 o2[4][MTW][D / 16][64];
+    float m2[4][MTW][64];
+    float l2[4][MTW][64];
 };
 
 template <int MT, int D>
@@ -514,8 +527,8 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
 {
     constexpr int MTW = (MT + 3) / 4;   // 16-row tiles per wavefront
     constexpr int DS = D / 32, DT = D / 16, CPR = D / 8;
-    constexpr int NLD = 64 * CPR / kFT; // 16-byte chunks per thread per tile
-    using L = AttnLds<D>;
+    constexpr int NLD = 64 * CPR / kFT; // 16-byte pieces per thread per tile, for K and for V alike
+    using L = AttnLds<MT, D>;
     L& sm = *reinterpret_cast<L*>(cx.lds);
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -526,46 +539,49 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
     const Share sh = make_share(nh, ntile, cx.j, cx.G);
     const long u0 = sh.c0, u1 = sh.c1;
 
-    // two tiles in flight: registers of set (u - u0) & 1 hold tile u until it is staged
+    if (barrier_first && !grid_barrier(a, cx)) return false;
+    if (u0 >= u1) return true;
+
+    // Two tiles in flight: registers of set (u - u0) & 1 hold tile u until it is staged.
+    // K piece id -> (row id / CPR, 8 channels id % CPR); V^T piece id -> (channel id / 8,
+    // 8 keys id % 8).
     half8 kreg[2][NLD], vreg[2][NLD];
-    auto load_tile = [&](auto set, long u, bool committed_only) {
+    auto load_tile = [&](auto set, long u) {
         constexpr int S = decltype(set)::value;
         int head = (int)(u / ntile), tile = (int)(u % ntile);
         const half_t* kh_ = kc + (size_t)head * a.stride_head;
-        const half_t* vh_ = vc + (size_t)head * a.stride_head;
+        const half_t* vh_ = vc + (size_t)head * a.v_stride_head;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             int id = tid + kFT * i;
             int row = id / CPR, ch = id % CPR;
-            int key = min(tile * 64 + row, committed_only ? a.kv_len - 1 : T - 1);
+            int key = min(tile * 64 + row, T - 1);
             kreg[S][i] = __builtin_nontemporal_load((const half8*)(kh_ + (size_t)key * a.stride_tok + ch * 8));
-            vreg[S][i] = __builtin_nontemporal_load((const half8*)(vh_ + (size_t)key * a.stride_tok + ch * 8));
+            int vch = id >> 3, seg = id & 7;
+            // keys past the capacity are never touched: the last piece is read instead and
+            // zeroed when it is staged
+            long ks = min((long)tile * 64 + seg * 8, a.v_stride_ch - 8);
+            vreg[S][i] = __builtin_nontemporal_load((const half8*)(vh_ + (size_t)vch * a.v_stride_ch + ks));
         }
     };
-    auto store_tile = [&](auto set) {
+    auto store_tile = [&](auto set, int tile) {
         constexpr int S = decltype(set)::value;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             int id = tid + kFT * i;
             int row = id / CPR, ch = id % CPR;
             *(half8*)(&sm.k[row * L::KS + ch * 8]) = kreg[S][i];
+            int vch = id >> 3, seg = id & 7;
+            half8 v = vreg[S][i];
+            int nvalid = T - (tile * 64 + seg * 8);      // rows from T on hold no data: zero them,
+            if (nvalid < 8) {                            // a stray NaN times a zero weight is a NaN
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sm.vt[(ch * 8 + e) * L::VS + row] = vreg[S][i][e];
+                for (int e = 0; e < 8; ++e)
+                    if (e >= nvalid) v[e] = (half_t)0;
+            }
+            *(half8*)(&sm.vt[vch * L::VS + seg * 8]) = v;
         }
     };
-
-    // The first tile can be requested before the barrier when it lies entirely in the
-    // committed cache (those rows do not depend on this step).
-    bool prefetched = false;
-    if (u0 < u1 && barrier_first) {
-        int tile = (int)(u0 % ntile);
-        if (tile * 64 + 64 <= a.kv_len) {
-            load_tile(std::integral_constant<int, 0>{}, u0, true);
-            prefetched = true;
-        }
-    }
-    if (barrier_first && !grid_barrier(a, cx)) return false;
-    if (u0 >= u1) return true;
 
     // per-wave query rows
     int mrow[MTW];
@@ -599,47 +615,73 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
             for (int e = 0; e < DT; ++e) oacc[t][e] = (floatx4){0.f, 0.f, 0.f, 0.f};
         }
     };
-    // parts of a head: workgroups first..last, two key halves each
-    auto head_first = [&](int head) { return sh.first_of(head); };
-    auto head_last = [&](int head) { return sh.last_of(head); };
-    auto slot_index = [&](int wg, int head, int half) -> size_t {
-        return ((size_t)wg * 2 + (sh.begins_in(wg, head) ? 0 : 1)) * 2 + half;
+    // parts of a head: workgroups first..last, one partial state each
+    auto slot_index = [&](int wg, int head) -> size_t {
+        return (size_t)wg * 2 + (sh.begins_in(wg, head) ? 0 : 1);
     };
+    // Ends this workgroup's share of a head: the wavefronts of the second key half hand
+    // their state over through LDS, their partners merge it into their own (online-softmax
+    // rescale) and store the workgroup's partial state.  Called by all threads.
     auto head_flush = [&](int head) {
-        if (!wave_active) return;
-        size_t slot = slot_index(cx.j, head, kh);
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
             float l = lrun[t];
             l += __shfl_xor(l, 16);
             l += __shfl_xor(l, 32);
-            if (!mok[t]) continue;
-            size_t row = slot * a.Mpad + mrow[t];
+            lrun[t] = l;
+        }
+        if (kh == 1 && wave_active) {
 #pragma unroll
-            for (int e = 0; e < DT; ++e)
-                *(floatx4*)(a.o_part + row * D + e * 16 + g4 * 4) = oacc[t][e];
-            if (g4 == 0) {
-                a.ml_part[row * 2] = mrun[t];
-                a.ml_part[row * 2 + 1] = l;
+            for (int t = 0; t < MTW; ++t) {
+#pragma unroll
+                for (int e = 0; e < DT; ++e) sm.o2[wq][t][e][lane] = oacc[t][e];
+                sm.m2[wq][t][lane] = mrun[t];
+                sm.l2[wq][t][lane] = lrun[t];
             }
         }
+        __syncthreads();
+        if (kh == 0 && wave_active) {
+            size_t slot = slot_index(cx.j, head);
+#pragma unroll
+            for (int t = 0; t < MTW; ++t) {
+                float mb = sm.m2[wq][t][lane], lb = sm.l2[wq][t][lane];
+                float mx = fmaxf(mrun[t], mb);
+                float wa = (mrun[t] == -INFINITY) ? 0.f : exp2f(mrun[t] - mx);
+                float wb = (mb == -INFINITY) ? 0.f : exp2f(mb - mx);
+                float l = lrun[t] * wa + lb * wb;
+                if (!mok[t]) continue;
+                size_t row = slot * a.Mpad + mrow[t];
+#pragma unroll
+                for (int e = 0; e < DT; ++e) {
+                    floatx4 ob = sm.o2[wq][t][e][lane];
+                    *(floatx4*)(a.o_part + row * D + e * 16 + g4 * 4) = oacc[t][e] * wa + ob * wb;
+                }
+                if (g4 == 0) {
+                    a.ml_part[row * 2] = mx;
+                    a.ml_part[row * 2 + 1] = l;
+                }
+            }
+        }
+        __syncthreads();   // the hand-over buffers may be refilled
     };
 
-    if (!prefetched) load_tile(std::integral_constant<int, 0>{}, u0, false);
-    if (u0 + 1 < u1) load_tile(std::integral_constant<int, 1>{}, u0 + 1, false);
+    const std::integral_constant<int, 0> s0;
+    const std::integral_constant<int, 1> s1;
+    load_tile(s0, u0);
+    load_tile(s1, min(u0 + 1, u1 - 1));
     int cur = (int)(u0 / ntile);
     head_begin(cur);
     auto do_tile = [&](auto set, auto prefetch, long u) {
         int head = (int)(u / ntile), tile = (int)(u % ntile);
-        __syncthreads();            // previous tile fully consumed
-        store_tile(set);
-        __syncthreads();
-        if constexpr (decltype(prefetch)::value) load_tile(set, u + 2, false);
         if (head != cur) {
             head_flush(cur);
             cur = head;
             head_begin(cur);
         }
+        __syncthreads();            // previous tile fully consumed
+        store_tile(set, tile);
+        __syncthreads();
+        if constexpr (decltype(prefetch)::value) load_tile(set, u + 2);
         if (!wave_active) return;
         const int key0 = tile * 64 + kh * 32;    // this wavefront's 32 keys
 #pragma unroll
@@ -721,13 +763,10 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
                 oacc[t][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pf, oacc[t][e], 0, 0, 0);
             }
         }
-    
     };
     // Tile u requests tile u + 2 while one exists; the loads of the steady-state loop are
     // unconditional, so the wait before a tile is staged counts exactly the younger loads.
     {
-        const std::integral_constant<int, 0> s0;
-        const std::integral_constant<int, 1> s1;
         const std::true_type pf;
         const std::false_type nopf;
         long u = u0;
@@ -748,7 +787,6 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
         }
     }
     head_flush(cur);
-    __syncthreads();
     int hfirst = (int)(u0 / ntile), hlast = (int)((u1 - 1) / ntile);
     if (tid == 0)
         for (int head = hfirst; head <= hlast; ++head)
@@ -756,44 +794,43 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
 
     // ---- merge: every workgroup of a head combines its share of the rows
     for (int head = hfirst; head <= hlast; ++head) {
-        int first = head_first(head), last = head_last(head);
-        int np = last - first + 1, me = cx.j - first;
+        int first = sh.first_of(head), last = sh.last_of(head);
+        int np = last - first + 1, me = cx.j - first;     // np <= 32 parts
         if (tid == 0) bounded_wait(a.sync, a.sync + kCntAttn + head * kCntStride, (uint32_t)np * (epoch + 1), 2000u);
         __syncthreads();
         int r0 = M * me / np, r1 = M * (me + 1) / np;
-        const int np2 = np * 2;      // parts: (workgroup, key half); at most 64
         for (int m = r0 + wave; m < r1; m += 8) {
             // lane q holds the statistics of part q
             float mq = -INFINITY, lq = 0.f;
             size_t rowq = 0;
-            if (lane < np2) {
-                rowq = slot_index(first + (lane >> 1), head, lane & 1) * a.Mpad + m;
+            if (lane < np) {
+                rowq = slot_index(first + lane, head) * a.Mpad + m;
                 mq = a.ml_part[rowq * 2];
                 lq = a.ml_part[rowq * 2 + 1];
             }
             float mx = mq;
             for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-            float wq = (mq == -INFINITY) ? 0.f : exp2f(mq - mx);
-            float den = wq * lq;
+            float wq_ = (mq == -INFINITY) ? 0.f : exp2f(mq - mx);
+            float den = wq_ * lq;
             for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off);
             // weighted sum of the parts' outputs, parts in index order, 8 loads in flight
             float num[D / 64];
 #pragma unroll
             for (int e = 0; e < D / 64; ++e) num[e] = 0.f;
-            for (int q0 = 0; q0 < np2; q0 += 8) {
+            for (int q0 = 0; q0 < np; q0 += 8) {
                 float t[8][D / 64], w8[8];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    int qq = min(q0 + q, np2 - 1);
+                for (int qi = 0; qi < 8; ++qi) {
+                    int qq = min(q0 + qi, np - 1);
                     size_t row = (size_t)__shfl((long long)rowq, qq);
-                    w8[q] = (q0 + q < np2) ? __shfl(wq, qq) : 0.f;
+                    w8[qi] = (q0 + qi < np) ? __shfl(wq_, qq) : 0.f;
 #pragma unroll
-                    for (int e = 0; e < D / 64; ++e) t[q][e] = a.o_part[row * D + e * 64 + lane];
+                    for (int e = 0; e < D / 64; ++e) t[qi][e] = a.o_part[row * D + e * 64 + lane];
                 }
 #pragma unroll
-                for (int q = 0; q < 8; ++q)
+                for (int qi = 0; qi < 8; ++qi)
 #pragma unroll
-                    for (int e = 0; e < D / 64; ++e) num[e] += w8[q] * t[q][e];
+                    for (int e = 0; e < D / 64; ++e) num[e] += w8[qi] * t[qi][e];
             }
 #pragma unroll
             for (int e = 0; e < D / 64; ++e)
@@ -954,7 +991,7 @@ template <int MT, int D>
 static size_t fused_lds_bytes()
 {
     size_t gemm = 2 * (size_t)kCH * MT * kFrag + (128 + 1024) * sizeof(float);
-    size_t attn = sizeof(AttnLds<D>);
+    size_t attn = sizeof(AttnLds<MT, D>);
     return 16 + (gemm > attn ? gemm : attn);
 }
 

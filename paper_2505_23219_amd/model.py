@@ -26,6 +26,17 @@ def upload_layer(w: Dict[str, torch.Tensor], head_dim: int, device="cuda") -> Di
     return out
 
 
+def upload_cache(k: torch.Tensor, v: torch.Tensor, device="cuda") -> Tuple[torch.Tensor, torch.Tensor]:
+    """[nh, capacity, d] K and V (any device) -> the device layouts of the library:
+    K as is, V channel-major [nh, d, capacity].  A copy, no arithmetic."""
+    return k.to(device).contiguous(), v.to(device).transpose(1, 2).contiguous()
+
+
+def rows_of_v(v_dev: torch.Tensor) -> torch.Tensor:
+    """The library's channel-major V cache back as [nh, capacity, d] (for comparisons)."""
+    return v_dev.transpose(1, 2)
+
+
 def upload_head(h: Dict[str, torch.Tensor], device="cuda") -> Dict[str, torch.Tensor]:
     return {"g_final": h["g_final"].to(device).contiguous(),
             "Wlm": B.ghd_pack_weight(h["Wlm"].to(device))}

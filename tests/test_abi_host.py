@@ -97,12 +97,13 @@ def test_linear_rejects_bad_arguments(lib):
 def test_attention_rejects_bad_arguments(lib):
     f = lib.ghd_tree_attention
     ok = dict(out=FAKE, q=FAKE, k=FAKE, v=FAKE, parent=FAKE, M=8, kv_len=100, nh=4, d=64,
-              sh=64 * 256, st=64, scale=0.125, ws=FAKE, ws_bytes=1 << 30, stream=None)
+              sh=64 * 256, st=64, vsh=64 * 256, vsc=256, scale=0.125, ws=FAKE, ws_bytes=1 << 30,
+              stream=None)
 
     def call(**kw):
         a = dict(ok, **kw)
         return f(a["out"], a["q"], a["k"], a["v"], a["parent"], a["M"], a["kv_len"], a["nh"], a["d"],
-                 a["sh"], a["st"], a["scale"], a["ws"], a["ws_bytes"], a["stream"])
+                 a["sh"], a["st"], a["vsh"], a["vsc"], a["scale"], a["ws"], a["ws_bytes"], a["stream"])
 
     for name in ("out", "q", "k", "v", "parent"):
         assert call(**{name: None}) == B.GHD_ERR_NULL
@@ -113,6 +114,8 @@ def test_attention_rejects_bad_arguments(lib):
     assert call(st=32) == B.GHD_ERR_SHAPE
     assert call(q=FAKE + 8) == B.GHD_ERR_ALIGN
     assert call(st=68) == B.GHD_ERR_ALIGN
+    assert call(vsc=260) == B.GHD_ERR_ALIGN          # V rows must stay 16-byte aligned
+    assert call(vsc=104) == B.GHD_ERR_CAPACITY       # fewer rows per channel than kv_len + M
     assert call(ws=None) == B.GHD_ERR_WORKSPACE
     assert call(ws_bytes=8) == B.GHD_ERR_WORKSPACE
 

@@ -174,13 +174,13 @@ def make_tree(kind, M):
 
 
 @pytest.mark.parametrize("M,nh,d,kv_len,tree", ATTN_CASES)
-def test_tree_attention(B, orc32, M, nh, d, kv_len, tree):
+def test_tree_attention(B, model, orc32, M, nh, d, kv_len, tree):
     say("attention", M, nh, d, kv_len, tree)
     parent = make_tree(tree, M)
     q, kc, vc = attention_case(M, nh, d, kv_len, parent, 41)
     ref = orc32.tree_attention(q.numpy().astype(np.float32), kc.numpy(), vc.numpy(), parent, kv_len)
     ws = B.workspace(B.lib().ghd_attention_workspace_bytes(M, kv_len, nh, d))
-    got = B.ghd_tree_attention(q.cuda(), kc.cuda(), vc.cuda(), torch.from_numpy(parent).cuda(),
+    got = B.ghd_tree_attention(q.cuda(), *model.upload_cache(kc, vc), torch.from_numpy(parent).cuda(),
                                kv_len, ws=ws)
     assert B.ghd_step_status(ws) == 0
     got = got.cpu().numpy()
@@ -188,15 +188,20 @@ def test_tree_attention(B, orc32, M, nh, d, kv_len, tree):
     assert ok, (ma, mr)
 
 
-def test_tree_attention_ignores_rows_past_the_tree(B):
+def test_tree_attention_ignores_rows_past_the_tree(B, model):
     M, nh, d, kv_len = 9, 2, 128, 70
     parent = wl.tree_random(M, 3, 1)
     q, kc, vc = attention_case(M, nh, d, kv_len, parent, 43, cap=256)
-    a = B.ghd_tree_attention(q.cuda(), kc.cuda(), vc.cuda(), torch.from_numpy(parent).cuda(), kv_len)
+    a = B.ghd_tree_attention(q.cuda(), *model.upload_cache(kc, vc), torch.from_numpy(parent).cuda(), kv_len)
     kc[:, kv_len + M:] = 100.0
     vc[:, kv_len + M:] = -100.0
-    b = B.ghd_tree_attention(q.cuda(), kc.cuda(), vc.cuda(), torch.from_numpy(parent).cuda(), kv_len)
+    b = B.ghd_tree_attention(q.cuda(), *model.upload_cache(kc, vc), torch.from_numpy(parent).cuda(), kv_len)
     assert torch.equal(a, b)
+    # not even a NaN there may leak (a zero weight times NaN would be NaN)
+    kc[:, kv_len + M:] = float("nan")
+    vc[:, kv_len + M:] = float("nan")
+    c = B.ghd_tree_attention(q.cuda(), *model.upload_cache(kc, vc), torch.from_numpy(parent).cuda(), kv_len)
+    assert torch.equal(a, c)
 
 
 def run_layer_case(B, model, orc32, shape, M, kv_len, parent, seed):
@@ -210,7 +215,7 @@ def run_layer_case(B, model, orc32, shape, M, kv_len, parent, seed):
                              x16.numpy().astype(np.float32), parent, kv_len, round16=True)
     # GPU
     wd = model.upload_layer(w, shape.d)
-    kc_d, vc_d = kc.cuda(), vc.cuda()
+    kc_d, vc_d = model.upload_cache(kc, vc)
     x = x16.float().cuda()
     cfg = B.make_cfg(shape, cap)
     ws = B.workspace(B.ghd_workspace_bytes(cfg, M, kv_len))
@@ -218,7 +223,7 @@ def run_layer_case(B, model, orc32, shape, M, kv_len, parent, seed):
     assert B.ghd_step_status(ws) == 0
     ok, ma, mr = close(x.cpu().numpy(), ref, 2e-2, 1e-2)
     assert ok, ("residual stream", ma, mr)
-    for name, got, want in (("k", kc_d, kc_o), ("v", vc_d, vc_o)):
+    for name, got, want in (("k", kc_d, kc_o), ("v", model.rows_of_v(vc_d), vc_o)):
         got = got.cpu().numpy()
         # committed rows untouched, rows past the tree untouched
         assert np.array_equal(got[:, :kv_len], want[:, :kv_len]), name
@@ -260,7 +265,7 @@ def run_stack_case(B, model, orc32, shape, M, kv_len, parent, seed):
         shape, [{k: v.numpy() for k, v in w.items()} for w in layers], kcs, vcs,
         {k: v.numpy() for k, v in head.items()}, x16.numpy(), parent, kv_len, round16=True)
     stack = model.build_stack(shape, cap, [model.upload_layer(w, shape.d) for w in layers],
-                              [(k.cuda(), v.cuda()) for k, v in caches], model.upload_head(head))
+                              [model.upload_cache(k, v) for k, v in caches], model.upload_head(head))
     x_out = torch.empty((M, shape.H), dtype=torch.float32, device="cuda")
     pd = torch.from_numpy(parent).cuda()
     ws = B.workspace(B.ghd_workspace_bytes(stack.cfg, M, kv_len))
@@ -395,12 +400,15 @@ def run_big_stack(B, model, orc32, w, L):
         wd = model.upload_layer(lw, shape.d)
         # this layer alone, on the oracle's input (scratch copies of the cache)
         xg = torch.from_numpy(x_in).cuda()
-        B.ghd_verify_layer(cfg, wd, kc.clone(), vc.clone(), xg, pd, kv_len, ws=ws)
+        kc_d, vc_d = model.upload_cache(kc, vc)
+        B.ghd_verify_layer(cfg, wd, kc_d.clone(), vc_d, xg, pd, kv_len, ws=ws)
         assert B.ghd_step_status(ws) == 0
         ok, ma, mr = close(xg.cpu().numpy(), xr, 2e-2, 1e-2)
         assert ok, ("layer", l, ma, mr)
         layers.append(wd)
-        caches.append((kc, vc))
+        # the free-running stack gets this layer's cache too: the tree rows the layer-alone
+        # run just wrote are simply written again
+        caches.append((kc, vc_d))
         del lw, lwh
         if l % 4 == 3:
             say("  layer", l + 1, "of", L, "max abs err (layer alone) %.4f" % ma)
