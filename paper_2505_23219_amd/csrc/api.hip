@@ -92,8 +92,8 @@ static Ws carve(void* ws, int what, int M, int H, int F, int d)
     if (what != 2) w.part = cv.take<float>((size_t)G * 2 * kTG * (Mpad / 16) * 256);
     if (what != 1) {
         w.mask = cv.take<uint64_t>(2 * GHD_MAX_M);
-        w.o_part = cv.take<float>((size_t)G * 2 * Mpad * d);
-        w.ml_part = cv.take<float>((size_t)G * 2 * Mpad * 2);
+        w.o_part = cv.take<float>((size_t)G * Mpad * d);
+        w.ml_part = cv.take<float>((size_t)G * Mpad * 2);
     }
     if (what == 0) {
         w.rope = cv.take<float2>((size_t)GHD_MAX_M * (d / 2));
@@ -120,6 +120,7 @@ static ghd_status check_cfg(const ghd_model_cfg* c, int M, int kv_len)
         return GHD_ERR_SHAPE;
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return GHD_ERR_SHAPE;
     if ((int64_t)kv_len + M > (int64_t)c->kv_capacity || (c->kv_capacity % 8) != 0) return GHD_ERR_CAPACITY;
+    if ((int64_t)c->kv_capacity * c->d >= (1ll << 31)) return GHD_ERR_SHAPE;   // 32-bit offsets inside a head
     return GHD_OK;
 }
 
@@ -382,6 +383,10 @@ ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, con
         return GHD_ERR_SHAPE;
     if (k_stride_tok < d || k_stride_head < 0 || v_stride_head < 0) return GHD_ERR_SHAPE;
     if (v_stride_ch < (int64_t)kv_len + M) return GHD_ERR_CAPACITY;
+    // the kernel indexes inside a head, and counts (head, key tile) pairs, in 32 bits
+    if (k_stride_tok * ((int64_t)kv_len + M) >= (1ll << 31) || v_stride_ch * d >= (1ll << 31) ||
+        (int64_t)nh * (((int64_t)kv_len + M + 63) / 64) >= (1ll << 31))
+        return GHD_ERR_SHAPE;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) ||
         (k_stride_tok % 8) != 0 || (k_stride_head % 8) != 0 || (v_stride_ch % 8) != 0 ||
         (v_stride_head % 8) != 0)

@@ -51,8 +51,8 @@ struct FusedArgs {
     // scratch (device)
     uint32_t* sync;        // kSyncWords
     float* part;           // GEMM partial slots: [G][2][16*MT KiB]
-    float* o_part;         // attention partial slots: [G][2][Mpad][d]
-    float* ml_part;        // [G][2][Mpad][2]
+    float* o_part;         // attention partial states, one per workgroup: [G][Mpad][d]
+    float* ml_part;        // [G][Mpad][2]
     float* x;              // residual stream [M, H] fp32
     half_t* xg16;          // fp16(x * gain of the next RMSNorm / 16) [M, H]: GEMM input
     float* ss;             // sums of squares per 16-column tile: [H/16][Mpad]

@@ -507,6 +507,10 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
 // ---------------------------------------------------------------------------
 // tree attention
 // ---------------------------------------------------------------------------
+// 2^x for x <= 0 (softmax weights): the hardware instruction; results below the smallest
+// normal number flush to zero, which is what a weight that small should be.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 template <int MT, int D>
 struct AttnLds {
     static constexpr int MTW = (MT + 3) / 4;
@@ -528,60 +532,41 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
     constexpr int MTW = (MT + 3) / 4;   // 16-row tiles per wavefront
     constexpr int DS = D / 32, DT = D / 16, CPR = D / 8;
     constexpr int NLD = 64 * CPR / kFT; // 16-byte pieces per thread per tile, for K and for V alike
+    constexpr int NT = (MT <= 4) ? 4 : 2;   // tiles in flight
     using L = AttnLds<MT, D>;
     L& sm = *reinterpret_cast<L*>(cx.lds);
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c = lane & 15, g4 = lane >> 4;
     const int kh = wave >> 2, wq = wave & 3;   // key half of the tile, row-tile slot
-    const int M = a.M, nh = a.nh, T = a.kv_len + a.M;
+    // scalars of the argument block used inside the loops, as plain locals
+    const int M = a.M, nh = a.nh, kv_len = a.kv_len, T = a.kv_len + a.M, Mpad = a.Mpad;
+    const float scale_log2e = a.scale_log2e;
+    uint32_t* const sync = a.sync;
+    float* const o_part = a.o_part;
+    float* const ml_part = a.ml_part;
     const int ntile = (T + 63) >> 6;
-    const Share sh = make_share(nh, ntile, cx.j, cx.G);
-    const long u0 = sh.c0, u1 = sh.c1;
 
     if (barrier_first && !grid_barrier(a, cx)) return false;
-    if (u0 >= u1) return true;
 
-    // Two tiles in flight: registers of set (u - u0) & 1 hold tile u until it is staged.
-    // K piece id -> (row id / CPR, 8 channels id % CPR); V^T piece id -> (channel id / 8,
-    // 8 keys id % 8).
-    half8 kreg[2][NLD], vreg[2][NLD];
-    auto load_tile = [&](auto set, long u) {
-        constexpr int S = decltype(set)::value;
-        int head = (int)(u / ntile), tile = (int)(u % ntile);
-        const half_t* kh_ = kc + (size_t)head * a.stride_head;
-        const half_t* vh_ = vc + (size_t)head * a.v_stride_head;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            int id = tid + kFT * i;
-            int row = id / CPR, ch = id % CPR;
-            int key = min(tile * 64 + row, T - 1);
-            kreg[S][i] = __builtin_nontemporal_load((const half8*)(kh_ + (size_t)key * a.stride_tok + ch * 8));
-            int vch = id >> 3, seg = id & 7;
-            // keys past the capacity are never touched: the last piece is read instead and
-            // zeroed when it is staged
-            long ks = min((long)tile * 64 + seg * 8, a.v_stride_ch - 8);
-            vreg[S][i] = __builtin_nontemporal_load((const half8*)(vh_ + (size_t)vch * a.v_stride_ch + ks));
-        }
-    };
-    auto store_tile = [&](auto set, int tile) {
-        constexpr int S = decltype(set)::value;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            int id = tid + kFT * i;
-            int row = id / CPR, ch = id % CPR;
-            *(half8*)(&sm.k[row * L::KS + ch * 8]) = kreg[S][i];
-            int vch = id >> 3, seg = id & 7;
-            half8 v = vreg[S][i];
-            int nvalid = T - (tile * 64 + seg * 8);      // rows from T on hold no data: zero them,
-            if (nvalid < 8) {                            // a stray NaN times a zero weight is a NaN
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (e >= nvalid) v[e] = (half_t)0;
-            }
-            *(half8*)(&sm.vt[vch * L::VS + seg * 8]) = v;
-        }
-    };
+    // Work shares.  Heads are dealt to the 8 XCDs in contiguous blocks.  Inside an XCD a
+    // workgroup works on one head at a time: with fewer heads than workgroups, every head
+    // gets its own run of workgroups, each taking a contiguous range of the head's key
+    // tiles; otherwise every workgroup takes whole heads.  A head is therefore always
+    // finished inside one XCD (partial states go through that XCD's L2), and the tile loop
+    // of a head has no head change in it.
+    const int nx = (cx.G % 8 == 0) ? 8 : 1;
+    const int Gx = cx.G / nx, x = cx.j / Gx, w = cx.j - x * Gx;
+    const int hx0 = (int)((long)nh * x / nx), Hx = (int)((long)nh * (x + 1) / nx) - hx0;
+    if (Hx == 0) return true;
+    int h_lo, h_hi;          // this workgroup's heads (local to the XCD)
+    if (Hx >= Gx) {
+        h_lo = Hx * w / Gx;
+        h_hi = Hx * (w + 1) / Gx;
+    } else {
+        h_lo = ((w + 1) * Hx - 1) / Gx;    // the head whose run of workgroups contains w
+        h_hi = h_lo + 1;
+    }
 
     // per-wave query rows
     int mrow[MTW];
@@ -597,10 +582,42 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
         alo[t] = mok[t] ? a.mask[2 * mrow[t]] : 0;
         ahi[t] = mok[t] ? a.mask[2 * mrow[t] + 1] : 0;
     }
-    half8 qf[MTW][DS];
-    float mrun[MTW], lrun[MTW];
-    floatx4 oacc[MTW][DT];
-    auto head_begin = [&](int head) {
+    // K piece id -> (row id / CPR, 8 channels id % CPR); V^T piece id -> (channel id / 8,
+    // 8 keys id % 8).  Offsets inside a head fit 32 bits (checked on the host).
+    int k_off[NLD], v_off[NLD], k_row[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        int id = tid + kFT * i;
+        k_row[i] = id / CPR;
+        k_off[i] = (id % CPR) * 8;
+        v_off[i] = (id >> 3) * (int)a.v_stride_ch + (id & 7) * 8;
+    }
+    const int v_last = (int)a.v_stride_ch - 8, st_tok = (int)a.stride_tok;
+    const std::integral_constant<int, 0> s0;
+    const std::integral_constant<int, 1> s1;
+    const std::integral_constant<int, NT == 4 ? 2 : 0> s2;
+    const std::integral_constant<int, NT == 4 ? 3 : 1> s3;
+
+    for (int hl = h_lo; hl < h_hi; ++hl) {
+        const int head = hx0 + hl;
+        // the workgroups first .. first + np - 1 split this head's tiles
+        int first = x * Gx + w, np = 1, me = 0;
+        if (Hx < Gx) {
+            int wl0 = Gx * hl / Hx;                        // head hl's run of local workgroups
+            int wl1 = Gx * (hl + 1) / Hx;
+            first = x * Gx + wl0;
+            np = min(wl1 - wl0, ntile);
+            me = w - wl0;
+        }
+        if (me >= np) continue;                            // more workgroups than tiles
+        const int t0 = ntile * me / np, t1 = ntile * (me + 1) / np;
+        const half_t* kh_ = kc + (size_t)head * a.stride_head;
+        const half_t* vh_ = vc + (size_t)head * a.v_stride_head;
+
+        // query fragments and running state of this head
+        half8 qf[MTW][DS];
+        float mrun[MTW], lrun[MTW];
+        floatx4 oacc[MTW][DT];
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
 #pragma unroll
@@ -614,15 +631,188 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
 #pragma unroll
             for (int e = 0; e < DT; ++e) oacc[t][e] = (floatx4){0.f, 0.f, 0.f, 0.f};
         }
+
+        // NT tiles in flight: registers of set (tile - t0) % NT hold a tile until it is
+        // staged.  A workgroup has few tiles (about 4 at 2048 cached tokens), so the time to
+        // the first byte dominates unless all of them are requested at once.  The loads
+        // are unconditional: past the last tile they all read one valid 16-byte piece (a
+        // broadcast), which keeps the wait counts of the loop exact.
+        half8 kreg[NT][NLD], vreg[NT][NLD];
+        int l_tile = t0;                                   // next tile to request
+        auto load_tile = [&](auto set) {
+            constexpr int S = decltype(set)::value;
+            const bool real = l_tile < t1;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                int key = min(l_tile * 64 + k_row[i], T - 1);
+                const half_t* kp = kh_ + key * st_tok + k_off[i];
+                // keys past the capacity are never touched: the last piece is read instead
+                // and zeroed when it is staged
+                int over = max(l_tile * 64 + (int)((tid + kFT * i) & 7) * 8 - v_last, 0);
+                const half_t* vp = vh_ + v_off[i] + l_tile * 64 - over;
+                kreg[S][i] = __builtin_nontemporal_load((const half8*)(real ? kp : kc));
+                vreg[S][i] = __builtin_nontemporal_load((const half8*)(real ? vp : vc));
+            }
+            ++l_tile;
+        };
+        auto store_tile = [&](auto set, int tile) {
+            constexpr int S = decltype(set)::value;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                int id = tid + kFT * i;
+                *(half8*)(&sm.k[k_row[i] * L::KS + k_off[i]]) = kreg[S][i];
+                int vch = id >> 3, seg = id & 7;
+                half8 v = vreg[S][i];
+                int nvalid = T - (tile * 64 + seg * 8);  // rows from T on hold no data: zero them,
+                if (nvalid < 8) {                        // a stray NaN times a zero weight is a NaN
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e >= nvalid) v[e] = (half_t)0;
+                }
+                *(half8*)(&sm.vt[vch * L::VS + seg * 8]) = v;
+            }
+        };
+        load_tile(s0);
+        load_tile(s1);
+        if constexpr (NT == 4) {
+            load_tile(s2);
+            load_tile(s3);
+        }
+        int p_tile = t0;                                   // the tile being processed
+        auto do_tile = [&](auto set) {
+            const int tile = p_tile++;
+            __syncthreads();            // previous tile fully consumed
+            store_tile(set, tile);
+            __syncthreads();
+            load_tile(set);
+        if (!wave_active) return;
+        const int key0 = tile * 64 + kh * 32;    // this wavefront's 32 keys
+        const bool committed = key0 + 32 <= kv_len;   // every key visible to every row
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+            floatx4 s[2];
+            float tmax = -INFINITY;
+            if (committed) {
+#pragma unroll
+                for (int jx = 0; jx < 2; ++jx) {
+                    s[jx] = (floatx4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ds = 0; ds < DS; ++ds) {
+                        half8 kf = *(const half8*)(&sm.k[(kh * 32 + jx * 16 + c) * L::KS + ds * 32 + g4 * 8]);
+                        s[jx] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[t][ds], s[jx], 0, 0, 0);
+                    }
+                    s[jx] *= scale_log2e;
+                    tmax = fmaxf(tmax, fmaxf(fmaxf(s[jx][0], s[jx][1]), fmaxf(s[jx][2], s[jx][3])));
+                }
+            } else {
+                bool sub_any[2];
+#pragma unroll
+                for (int jx = 0; jx < 2; ++jx) {
+                    const int kbase = key0 + jx * 16;
+                    bool vis_any;
+                    if (kbase + 16 <= kv_len) {
+                        vis_any = true;
+                    } else {
+                        bool mine = false;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            int key = kbase + g4 * 4 + r;
+                            bool vis = key < kv_len;
+                            if (key >= kv_len && key < T) {
+                                int jn = key - kv_len;
+                                vis = (jn < 64 ? (alo[t] >> jn) : (ahi[t] >> (jn - 64))) & 1ull;
+                            }
+                            mine = mine || (vis && mok[t]);
+                        }
+                        vis_any = __ballot(mine) != 0ull;
+                    }
+                    sub_any[jx] = vis_any;
+                    s[jx] = (floatx4){0.f, 0.f, 0.f, 0.f};
+                    if (vis_any) {
+#pragma unroll
+                        for (int ds = 0; ds < DS; ++ds) {
+                            half8 kf = *(const half8*)(&sm.k[(kh * 32 + jx * 16 + c) * L::KS + ds * 32 + g4 * 8]);
+                            s[jx] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[t][ds], s[jx], 0, 0, 0);
+                        }
+                    }
+                }
+                if (!(sub_any[0] || sub_any[1])) continue;
+#pragma unroll
+                for (int jx = 0; jx < 2; ++jx) {
+                    const int kbase = key0 + jx * 16;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        int key = kbase + g4 * 4 + r;
+                        bool vis = sub_any[jx] && key < kv_len;
+                        if (sub_any[jx] && key >= kv_len && key < T) {
+                            int jn = key - kv_len;
+                            vis = (jn < 64 ? (alo[t] >> jn) : (ahi[t] >> (jn - 64))) & 1ull;
+                        }
+                        float v = vis ? s[jx][r] * scale_log2e : -INFINITY;
+                        s[jx][r] = v;
+                        tmax = fmaxf(tmax, v);
+                    }
+                }
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            float mnew = fmaxf(mrun[t], tmax);
+            float muse = (mnew == -INFINITY) ? 0.f : mnew;
+            float alpha = fast_exp2(mrun[t] - muse);
+            mrun[t] = mnew;
+            float lsum = 0.f;
+            half8 pf;
+#pragma unroll
+            for (int jx = 0; jx < 2; ++jx)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float pv = fast_exp2(s[jx][r] - muse);
+                    lsum += pv;
+                    pf[jx * 4 + r] = (half_t)pv;
+                }
+            lrun[t] = lrun[t] * alpha + lsum;
+#pragma unroll
+            for (int e = 0; e < DT; ++e) {
+                oacc[t][e] *= alpha;
+                const half_t* vrow = &sm.vt[(e * 16 + c) * L::VS + kh * 32];
+                half4 a0 = *(const half4*)(vrow + g4 * 4);
+                half4 a1 = *(const half4*)(vrow + 16 + g4 * 4);
+                half8 vf = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                oacc[t][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pf, oacc[t][e], 0, 0, 0);
+            }
+        }
     };
-    // parts of a head: workgroups first..last, one partial state each
-    auto slot_index = [&](int wg, int head) -> size_t {
-        return (size_t)wg * 2 + (sh.begins_in(wg, head) ? 0 : 1);
-    };
-    // Ends this workgroup's share of a head: the wavefronts of the second key half hand
-    // their state over through LDS, their partners merge it into their own (online-softmax
-    // rescale) and store the workgroup's partial state.  Called by all threads.
-    auto head_flush = [&](int head) {
+        // Whole groups of NT tiles run in a branch-free loop; the rest is a chain of nested
+        // conditions, so every tile is only reachable through its predecessor and the number
+        // of loads younger than the one being waited for is known.
+        {
+            int u = t0;
+            if constexpr (NT == 4) {
+                for (; u + 3 < t1; u += 4) {
+                    do_tile(s0);
+                    do_tile(s1);
+                    do_tile(s2);
+                    do_tile(s3);
+                }
+                if (u < t1) {
+                    do_tile(s0);
+                    if (u + 1 < t1) {
+                        do_tile(s1);
+                        if (u + 2 < t1) do_tile(s2);
+                    }
+                }
+            } else {
+                for (; u + 1 < t1; u += 2) {
+                    do_tile(s0);
+                    do_tile(s1);
+                }
+                if (u < t1) do_tile(s0);
+            }
+        }
+
+        // ---- end of this workgroup's share of the head: the wavefronts of the second key
+        //      half hand their state over through LDS, their partners merge it into their
+        //      own (online-softmax rescale) and store the workgroup's partial state
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
             float l = lrun[t];
@@ -641,176 +831,45 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
         }
         __syncthreads();
         if (kh == 0 && wave_active) {
-            size_t slot = slot_index(cx.j, head);
 #pragma unroll
             for (int t = 0; t < MTW; ++t) {
                 float mb = sm.m2[wq][t][lane], lb = sm.l2[wq][t][lane];
                 float mx = fmaxf(mrun[t], mb);
-                float wa = (mrun[t] == -INFINITY) ? 0.f : exp2f(mrun[t] - mx);
-                float wb = (mb == -INFINITY) ? 0.f : exp2f(mb - mx);
+                float wa = (mrun[t] == -INFINITY) ? 0.f : fast_exp2(mrun[t] - mx);
+                float wb = (mb == -INFINITY) ? 0.f : fast_exp2(mb - mx);
                 float l = lrun[t] * wa + lb * wb;
                 if (!mok[t]) continue;
-                size_t row = slot * a.Mpad + mrow[t];
+                size_t row = (size_t)cx.j * Mpad + mrow[t];
 #pragma unroll
                 for (int e = 0; e < DT; ++e) {
                     floatx4 ob = sm.o2[wq][t][e][lane];
-                    *(floatx4*)(a.o_part + row * D + e * 16 + g4 * 4) = oacc[t][e] * wa + ob * wb;
+                    *(floatx4*)(o_part + row * D + e * 16 + g4 * 4) = oacc[t][e] * wa + ob * wb;
                 }
                 if (g4 == 0) {
-                    a.ml_part[row * 2] = mx;
-                    a.ml_part[row * 2 + 1] = l;
+                    ml_part[row * 2] = mx;
+                    ml_part[row * 2 + 1] = l;
                 }
             }
         }
-        __syncthreads();   // the hand-over buffers may be refilled
-    };
+        __syncthreads();   // partial state acknowledged by the L2; hand-over buffers free again
+        if (tid == 0) atomicAdd(sync + kCntAttn + head * kCntStride, 1u);
 
-    const std::integral_constant<int, 0> s0;
-    const std::integral_constant<int, 1> s1;
-    load_tile(s0, u0);
-    load_tile(s1, min(u0 + 1, u1 - 1));
-    int cur = (int)(u0 / ntile);
-    head_begin(cur);
-    auto do_tile = [&](auto set, auto prefetch, long u) {
-        int head = (int)(u / ntile), tile = (int)(u % ntile);
-        if (head != cur) {
-            head_flush(cur);
-            cur = head;
-            head_begin(cur);
-        }
-        __syncthreads();            // previous tile fully consumed
-        store_tile(set, tile);
-        __syncthreads();
-        if constexpr (decltype(prefetch)::value) load_tile(set, u + 2);
-        if (!wave_active) return;
-        const int key0 = tile * 64 + kh * 32;    // this wavefront's 32 keys
-#pragma unroll
-        for (int t = 0; t < MTW; ++t) {
-            floatx4 s[2];
-            bool sub_any[2];
-#pragma unroll
-            for (int jx = 0; jx < 2; ++jx) {
-                const int kbase = key0 + jx * 16;
-                bool vis_any;
-                if (kbase + 16 <= a.kv_len) {
-                    vis_any = true;
-                } else {
-                    bool mine = false;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        int key = kbase + g4 * 4 + r;
-                        bool vis = key < a.kv_len;
-                        if (key >= a.kv_len && key < T) {
-                            int jn = key - a.kv_len;
-                            vis = (jn < 64 ? (alo[t] >> jn) : (ahi[t] >> (jn - 64))) & 1ull;
-                        }
-                        mine = mine || (vis && mok[t]);
-                    }
-                    vis_any = __ballot(mine) != 0ull;
-                }
-                sub_any[jx] = vis_any;
-                s[jx] = (floatx4){0.f, 0.f, 0.f, 0.f};
-                if (vis_any) {
-#pragma unroll
-                    for (int ds = 0; ds < DS; ++ds) {
-                        half8 kf = *(const half8*)(&sm.k[(kh * 32 + jx * 16 + c) * L::KS + ds * 32 + g4 * 8]);
-                        s[jx] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[t][ds], s[jx], 0, 0, 0);
-                    }
-                }
-            }
-            if (!(sub_any[0] || sub_any[1])) continue;
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int jx = 0; jx < 2; ++jx) {
-                const int kbase = key0 + jx * 16;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    int key = kbase + g4 * 4 + r;
-                    bool vis = sub_any[jx] && key < a.kv_len;
-                    if (sub_any[jx] && key >= a.kv_len && key < T) {
-                        int jn = key - a.kv_len;
-                        vis = (jn < 64 ? (alo[t] >> jn) : (ahi[t] >> (jn - 64))) & 1ull;
-                    }
-                    float v = vis ? s[jx][r] * a.scale_log2e : -INFINITY;
-                    s[jx][r] = v;
-                    tmax = fmaxf(tmax, v);
-                }
-            }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            float mnew = fmaxf(mrun[t], tmax);
-            float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            float alpha = exp2f(mrun[t] - muse);
-            mrun[t] = mnew;
-            float lsum = 0.f;
-            half8 pf;
-#pragma unroll
-            for (int jx = 0; jx < 2; ++jx)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float pv = exp2f(s[jx][r] - muse);
-                    lsum += pv;
-                    pf[jx * 4 + r] = (half_t)pv;
-                }
-            lrun[t] = lrun[t] * alpha + lsum;
-#pragma unroll
-            for (int e = 0; e < DT; ++e) {
-                oacc[t][e] *= alpha;
-                const half_t* vrow = &sm.vt[(e * 16 + c) * L::VS + kh * 32];
-                half4 a0 = *(const half4*)(vrow + g4 * 4);
-                half4 a1 = *(const half4*)(vrow + 16 + g4 * 4);
-                half8 vf = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-                oacc[t][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pf, oacc[t][e], 0, 0, 0);
-            }
-        }
-    };
-    // Tile u requests tile u + 2 while one exists; the loads of the steady-state loop are
-    // unconditional, so the wait before a tile is staged counts exactly the younger loads.
-    {
-        const std::true_type pf;
-        const std::false_type nopf;
-        long u = u0;
-        for (; u + 3 < u1; u += 2) {
-            do_tile(s0, pf, u);
-            do_tile(s1, pf, u + 1);
-        }
-        const int rest = (int)(u1 - u);
-        if (rest == 3) {
-            do_tile(s0, pf, u);
-            do_tile(s1, nopf, u + 1);
-            do_tile(s0, nopf, u + 2);
-        } else if (rest == 2) {
-            do_tile(s0, nopf, u);
-            do_tile(s1, nopf, u + 1);
-        } else {
-            do_tile(s0, nopf, u);
-        }
-    }
-    head_flush(cur);
-    int hfirst = (int)(u0 / ntile), hlast = (int)((u1 - 1) / ntile);
-    if (tid == 0)
-        for (int head = hfirst; head <= hlast; ++head)
-            atomicAdd(a.sync + kCntAttn + head * kCntStride, 1u);
-
-    // ---- merge: every workgroup of a head combines its share of the rows
-    for (int head = hfirst; head <= hlast; ++head) {
-        int first = sh.first_of(head), last = sh.last_of(head);
-        int np = last - first + 1, me = cx.j - first;     // np <= 32 parts
-        if (tid == 0) bounded_wait(a.sync, a.sync + kCntAttn + head * kCntStride, (uint32_t)np * (epoch + 1), 2000u);
+        // ---- merge: every workgroup of the head combines its share of the rows
+        if (tid == 0) bounded_wait(sync, sync + kCntAttn + head * kCntStride, (uint32_t)np * (epoch + 1), 2000u);
         __syncthreads();
         int r0 = M * me / np, r1 = M * (me + 1) / np;
         for (int m = r0 + wave; m < r1; m += 8) {
-            // lane q holds the statistics of part q
+            // lane p holds the statistics of part p (np <= 64: one XCD's workgroups)
             float mq = -INFINITY, lq = 0.f;
             size_t rowq = 0;
             if (lane < np) {
-                rowq = slot_index(first + lane, head) * a.Mpad + m;
-                mq = a.ml_part[rowq * 2];
-                lq = a.ml_part[rowq * 2 + 1];
+                rowq = (size_t)(first + lane) * Mpad + m;
+                mq = ml_part[rowq * 2];
+                lq = ml_part[rowq * 2 + 1];
             }
             float mx = mq;
             for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-            float wq_ = (mq == -INFINITY) ? 0.f : exp2f(mq - mx);
+            float wq_ = (mq == -INFINITY) ? 0.f : fast_exp2(mq - mx);
             float den = wq_ * lq;
             for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off);
             // weighted sum of the parts' outputs, parts in index order, 8 loads in flight
@@ -825,7 +884,7 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
                     size_t row = (size_t)__shfl((long long)rowq, qq);
                     w8[qi] = (q0 + qi < np) ? __shfl(wq_, qq) : 0.f;
 #pragma unroll
-                    for (int e = 0; e < D / 64; ++e) t[qi][e] = a.o_part[row * D + e * 64 + lane];
+                    for (int e = 0; e < D / 64; ++e) t[qi][e] = o_part[row * D + e * 64 + lane];
                 }
 #pragma unroll
                 for (int qi = 0; qi < 8; ++qi)
@@ -836,6 +895,9 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
             for (int e = 0; e < D / 64; ++e)
                 out[((size_t)m * nh + head) * D + e * 64 + lane] = (half_t)(num[e] / den);
         }
+        // a workgroup that goes on to another head reuses its partial-state slot: wait until
+        // the other parts have read it
+        if (hl + 1 < h_hi) __syncthreads();
     }
     return true;
 }
