@@ -1,8 +1,10 @@
-// Greedy acceptance: after the verification pass the step "falls back to the
-// longest validated prefix" (Ghidorah, section 2.3).  Two launches:
-//   k_row_argmax : amax[i] = lowest index of the largest logit of row i,
-//                  a wavefront-level (value, index) reduction per row;
-//   k_accept     : a node is valid iff every edge (p -> c) on its root path has
+// Greedy acceptance: after the verification pass the longest root path that the model
+// itself would have produced is kept (Ghidorah, section 2.3).  Two launches:
+//   k_row_argmax : every row of the logits is cut into kArgSeg segments; a workgroup
+//                  finds the (largest value, lowest index) of one segment with a
+//                  wavefront-level reduction;
+//   k_accept     : merges the segments into amax[i] (lowest index on ties); a node is
+//                  valid iff every edge (p -> c) on its root path has
 //                  tokens[c] == amax[p]; the deepest valid node (lowest index on
 //                  ties) wins and its root path is written out.
 #include "common.h"
@@ -17,16 +19,29 @@ __device__ inline void argmax_merge(float& v, int& i, float ov, int oi)
     }
 }
 
+constexpr int kArgSeg = 8;   // segments per row
+
 __global__ __launch_bounds__(256) void k_row_argmax(const float* __restrict__ logits, int V,
-                                                    int32_t* __restrict__ amax)
+                                                    float* __restrict__ seg_v,
+                                                    int32_t* __restrict__ seg_i)
 {
     __shared__ float s_v[4];
     __shared__ int s_i[4];
-    const float* row = logits + (size_t)blockIdx.x * V;
+    const int rowi = blockIdx.x / kArgSeg, seg = blockIdx.x % kArgSeg;
+    const float* row = logits + (size_t)rowi * V;
+    const int lo = (int)((long)V * seg / kArgSeg), hi = (int)((long)V * (seg + 1) / kArgSeg);
     int tid = threadIdx.x;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int idx = tid; idx < V; idx += 256) argmax_merge(bv, bi, row[idx], idx);
+    // four independent loads in flight per thread
+    for (int idx = lo + tid; idx < hi; idx += 1024) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = (idx + 256 * u < hi) ? row[idx + 256 * u] : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (idx + 256 * u < hi) argmax_merge(bv, bi, v[u], idx + 256 * u);
+    }
     for (int off = 32; off > 0; off >>= 1) {
         float ov = __shfl_xor(bv, off);
         int oi = __shfl_xor(bi, off);
@@ -39,11 +54,13 @@ __global__ __launch_bounds__(256) void k_row_argmax(const float* __restrict__ lo
     __syncthreads();
     if (tid == 0) {
         for (int w = 1; w < 4; ++w) argmax_merge(bv, bi, s_v[w], s_i[w]);
-        amax[blockIdx.x] = bi;
+        seg_v[rowi * kArgSeg + seg] = bv;
+        seg_i[rowi * kArgSeg + seg] = bi;
     }
 }
 
-__global__ __launch_bounds__(128) void k_accept(const int32_t* __restrict__ amax,
+__global__ __launch_bounds__(128) void k_accept(const float* __restrict__ seg_v,
+                                                const int32_t* __restrict__ seg_i,
                                                 const int32_t* __restrict__ tokens,
                                                 const int32_t* __restrict__ parent, int M,
                                                 int32_t* __restrict__ res,
@@ -55,7 +72,10 @@ __global__ __launch_bounds__(128) void k_accept(const int32_t* __restrict__ amax
     if (i < M) {
         s_par[i] = parent[i];
         s_tok[i] = tokens[i];
-        s_amax[i] = amax[i];
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int sg = 0; sg < kArgSeg; ++sg) argmax_merge(bv, bi, seg_v[i * kArgSeg + sg], seg_i[i * kArgSeg + sg]);
+        s_amax[i] = bi;
         if (amax_out) amax_out[i] = s_amax[i];
     }
     __syncthreads();
@@ -85,12 +105,17 @@ __global__ __launch_bounds__(128) void k_accept(const int32_t* __restrict__ amax
     }
 }
 
+size_t accept_workspace_bytes() { return (size_t)GHD_MAX_M * kArgSeg * 8; }
+
 ghd_status launch_accept(const float* logits, const int32_t* tokens, const int32_t* parent, int M,
-                         int V, int32_t* res, int32_t* amax_out, int32_t* amax_ws, hipStream_t st)
+                         int V, int32_t* res, int32_t* amax_out, void* ws, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_row_argmax, dim3(M), dim3(256), 0, st, logits, V, amax_ws);
-    hipLaunchKernelGGL(k_accept, dim3(1), dim3(128), 0, st, (const int32_t*)amax_ws, tokens, parent,
-                       M, res, amax_out);
+    // workspace: per-segment maxima [GHD_MAX_M][kArgSeg] float, then their indices
+    float* seg_v = (float*)ws;
+    int32_t* seg_i = (int32_t*)(seg_v + GHD_MAX_M * kArgSeg);
+    hipLaunchKernelGGL(k_row_argmax, dim3(M * kArgSeg), dim3(256), 0, st, logits, V, seg_v, seg_i);
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(128), 0, st, (const float*)seg_v,
+                       (const int32_t*)seg_i, tokens, parent, M, res, amax_out);
     return check_launch();
 }
 

@@ -508,7 +508,7 @@ ghd_status ghd_step_status(const void* ws, int32_t* status_host, void* stream)
 size_t ghd_accept_workspace_bytes(int M)
 {
     if (M < 1 || M > GHD_MAX_M) return 0;
-    return align_up(GHD_MAX_M * sizeof(int32_t), 256);
+    return align_up(accept_workspace_bytes(), 256);
 }
 
 ghd_status ghd_accept_greedy(const float* logits, const int32_t* tokens_dev,
@@ -520,7 +520,7 @@ ghd_status ghd_accept_greedy(const float* logits, const int32_t* tokens_dev,
     if (!ws) return GHD_ERR_WORKSPACE;
     if (((uintptr_t)ws & 3) != 0) return GHD_ERR_ALIGN;
     if (ws_bytes < ghd_accept_workspace_bytes(M)) return GHD_ERR_WORKSPACE;
-    return launch_accept(logits, tokens_dev, parent_dev, M, V, res_dev, amax_dev, (int32_t*)ws,
+    return launch_accept(logits, tokens_dev, parent_dev, M, V, res_dev, amax_dev, ws,
                          (hipStream_t)stream);
 }
 

@@ -22,6 +22,7 @@ ghd_status hip_fail(hipError_t e);
 ghd_status check_launch();
 
 ghd_status launch_accept(const float* logits, const int32_t* tokens, const int32_t* parent, int M,
-                         int V, int32_t* res, int32_t* amax_out, int32_t* amax_ws, hipStream_t st);
+                         int V, int32_t* res, int32_t* amax_out, void* ws, hipStream_t st);
+size_t accept_workspace_bytes();
 
 }  // namespace ghd

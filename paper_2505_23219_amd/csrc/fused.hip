@@ -337,24 +337,24 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     else if (c0 < c1) x_fetch(c0);
     if (barrier_first && !grid_barrier(a, cx)) return false;
 
+    if (!barrier_first) w_first();     // the ring queues up behind the first x chunk
+
     // ---- RMSNorm factor per row from the per-tile sums of squares ss[tile][Mpad]:
     //      thread (rq, part) adds 4 rows of every P-th tile, lanes of a wavefront that share
-    //      rq are combined by shuffles, the 8 wavefronts through LDS; fixed order throughout
-    const int n_ss = op.K >> 4;
-    const int RQ = a.Mpad >> 2, P = kFT / RQ;
-    const int rq = tid % RQ, part = tid / RQ;
-    floatx4 sst[8];
-    auto ss_fetch = [&](int t0) {
-#pragma unroll
-        for (int q = 0; q < 8; ++q)
-            sst[q] = *(const floatx4*)(a.ss + (size_t)min(t0 + q * P, n_ss - 1) * a.Mpad + rq * 4);
-    };
-    if (op.rscale) ss_fetch(part);
-    if (!barrier_first) w_first();     // the ring queues up behind x and the first ss batch
-    if (op.rscale) {
+    //      rq are combined by shuffles, the 8 wavefronts through LDS; fixed order throughout.
+    //      Only the epilogue needs it, so it is computed late: after this workgroup has
+    //      signalled its partial sums, while the other parts of the group are still arriving.
+    bool rinv_ready = !op.rscale;
+    auto compute_rinv = [&]() {
+        const int n_ss = op.K >> 4;
+        const int RQ = a.Mpad >> 2, P = kFT / RQ;
+        const int rq = tid % RQ, part = tid / RQ;
         floatx4 s4 = {0.f, 0.f, 0.f, 0.f};
         for (int t0 = part; t0 < n_ss; t0 += 8 * P) {
-            if (t0 != part) ss_fetch(t0);
+            floatx4 sst[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                sst[q] = *(const floatx4*)(a.ss + (size_t)min(t0 + q * P, n_ss - 1) * a.Mpad + rq * 4);
 #pragma unroll
             for (int q = 0; q < 8; ++q)
                 if (t0 + q * P < n_ss) s4 += sst[q];
@@ -371,7 +371,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             s_rinv[tid] = (1.0f / kXgScale) / sqrtf(tot / (float)op.K + a.eps);
         }
         __syncthreads();
-    }
+        rinv_ready = true;
+    };
 
     floatx4 acc[2][MT];
     auto acc_zero = [&]() {
@@ -396,6 +397,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     auto flush = [&](int grp) {
         int first = group_first(grp), last = group_last(grp);
         if (first == last) {
+            if (!rinv_ready) compute_rinv();
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -472,6 +474,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         }
 
         // ---- cooperative finish of the split groups this workgroup took part in
+        if (!rinv_ready) compute_rinv();
         int gfirst = (int)(c0 / op.ncpg), glast = (int)((c1 - 1) / op.ncpg);
         for (int grp = gfirst; grp <= glast; ++grp) {
             int first = group_first(grp), last = group_last(grp);
@@ -1113,9 +1116,11 @@ ghd_status launch_fused(const FusedArgs& a, hipStream_t st)
 }
 
 // ---- setup kernel ------------------------------------------------------------
-// Block 0: tree tables (depth, ancestor masks, rotary table).  Blocks 1..kZeroBlocks:
-// zero the sync block.  Further blocks: one per 16-column tile of the residual stream,
+// Blocks 0..kTreeBlocks-1: tree tables (every block walks the parents itself; block 0
+// writes the ancestor masks, each block a slice of the rotary table).  The next kZeroBlocks
+// blocks zero the sync block.  Further blocks: one per 16-column tile of the residual stream,
 // writing x = widen(x_in), the tile's sums of squares and the gain-scaled fp16 image.
+constexpr int kTreeBlocks = 8;
 constexpr int kZeroBlocks = 32;
 
 __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync,
@@ -1129,7 +1134,7 @@ __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync
                                                      half_t* __restrict__ xg16)
 {
     int tid = threadIdx.x;
-    if (blockIdx.x == 0) {
+    if (blockIdx.x < kTreeBlocks) {
         __shared__ int32_t s_parent[GHD_MAX_M];
         __shared__ int32_t s_depth[GHD_MAX_M];
         if (!parent) return;
@@ -1146,26 +1151,30 @@ __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync
                 ++dep;
             }
             s_depth[tid] = dep;
-            mask[2 * tid] = lo;
-            mask[2 * tid + 1] = hi;
+            if (blockIdx.x == 0) {
+                mask[2 * tid] = lo;
+                mask[2 * tid + 1] = hi;
+            }
         }
         __syncthreads();
         if (rope) {
-            int half = d / 2;
-            for (int e = tid; e < M * half; e += 256) {
+            // angle = position * base^(-2j/d), evaluated in double
+            const int half = d / 2;
+            const double c = -2.0 / d * log2((double)rope_base);
+            for (int e = blockIdx.x * 256 + tid; e < M * half; e += kTreeBlocks * 256) {
                 int m = e / half, j = e % half;
-                double ang = (double)(kv_len + s_depth[m]) * pow((double)rope_base, -2.0 * j / d);
+                double ang = (double)(kv_len + s_depth[m]) * exp2(c * j);
                 rope[e] = make_float2((float)cos(ang), (float)sin(ang));
             }
         }
         return;
     }
-    if (blockIdx.x <= kZeroBlocks) {
-        for (int i = (blockIdx.x - 1) * 256 + tid; i < kSyncWords; i += kZeroBlocks * 256) sync[i] = 0;
+    if (blockIdx.x < kTreeBlocks + kZeroBlocks) {
+        for (int i = (blockIdx.x - kTreeBlocks) * 256 + tid; i < kSyncWords; i += kZeroBlocks * 256) sync[i] = 0;
         return;
     }
     // residual stream tiles: thread -> (row m, column within the 16-wide tile)
-    int tile = blockIdx.x - 1 - kZeroBlocks;
+    int tile = blockIdx.x - kTreeBlocks - kZeroBlocks;
     for (int e = tid; e < Mpad * 16; e += 256) {
         int m = e >> 4, col = tile * 16 + (e & 15);
         float v = 0.f;
@@ -1188,7 +1197,7 @@ ghd_status launch_fused_setup(uint32_t* sync, const int32_t* parent, int M, int 
                               const half_t* x_in16, int H, float* ss, const half_t* gain,
                               half_t* xg16, hipStream_t st)
 {
-    int blocks = 1 + kZeroBlocks + (ss ? H / 16 : 0);
+    int blocks = kTreeBlocks + kZeroBlocks + (ss ? H / 16 : 0);
     hipLaunchKernelGGL(k_fused_setup, dim3(blocks), dim3(256), 0, st, sync, parent, M, Mpad, kv_len, d,
                        rope_base, mask, rope, x, x_in16, H, ss, gain, xg16);
     return check_launch();
