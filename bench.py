@@ -64,7 +64,7 @@ def recorded_traffic():
     """HBM bytes per launch of the linear-layer kernel from the committed counter
     summary (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known
     size); None when the kernel sources have changed since."""
-    path = os.path.join(ROOT, "profiles", "k_fused_linear_stack7b_hbm_traffic.md")
+    path = os.path.join(ROOT, "profiles", "k_linear_stack7b_hbm_traffic.md")
     if not os.path.exists(path):
         return None
     from paper_2505_23219_amd.profile_summary import source_digest
@@ -112,12 +112,12 @@ def linear_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w
     achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
     att_ms, att_n = timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, 2, steps)
     kv_bytes = 2 * 2 * s.L * s.nh * s.d * (kv_len + w.M)
-    return {"bound": "hbm", "kernel": "k_fused<MT, 128, MODE_LINEAR>", "achieved": round(achieved, 1),
+    return {"bound": "hbm", "kernel": "k_linear<MT>", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": recorded_traffic(), "launches_per_step": per_step,
             "avg_launch_us": round(avg_ms * 1e3, 2),
             "algorithmic_bytes_per_launch": int(per_launch_bytes),
-            "attention": {"kernel": "k_fused<MT, D, MODE_ATTN>", "launches_per_step": att_n // steps,
+            "attention": {"kernel": "k_attention<MT, D>", "launches_per_step": att_n // steps,
                           "avg_launch_us": round(att_ms / att_n * 1e3, 2),
                           "algorithmic_bytes_per_launch": int(kv_bytes / (att_n // steps)),
                           "achieved": round(kv_bytes / (att_n // steps) / (att_ms / att_n * 1e-3) / 1e9, 1)}}

@@ -133,8 +133,6 @@ static void fill_common(FusedArgs& a, const ghd_model_cfg* c, const Ws& w, int M
     a.nh = c->nh;
     a.d = c->d;
     a.F = c->F;
-    a.V = c->V;
-    a.L = c->L;
     a.stride_head = (int64_t)c->kv_capacity * c->d;
     a.stride_tok = c->d;
     a.v_stride_head = (int64_t)c->kv_capacity * c->d;
@@ -163,18 +161,6 @@ static ghd_status check_layer(const ghd_layer_weights* w, const ghd_kv* kv)
         !aligned16(w->Wgu) || !aligned16(w->Wdown) || !aligned16(kv->k) || !aligned16(kv->v))
         return GHD_ERR_ALIGN;
     return GHD_OK;
-}
-
-static void fill_layer(LayerPtrs& lp, const ghd_layer_weights* w, const ghd_kv* kv)
-{
-    lp.g_attn = (const half_t*)w->g_attn;
-    lp.Wqkv = (const half8*)w->Wqkv;
-    lp.Wo = (const half8*)w->Wo;
-    lp.g_ffn = (const half_t*)w->g_ffn;
-    lp.Wgu = (const half8*)w->Wgu;
-    lp.Wdown = (const half8*)w->Wdown;
-    lp.kc = (half_t*)kv->k;
-    lp.vc = (half_t*)kv->v;
 }
 
 

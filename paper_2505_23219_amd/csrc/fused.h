@@ -1,4 +1,4 @@
-// Argument block of the persistent verification kernel (fused.hip).
+// Argument block and launchers of the persistent kernels (fused.hip).
 #pragma once
 #include "common.h"
 
@@ -9,16 +9,15 @@ constexpr int kTG = 16;         // 16-row weight tiles per row group (8 wavefron
 constexpr int kCH = 4;          // k-steps (32 columns) per staged chunk of x
 constexpr int kGroupRows = kTG * 16;
 constexpr int kChunkCols = kCH * 32;
-constexpr int kMaxLayers = 48;  // per-layer pointers travel as kernel arguments
+constexpr int kMaxLayers = 48;  // the counter epochs (one per layer) are laid out for this many
 
 enum { EPI_STORE_F32 = 0, EPI_STORE_F16 = 1, EPI_RESID = 2, EPI_SWIGLU = 3, EPI_QKV = 4 };
-enum { MODE_STACK = 0, MODE_LAYER = 1, MODE_LINEAR = 2, MODE_ATTN = 3 };
+enum { MODE_LINEAR = 0, MODE_ATTN = 1 };
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 
 // The sync block (uint32 words), zeroed by the set-up kernel.  Every item counter has a
 // 128-byte line of its own (kCntStride words apart): the workgroups of one item poll and
 // bump it without disturbing the others.
-constexpr int kSyncBarrier = 0;   // grid-barrier arrivals (monotonic)
 constexpr int kSyncStatus = 1;    // 0 = ok, else the code of the wait that gave up
 constexpr int kCntStride = 32;
 constexpr int kSyncCnt = 32;                          // first counter line
@@ -30,21 +29,10 @@ constexpr int kCntLm = kCntDown + 512 * kCntStride;   // up to 1024 row groups
 constexpr int kCntAttn = kCntLm + 1024 * kCntStride;  // up to 256 heads
 constexpr int kSyncWords = kCntAttn + 256 * kCntStride;
 
-struct LayerPtrs {
-    const half_t* g_attn;
-    const half8* Wqkv;
-    const half8* Wo;
-    const half_t* g_ffn;
-    const half8* Wgu;
-    const half8* Wdown;
-    half_t* kc;
-    half_t* vc;
-};
-
 struct FusedArgs {
     int mode;
     int M, Mpad, kv_len;
-    int H, nh, d, F, V, L;
+    int H, nh, d, F;
     int64_t stride_head, stride_tok;       // K cache: (head, row, channel) at h*sh + t*st + c
     int64_t v_stride_head, v_stride_ch;    // V cache, channel-major: (head, channel, row) at h*vh + c*vc + t
     float eps, scale_log2e;
@@ -61,11 +49,7 @@ struct FusedArgs {
     half_t* a16;           // [M, F]
     const float2* rope;    // (cos, sin) [M][d/2]
     const uint64_t* mask;  // ancestor masks [M][2]
-    // model tail
-    const half_t* g_final;
-    const half8* Wlm;
-    float* logits;         // [M, V]
-    // single-op modes
+    // linear-layer launch
     const half8* lin_W;
     const half_t* lin_x;
     void* lin_y;
@@ -77,9 +61,9 @@ struct FusedArgs {
     uint32_t lin_epoch;    // how often that array was used since it was zeroed
     uint32_t att_epoch;    // same for the attention head counters
     int64_t lin_ldx, lin_ldy;
+    // attention launch
     const half_t *att_q, *att_k, *att_v;
     half_t* att_out;
-    LayerPtrs layer[kMaxLayers];
 };
 
 ghd_status launch_fused(const FusedArgs& a, hipStream_t st);

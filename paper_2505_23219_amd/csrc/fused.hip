@@ -1,14 +1,12 @@
-// The verification step as ONE persistent kernel.
+// The two persistent kernels of the verification step: skinny linear layers and
+// tree attention.
 //
-// Why: the step is a chain of short, strictly dependent, bandwidth-bound
-// operations (Ghidorah, section 2.1: every decoding step re-reads all weights;
-// section 2.2.2: per layer QKV linear, attention, output linear, two MLP
-// linears).  At HBM speed one 7B layer lasts about 60 us, so launch gaps and
-// drain/refill at every dependency would cost as much as the streaming itself.
-// Here one workgroup per compute unit stays resident for the whole step; the
-// operations are phases separated by grid-wide barriers, and before waiting at a
-// barrier every wavefront already has the first weight blocks of the next phase
-// in flight (weights do not depend on activations).
+// The step is a chain of short, strictly dependent, bandwidth-bound operations
+// (Ghidorah, section 2.1: every decoding step re-reads all weights; section
+// 2.2.2: per layer QKV linear, attention, output linear, two MLP linears).  Each
+// of them is one launch with one workgroup per compute unit, all resident, that
+// cuts the operation's byte stream into equal contiguous shares whatever its
+// shape; the layer's element-wise work rides on those launches.
 //
 // Skinny linear layers.  W is packed in row groups of 256 output features
 // (16 tiles of 16 rows), inside a group k-step major: one k-step of a group is
@@ -65,9 +63,7 @@ struct GemmOp {
 
 struct Ctx {
     int j, G;            // logical workgroup index, number of workgroups
-    uint32_t nbar;       // barriers passed so far
-    char* lds;           // dynamic LDS: phase buffers, then one status word at lds_bytes - 16
-    uint32_t* s_status;  // LDS word used to hand a decision of thread 0 to the workgroup
+    char* lds;           // dynamic LDS
 };
 
 __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
@@ -127,7 +123,7 @@ __device__ __forceinline__ Share make_share(int items, int per_item, int j, int 
 
 // Waits until *p >= target.  Gives up (and raises the status word to `code`) after
 // kWaitTicks of wall-clock time, or as soon as another workgroup has given up, so that a
-// grid that is not fully resident ends with an error instead of hanging.  One thread calls.
+// launch that is not fully resident ends with an error instead of hanging.  One thread calls.
 __device__ __forceinline__ uint32_t poll(uint32_t* p)
 {
     // a read-modify-write that changes nothing: it is served where the counting atomics
@@ -148,29 +144,6 @@ __device__ __forceinline__ void bounded_wait(uint32_t* sync, uint32_t* p, uint32
         __builtin_amdgcn_s_sleep(8);
     }
 }
-
-// Grid-wide barrier.  All of this workgroup's stores have reached L2 once its threads
-// pass the first __syncthreads(); thread 0 then publishes them device-wide (release
-// fence: the cache write-back acts on the whole L2, so one thread does it for all),
-// counts the arrival, waits (bounded) for all G workgroups, and makes the other
-// workgroups' stores visible (acquire fence: invalidates this compute unit's view) before
-// the second __syncthreads() lets the rest of the workgroup go on.  Returns false (to
-// every thread alike) once any wait in the grid has given up, so the grid winds down.
-__device__ __forceinline__ bool grid_barrier(const FusedArgs& a, Ctx& cx)
-{
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __threadfence();
-        atomicAdd(a.sync + kSyncBarrier, 1u);
-        bounded_wait(a.sync, a.sync + kSyncBarrier, (uint32_t)cx.G * (cx.nbar + 1), 100u + cx.nbar);
-        __threadfence();
-        *cx.s_status = ld_relaxed(a.sync + kSyncStatus);
-    }
-    cx.nbar += 1;
-    __syncthreads();
-    return *cx.s_status == 0;
-}
-
 
 // ---------------------------------------------------------------------------
 // epilogue of one 16x16 output fragment: lane (c, g4) holds y[m][n0 .. n0+3]
@@ -257,7 +230,7 @@ __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, f
 // one skinny linear layer
 // ---------------------------------------------------------------------------
 template <int MT>
-__device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op, Ctx& cx, bool barrier_first)
+__device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op, Ctx& cx)
 {
     constexpr int CHUNK = kCH * MT * kFrag;        // LDS bytes of one staged x chunk
     constexpr int PIECES = kCH * MT * 64;          // 16-byte pieces per chunk
@@ -321,9 +294,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             if (tid + i * kFT < PIECES) *(half8*)(xs + buf * CHUNK + p_dst[i]) = xok[i] ? xr[i] : zero8;
     };
 
-    // Loads return in issue order.  In a launch of its own the first x chunk is requested
-    // ahead of the weight ring so that staging does not wait behind the ring; after a grid
-    // barrier x does not exist yet, and the ring (which does not depend on it) goes first.
+    // Loads return in issue order: the first x chunk is requested ahead of the weight ring
+    // so that staging does not wait behind the ring.
     auto w_first = [&]() {
         if (c0 >= c1) return;
 #pragma unroll
@@ -333,11 +305,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             for (int s = 0; s < kCH; ++s) w_fetch(std::integral_constant<int, 1>{}, s, min(c0 + 1, c1 - 1));
         }
     };
-    if (barrier_first) w_first();
-    else if (c0 < c1) x_fetch(c0);
-    if (barrier_first && !grid_barrier(a, cx)) return false;
-
-    if (!barrier_first) w_first();     // the ring queues up behind the first x chunk
+    if (c0 < c1) x_fetch(c0);
+    w_first();
 
     // ---- RMSNorm factor per row from the per-tile sums of squares ss[tile][Mpad]:
     //      thread (rq, part) adds 4 rows of every P-th tile, lanes of a wavefront that share
@@ -418,7 +387,6 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     };
 
     if (c0 < c1) {
-        if (barrier_first) x_fetch(c0);
         x_store(0);
         x_fetch(c0 + 1);
         __syncthreads();
@@ -504,7 +472,6 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             }
         }
     }
-    return true;
 }
 
 // ---------------------------------------------------------------------------
@@ -529,8 +496,8 @@ struct AttnLds {
 };
 
 template <int MT, int D>
-__device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const half_t* q, const half_t* kc,
-                           const half_t* vc, half_t* out, uint32_t epoch, bool barrier_first)
+__device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const half_t* q, const half_t* kc,
+                           const half_t* vc, half_t* out, uint32_t epoch)
 {
     constexpr int MTW = (MT + 3) / 4;   // 16-row tiles per wavefront
     constexpr int DS = D / 32, DT = D / 16, CPR = D / 8;
@@ -550,8 +517,6 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
     float* const ml_part = a.ml_part;
     const int ntile = (T + 63) >> 6;
 
-    if (barrier_first && !grid_barrier(a, cx)) return false;
-
     // Work shares.  Heads are dealt to the 8 XCDs in contiguous blocks.  Inside an XCD a
     // workgroup works on one head at a time: with fewer heads than workgroups, every head
     // gets its own run of workgroups, each taking a contiguous range of the head's key
@@ -561,7 +526,7 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
     const int nx = (cx.G % 8 == 0) ? 8 : 1;
     const int Gx = cx.G / nx, x = cx.j / Gx, w = cx.j - x * Gx;
     const int hx0 = (int)((long)nh * x / nx), Hx = (int)((long)nh * (x + 1) / nx) - hx0;
-    if (Hx == 0) return true;
+    if (Hx == 0) return;
     int h_lo, h_hi;          // this workgroup's heads (local to the XCD)
     if (Hx >= Gx) {
         h_lo = Hx * w / Gx;
@@ -902,137 +867,59 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
         // the other parts have read it
         if (hl + 1 < h_hi) __syncthreads();
     }
-    return true;
 }
 
 // ---------------------------------------------------------------------------
-// the kernel
+// the kernels
 // ---------------------------------------------------------------------------
-template <int MT, int D, int MODE>
-__global__ __launch_bounds__(kFT) void k_fused(const FusedArgs a)
+// Workgroups are dealt round-robin to the 8 XCDs; neighbours in the work sequence (which
+// share row groups, or heads, and exchange partial results) get the same XCD.  The
+// exchange relies on workgroup i running on XCD i % 8, which is checked here.
+__device__ __forceinline__ Ctx make_ctx(const FusedArgs& a, char* lds)
 {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
     Ctx cx;
-    // Workgroups are dealt round-robin to the 8 XCDs; give neighbours in the work
-    // sequence (which share row groups and exchange partial sums) the same XCD.
     const int G = gridDim.x, i = blockIdx.x;
     cx.G = G;
     cx.j = (G % 8 == 0) ? (i % 8) * (G / 8) + i / 8 : i;
-    cx.nbar = 0;
-    cx.s_status = (uint32_t*)lds;      // first 16 bytes of LDS: barrier status hand-over
-    cx.lds = lds + 16;
-    // The exchange of partial results relies on workgroup i running on XCD i % 8.
+    cx.lds = lds;
     if (G % 8 == 0 && threadIdx.x == 0) {
         unsigned xcc = __builtin_amdgcn_s_getreg(20 | (31 << 11)) & 15u;   // HW_REG_XCC_ID
         if (xcc != (unsigned)(i % 8)) atomicCAS(a.sync + kSyncStatus, 0u, 3u);
     }
+    return cx;
+}
 
-    // The step as a flat list of phases, decoded here so that each phase routine has a
-    // single (inlined) call site and the argument block stays in scalar registers.
-    //   stack / layer: per layer  0 QKV linear  1 attention  2 output linear
-    //                             3 gate|up linear  4 down linear;  then the LM head
-    const int H = a.H, F = a.F;
-    int nph = 1;
-    if (MODE == MODE_LAYER) nph = 5 * a.L;
-    if (MODE == MODE_STACK) nph = 5 * a.L + 1;
-    for (int ph = 0; ph < nph; ++ph) {
-        const int l = ph / 5, kind = ph % 5;
-        const bool is_lm = (MODE == MODE_STACK) && ph == 5 * a.L;
-        const bool first = ph == 0;
-        if (MODE == MODE_ATTN || (MODE != MODE_LINEAR && !is_lm && kind == 1)) {
-            const half_t* q = MODE == MODE_ATTN ? a.att_q : a.q16;
-            const half_t* kc = MODE == MODE_ATTN ? a.att_k : a.layer[l].kc;
-            const half_t* vc = MODE == MODE_ATTN ? a.att_v : a.layer[l].vc;
-            half_t* out = MODE == MODE_ATTN ? a.att_out : a.o16;
-            if (!attn_phase<MT, D>(a, cx, q, kc, vc, out, MODE == MODE_ATTN ? a.att_epoch : (uint32_t)l, !first)) return;
-            continue;
-        }
-        GemmOp op;
-        op.in16 = nullptr;
-        op.ld_in = 0;
-        op.rscale = false;
-        op.gnext = nullptr;
-        op.out = nullptr;
-        op.ldo = 0;
-        op.kc = nullptr;
-        op.vc = nullptr;
-        op.epoch = (uint32_t)l;
-        if (MODE == MODE_LINEAR) {
-            op.W = a.lin_W;
-            op.N = a.lin_N;
-            op.K = a.lin_K;
-            op.epi = a.lin_epi;
-            op.in16 = a.lin_x;
-            op.ld_in = a.lin_ldx;
-            op.rscale = a.lin_rscale != 0;
-            op.gnext = a.lin_gnext;
-            op.kc = a.lin_kc;
-            op.vc = a.lin_vc;
-            op.out = a.lin_y;
-            op.ldo = a.lin_ldy;
-            op.cnt = a.sync + a.lin_cnt;
-            op.epoch = a.lin_epoch;
-        } else if (is_lm) {
-            op.W = a.Wlm;
-            op.N = a.V;
-            op.K = H;
-            op.epi = EPI_STORE_F32;
-            op.in16 = a.xg16;
-            op.ld_in = H;
-            op.rscale = true;
-            op.out = a.logits;
-            op.ldo = a.V;
-            op.cnt = a.sync + kCntLm;
-            op.epoch = 0;
-        } else if (kind == 0) {
-            op.W = a.layer[l].Wqkv;
-            op.N = 3 * H;
-            op.K = H;
-            op.epi = EPI_QKV;
-            op.in16 = a.xg16;
-            op.ld_in = H;
-            op.rscale = true;
-            op.kc = a.layer[l].kc;
-            op.vc = a.layer[l].vc;
-            op.cnt = a.sync + kCntQkv;
-        } else if (kind == 2) {
-            op.W = a.layer[l].Wo;
-            op.N = H;
-            op.K = H;
-            op.epi = EPI_RESID;
-            op.in16 = a.o16;
-            op.ld_in = H;
-            op.out = a.x;
-            op.ldo = H;
-            op.gnext = a.layer[l].g_ffn;
-            op.cnt = a.sync + kCntWo;
-        } else if (kind == 3) {
-            op.W = a.layer[l].Wgu;
-            op.N = 2 * F;
-            op.K = H;
-            op.epi = EPI_SWIGLU;
-            op.in16 = a.xg16;
-            op.ld_in = H;
-            op.rscale = true;
-            op.out = a.a16;
-            op.ldo = F;
-            op.cnt = a.sync + kCntGu;
-        } else {
-            op.W = a.layer[l].Wdown;
-            op.N = H;
-            op.K = F;
-            op.epi = EPI_RESID;
-            op.in16 = a.a16;
-            op.ld_in = F;
-            op.out = a.x;
-            op.ldo = H;
-            op.gnext = (l + 1 < a.L) ? a.layer[l + 1].g_attn : (MODE == MODE_STACK ? a.g_final : nullptr);
-            op.cnt = a.sync + kCntDown;
-        }
-        op.ngroups = (op.N + kGroupRows - 1) / kGroupRows;
-        op.ncpg = (op.K + kChunkCols - 1) / kChunkCols;
-        if (!gemm_phase<MT>(a, op, cx, !first)) return;
-    }
+template <int MT>
+__global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    Ctx cx = make_ctx(a, lds);
+    GemmOp op;
+    op.W = a.lin_W;
+    op.N = a.lin_N;
+    op.K = a.lin_K;
+    op.epi = a.lin_epi;
+    op.in16 = a.lin_x;
+    op.ld_in = a.lin_ldx;
+    op.rscale = a.lin_rscale != 0;
+    op.gnext = a.lin_gnext;
+    op.out = a.lin_y;
+    op.ldo = a.lin_ldy;
+    op.kc = a.lin_kc;
+    op.vc = a.lin_vc;
+    op.cnt = a.sync + a.lin_cnt;
+    op.epoch = a.lin_epoch;
+    op.ngroups = (op.N + kGroupRows - 1) / kGroupRows;
+    op.ncpg = (op.K + kChunkCols - 1) / kChunkCols;
+    gemm_phase<MT>(a, op, cx);
+}
+
+template <int MT, int D>
+__global__ __launch_bounds__(kFT) void k_attention(const FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    Ctx cx = make_ctx(a, lds);
+    attn_phase<MT, D>(a, cx, a.att_q, a.att_k, a.att_v, a.att_out, a.att_epoch);
 }
 
 // ---------------------------------------------------------------------------
@@ -1052,67 +939,67 @@ int fused_grid_size()
     return g_num_cu;
 }
 
-template <int MT, int D>
-static size_t fused_lds_bytes()
+template <int MT>
+static size_t linear_lds_bytes()
 {
-    size_t gemm = 2 * (size_t)kCH * MT * kFrag + (128 + 1024) * sizeof(float);
-    size_t attn = sizeof(AttnLds<MT, D>);
-    return 16 + (gemm > attn ? gemm : attn);
+    return 2 * (size_t)kCH * MT * kFrag + (128 + 1024) * sizeof(float);
 }
 
-template <int MT, int D, int MODE>
-static ghd_status launch_fused_m(const FusedArgs& a, hipStream_t st)
+// All workgroups must be resident at once (they wait for each other): one per compute unit.
+template <class Kernel>
+static ghd_status launch_resident(Kernel kernel, bool& checked, size_t lds, const FusedArgs& a,
+                                  hipStream_t st)
 {
-    static bool checked = false;
-    size_t lds = fused_lds_bytes<MT, D>();
     int G = fused_grid_size();
     if (G <= 0) return hip_fail(hipErrorInvalidDevice);
     if (!checked) {
-        // all workgroups must be resident at once: one per compute unit
-        hipError_t e = hipFuncSetAttribute((const void*)k_fused<MT, D, MODE>,
+        hipError_t e = hipFuncSetAttribute((const void*)kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return hip_fail(e);
         int per_cu = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<MT, D, MODE>, kFT, lds);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kFT, lds);
         if (e != hipSuccess) return hip_fail(e);
         if (per_cu < 1) return hip_fail(hipErrorLaunchOutOfResources);
         checked = true;
     }
-    hipLaunchKernelGGL((k_fused<MT, D, MODE>), dim3(G), dim3(kFT), lds, st, a);
+    hipLaunchKernelGGL(kernel, dim3(G), dim3(kFT), lds, st, a);
     return check_launch();
 }
 
-// The whole-step modes (one launch for all phases, grid barriers in between) are
-// switched off: their first runs on hardware ended in a GPU fault whose cause is not
-// yet known, although the same code is clean under a CPU emulation with address
-// checking.  Until it is understood, a step is a sequence of single-phase launches.
-constexpr bool kWholeStepKernel = false;
+template <int MT>
+static ghd_status launch_linear_t(const FusedArgs& a, hipStream_t st)
+{
+    static bool checked = false;
+    return launch_resident(k_linear<MT>, checked, linear_lds_bytes<MT>(), a, st);
+}
 
 template <int MT, int D>
-static ghd_status launch_fused_t(const FusedArgs& a, hipStream_t st)
+static ghd_status launch_attention_t(const FusedArgs& a, hipStream_t st)
 {
-    if (a.mode == MODE_LINEAR) return launch_fused_m<MT, 128, MODE_LINEAR>(a, st);
-    if (a.mode == MODE_ATTN) return launch_fused_m<MT, D, MODE_ATTN>(a, st);
-    if constexpr (kWholeStepKernel) {
-        if (a.mode == MODE_STACK) return launch_fused_m<MT, D, MODE_STACK>(a, st);
-        return launch_fused_m<MT, D, MODE_LAYER>(a, st);
-    }
-    return hip_fail(hipErrorNotSupported);
+    static bool checked = false;
+    return launch_resident(k_attention<MT, D>, checked, sizeof(AttnLds<MT, D>), a, st);
 }
 
 template <int D>
-static ghd_status launch_fused_d(const FusedArgs& a, hipStream_t st)
+static ghd_status launch_attention_d(const FusedArgs& a, int mt, hipStream_t st)
 {
-    int mt = (a.M + 15) / 16;
-    if (mt <= 1) return launch_fused_t<1, D>(a, st);
-    if (mt <= 2) return launch_fused_t<2, D>(a, st);
-    if (mt <= 4) return launch_fused_t<4, D>(a, st);
-    return launch_fused_t<8, D>(a, st);
+    if (mt <= 1) return launch_attention_t<1, D>(a, st);
+    if (mt <= 2) return launch_attention_t<2, D>(a, st);
+    if (mt <= 4) return launch_attention_t<4, D>(a, st);
+    return launch_attention_t<8, D>(a, st);
 }
 
+// a.mode selects the kernel; the row-tile count of M selects the instantiation
 ghd_status launch_fused(const FusedArgs& a, hipStream_t st)
 {
-    return a.d == 64 ? launch_fused_d<64>(a, st) : launch_fused_d<128>(a, st);
+    const int mt = (a.M + 15) / 16;
+    if (a.mode == MODE_LINEAR) {
+        if (mt <= 1) return launch_linear_t<1>(a, st);
+        if (mt <= 2) return launch_linear_t<2>(a, st);
+        if (mt <= 4) return launch_linear_t<4>(a, st);
+        return launch_linear_t<8>(a, st);
+    }
+    return a.d == 64 ? launch_attention_d<64>(a, mt, st) : launch_attention_d<128>(a, mt, st);
 }
 
 // ---- setup kernel ------------------------------------------------------------
