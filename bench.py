@@ -123,6 +123,42 @@ def linear_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w
                           "achieved": round(kv_bytes / (att_n // steps) / (att_ms / att_n * 1e-3) / 1e9, 1)}}
 
 
+def sweep(torch, B, model, wl, stream, sets=4, iters=40):
+    """Tree-size sweep: one 7B-shaped layer, 2048 cached tokens, M in 1..128, chain and
+    bushy trees.  `sets` distinct weight + cache sets (1.8 GB) are used round-robin so that
+    every timed call streams from HBM, not from the memory-side cache."""
+    dev = "cuda"
+    rows = []
+    shape = wl.sweep_workload(1, "chain").shape
+    cap = wl.sweep_workload(128, "chain").capacity
+    layers = [model.upload_layer(wl.layer_weights(shape, 3, l, device=dev), shape.d, dev) for l in range(sets)]
+    caches = [model.upload_cache(*wl.kv_cache(shape, cap, 2048, 3, l, device=dev), device=dev) for l in range(sets)]
+    cfg = B.make_cfg(shape, cap)
+    for M in (1, 4, 8, 16, 32, 64, 128):
+        for kind in (("chain",) if M == 1 else ("chain", "bushy")):
+            w = wl.sweep_workload(M, kind)
+            parent = torch.from_numpy(w.parent).to(dev)
+            x = wl.activations(M, shape.H, 3).float().to(dev)
+            ws = B.workspace(B.ghd_workspace_bytes(cfg, M, 2048))
+            with torch.cuda.stream(stream):
+                for i in range(sets):
+                    B.ghd_verify_layer(cfg, layers[i], *caches[i], x, parent, 2048, ws=ws)
+                torch.cuda.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for i in range(iters):
+                    B.ghd_verify_layer(cfg, layers[i % sets], *caches[i % sets], x, parent, 2048, ws=ws)
+                e1.record(stream)
+                torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / iters * 1e3
+            nbytes = 2 * (4 * shape.H * shape.H + 3 * shape.H * shape.F) + 4 * shape.H * (2048 + M)
+            rows.append({"M": M, "tree": kind, "layer_us": round(us, 1),
+                         "gbps": round(nbytes / us / 1e3, 1)})
+            log("  sweep M=%3d %-5s %7.1f us  %6.1f GB/s" % (M, kind, us, nbytes / us / 1e3))
+    return rows
+
+
 def cpu_baseline(wl, w, sample_layers):
     """The CPU oracle, as it stands, timed on the host cores on a bounded sample of
     the same workload: `sample_layers` decoder layers + the LM head; the step
@@ -163,6 +199,8 @@ def main():
     ap.add_argument("--workload", default="stack7b")
     ap.add_argument("--cpu-sample-layers", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time one 7B-shaped layer at tree sizes 1..128 (adds a \"sweep\" list)")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also launch one plain 1 GiB copy kernel (for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -236,6 +274,10 @@ def main():
         "tree_over_decode": round(ms / dec_ms, 3),
         "roofline": roof,
     }
+    if args.sweep:
+        del stack
+        torch.cuda.empty_cache()
+        out["sweep"] = sweep(torch, B, model, wl, stream)
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on %d layers ..." % args.cpu_sample_layers)
         out["cpu_baseline"] = cpu_baseline(wl, w, args.cpu_sample_layers)
