@@ -3,6 +3,7 @@ under profiles/.
 
   python -m paper_2505_23219_amd.profile_summary stats   KERNEL_STATS.csv OUT.md --command "..."
   python -m paper_2505_23219_amd.profile_summary traffic FETCH.csv WRITE.csv OUT.md --command "..."
+  python -m paper_2505_23219_amd.profile_summary counter COUNTERS.csv NAME OUT.md --command "..."
 
 `stats` lists this library's kernels from a `--kernel-trace --stats` run.  `traffic`
 takes the counter_collection CSVs of two `--pmc` runs (FETCH_SIZE, then WRITE_SIZE) of
@@ -95,6 +96,23 @@ def traffic(fetch_csv: str, write_csv: str, out: str, command: str) -> None:
         f.write("source_sha256: %s\n" % source_digest())
 
 
+def counter(path: str, name: str, out: str, command: str) -> None:
+    """Average of one (derived) counter per kernel of this library."""
+    acc = {}
+    for r in csv.DictReader(open(path)):
+        if r["Counter_Name"] != name or "ghd" not in r["Kernel_Name"]:
+            continue
+        acc.setdefault(_short(r["Kernel_Name"]), []).append(float(r["Counter_Value"]))
+    if not acc:
+        sys.exit("%s: no %s rows for this library's kernels" % (path, name))
+    with open(out, "w") as f:
+        f.write("# %s per kernel, workload stack7b\n\n" % name)
+        f.write("Command (on the GPU box, from the repository root):\n\n    %s\n\n" % command)
+        f.write("| kernel | dispatches | avg %s | min | max |\n|---|---|---|---|---|\n" % name)
+        for k, v in sorted(acc.items(), key=lambda kv: -len(kv[1])):
+            f.write("| `%s` | %d | %.2f | %.2f | %.2f |\n" % (k, len(v), sum(v) / len(v), min(v), max(v)))
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="what", required=True)
@@ -107,8 +125,15 @@ def main() -> None:
     b.add_argument("write_csv")
     b.add_argument("out")
     b.add_argument("--command", required=True)
+    c = sub.add_parser("counter")
+    c.add_argument("csv")
+    c.add_argument("name")
+    c.add_argument("out")
+    c.add_argument("--command", required=True)
     args = ap.parse_args()
-    if args.what == "stats":
+    if args.what == "counter":
+        counter(args.csv, args.name, args.out, args.command)
+    elif args.what == "stats":
         stats(args.csv, args.out, args.command)
     else:
         traffic(args.fetch_csv, args.write_csv, args.out, args.command)
