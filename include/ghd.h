@@ -209,6 +209,20 @@ ghd_status ghd_accept_greedy(const float *logits, const int32_t *tokens_dev,
                              int32_t *amax_dev, void *ws, size_t ws_bytes, void *stream);
 size_t ghd_accept_workspace_bytes(int M);
 
+/* ---- commit of the accepted path (section 2.3: of the drafted tree only the
+ *      verified tokens join the context) ---------------------------------- */
+
+/* In every layer and head the K and V rows of the accepted nodes move from cache
+ * rows kv_len + path[j] (where the verification pass left them) to rows
+ * kv_len + j, j = 0 .. len-1; the caller then counts kv_len + len committed rows.
+ * res_dev is the device result of ghd_accept_greedy for the same tree (len =
+ * res_dev[0], path = res_dev[2..]), read on the device: no host round trip
+ * between acceptance and commit.  Entries are clamped to the tree, so a corrupt
+ * result cannot reach other rows.  kv_host: host array of cfg->L caches (device
+ * pointers).  One launch. */
+ghd_status ghd_commit_path(const ghd_model_cfg *cfg, const ghd_kv *kv_host, const int32_t *res_dev,
+                           int M, int kv_len, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

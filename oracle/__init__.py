@@ -242,3 +242,14 @@ class Oracle:
         self.lib.orc_accept_greedy(_p(lg), _p(t), _p(p), C.c_int(M), C.c_int(V), _p(res), _p(amax))
         n = int(res[0])
         return n, int(res[1]), res[2:2 + n].copy(), amax
+
+    # ---- commit of the accepted path
+    def commit_path(self, kc16, vc16, kv_len: int, path) -> None:
+        """Moves the K/V rows of the accepted nodes to rows kv_len.. in path order, in place
+        (caches [nh, cap, d] as uint16 views)."""
+        kc, vc = _u16(kc16), _u16(vc16)
+        assert kc.flags.writeable and vc.flags.writeable
+        p = _i32(path)
+        nh, cap, d = kc.shape
+        self.lib.orc_commit_path(_p(kc), _p(vc), C.c_int(nh), C.c_int(cap), C.c_int(d),
+                                 C.c_int(kv_len), _p(p), C.c_int(len(p)))

@@ -12,8 +12,8 @@
  *   - Eq. (1): X = Q K^T, A = softmax(X), O = A V;
  *   - section 2.3: under a verification tree a drafted token is related only to
  *     the tokens on its own root path, all drafted tokens see the whole KV
- *     cache, and softmax and A V share that sparsity pattern; after the pass the
- *     step falls back to the longest validated prefix.
+ *     cache, and softmax and A V share that sparsity pattern; after the pass only
+ *     the longest verified root path is kept and joins the context.
  * The model details the paper leaves to its model choice (section 4.1,
  * Vicuna-7B, i.e. the LLaMA architecture) are written out here: RMSNorm,
  * rotary embedding in the half-split pairing, SwiGLU MLP, no biases, softmax
@@ -33,7 +33,8 @@
  * path decomposition; width-1 tree == sequential decode steps; library
  * cross-checks (fp64 matmul, scaled_dot_product_attention with a boolean
  * mask); closed forms for the element-wise pieces; acceptance vs. brute-force
- * path enumeration.  End-to-end logits have no value printed in the paper to
+ * path enumeration; commit of the accepted path == feeding the accepted tokens
+ * one after the other.  End-to-end logits have no value printed in the paper to
  * compare with: for those, parity is pinned only through these pieces.
  */
 #include <math.h>
@@ -414,4 +415,29 @@ void orc_accept_greedy(const real *logits, const int32_t *tokens, const int32_t 
     res[1] = amax[last];
     for (int node = last, p = len - 1; node >= 0; node = parent[node], --p)
         res[2 + p] = node;
+}
+
+/* ---------------------------------------------------------------- commit -- */
+
+/* Commit of the accepted path (section 2.3: only the verified tokens join the
+ * context).  The K and V rows of the accepted nodes path[0..len), which the
+ * verification pass left at cache rows kv_len + path[j], become the rows
+ * kv_len + j, j = 0..len-1; the caller's committed length then grows by len.
+ * Cache [nh][cap][d] as fp16 bit patterns; rows from kv_len + len on are left as
+ * they are.  Written with a scratch copy so that no source row can have been
+ * overwritten before it is read. */
+void orc_commit_path(uint16_t *kc, uint16_t *vc, int nh, int cap, int d, int kv_len,
+                     const int32_t *path, int len)
+{
+    uint16_t *tmp = (uint16_t *)malloc((size_t)len * d * sizeof(uint16_t));
+    uint16_t *caches[2] = {kc, vc};
+    for (int which = 0; which < 2; ++which)
+        for (int h = 0; h < nh; ++h) {
+            uint16_t *head = caches[which] + (size_t)h * cap * d;
+            for (int j = 0; j < len; ++j)
+                memcpy(tmp + (size_t)j * d, head + (size_t)(kv_len + path[j]) * d,
+                       (size_t)d * sizeof(uint16_t));
+            memcpy(head + (size_t)kv_len * d, tmp, (size_t)len * d * sizeof(uint16_t));
+        }
+    free(tmp);
 }

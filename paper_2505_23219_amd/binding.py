@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
             "ghd_workspace_bytes": (sz, [vp, i32, i32]),
             "ghd_accept_greedy": (C.c_int32, [vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]),
             "ghd_accept_workspace_bytes": (sz, [i32]),
+            "ghd_commit_path": (C.c_int32, [vp, vp, vp, i32, i32, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -92,7 +93,7 @@ EXPORTS = ["ghd_status_str", "ghd_last_hip_error", "ghd_tree_validate", "ghd_tre
            "ghd_packed_weight_bytes", "ghd_pack_weight", "ghd_linear_skinny",
            "ghd_linear_workspace_bytes", "ghd_tree_attention", "ghd_attention_workspace_bytes",
            "ghd_verify_layer", "ghd_verify_stack", "ghd_workspace_bytes", "ghd_accept_greedy",
-           "ghd_accept_workspace_bytes"]
+           "ghd_accept_workspace_bytes", "ghd_commit_path"]
 
 
 def status_str(status: int) -> str:
@@ -267,3 +268,10 @@ def ghd_accept_greedy(logits: torch.Tensor, tokens: torch.Tensor, parent: torch.
                                    _ptr(_dev(parent, torch.int32)), M, V, _ptr(res), _ptr(amax),
                                    _ptr(ws), ws.numel(), _stream()), "ghd_accept_greedy")
     return res, amax
+
+
+def ghd_commit_path(stack: Stack, res: torch.Tensor, M: int, kv_len: int) -> None:
+    """Moves the K/V rows of the accepted path (res from ghd_accept_greedy, on the device)
+    to rows kv_len.. of every layer's cache, in place."""
+    _check(lib().ghd_commit_path(C.byref(stack.cfg), stack.kv, _ptr(_dev(res, torch.int32)), M, kv_len,
+                                 _stream()), "ghd_commit_path")

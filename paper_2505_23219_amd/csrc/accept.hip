@@ -11,6 +11,8 @@
 
 namespace ghd {
 
+constexpr int kCommitMaxLayers = 48;
+
 __device__ inline void argmax_merge(float& v, int& i, float ov, int oi)
 {
     if (ov > v || (ov == v && oi < i)) {
@@ -103,6 +105,69 @@ __global__ __launch_bounds__(128) void k_accept(const float* __restrict__ seg_v,
         res[1] = s_amax[node];
         for (int pos = depth, j = node; pos >= 0 && j >= 0; --pos, j = s_par[j]) res[2 + pos] = j;
     }
+}
+
+// ---- commit of the accepted path ---------------------------------------------
+// One workgroup per (layer, head).  The K rows (and the V columns: V is channel-major) of
+// the accepted nodes are gathered into LDS, and only after a barrier written to rows
+// kv_len + j, so no source can have been overwritten before it is read.  The path comes
+// from the device result of the acceptance kernel; its entries are clamped, so that
+// whatever that buffer holds no access leaves the tree rows.
+struct CommitArgs {
+    half_t* k[kCommitMaxLayers];
+    half_t* v[kCommitMaxLayers];
+    const int32_t* res;
+    int nh, d, cap, kv_len, M;
+};
+
+__global__ __launch_bounds__(256) void k_commit_path(const CommitArgs a)
+{
+    __shared__ __attribute__((aligned(16))) half_t s_rows[GHD_MAX_M * 128];
+    __shared__ int32_t s_path[GHD_MAX_M];
+    const int tid = threadIdx.x, layer = blockIdx.x / a.nh, head = blockIdx.x % a.nh;
+    const int d = a.d, len = min(max(a.res[0], 0), a.M);
+    for (int j = tid; j < len; j += 256) s_path[j] = min(max(a.res[2 + j], 0), a.M - 1);
+    __syncthreads();
+    half_t* kh = a.k[layer] + (size_t)head * a.cap * d;
+    const int cpr = d / 8;
+    for (int idx = tid; idx < len * cpr; idx += 256) {
+        int j = idx / cpr, c = idx % cpr;
+        *(half8*)(s_rows + idx * 8) = *(const half8*)(kh + (size_t)(a.kv_len + s_path[j]) * d + c * 8);
+    }
+    __syncthreads();
+    for (int idx = tid; idx < len * cpr; idx += 256) {
+        int j = idx / cpr, c = idx % cpr;
+        *(half8*)(kh + (size_t)(a.kv_len + j) * d + c * 8) = *(const half8*)(s_rows + idx * 8);
+    }
+    __syncthreads();
+    half_t* vh = a.v[layer] + (size_t)head * d * a.cap + a.kv_len;
+    for (int idx = tid; idx < d * len; idx += 256) {
+        int ch = idx / len, j = idx % len;
+        s_rows[idx] = vh[(size_t)ch * a.cap + s_path[j]];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < d * len; idx += 256) {
+        int ch = idx / len, j = idx % len;
+        vh[(size_t)ch * a.cap + j] = s_rows[idx];
+    }
+}
+
+ghd_status launch_commit_path(void* const* k, void* const* v, int L, int nh, int d, int cap,
+                              int kv_len, int M, const int32_t* res, hipStream_t st)
+{
+    CommitArgs a;
+    for (int l = 0; l < L; ++l) {
+        a.k[l] = (half_t*)k[l];
+        a.v[l] = (half_t*)v[l];
+    }
+    a.res = res;
+    a.nh = nh;
+    a.d = d;
+    a.cap = cap;
+    a.kv_len = kv_len;
+    a.M = M;
+    hipLaunchKernelGGL(k_commit_path, dim3(L * nh), dim3(256), 0, st, a);
+    return check_launch();
 }
 
 size_t accept_workspace_bytes() { return (size_t)GHD_MAX_M * kArgSeg * 8; }

@@ -510,6 +510,24 @@ ghd_status ghd_accept_greedy(const float* logits, const int32_t* tokens_dev,
                          (hipStream_t)stream);
 }
 
+ghd_status ghd_commit_path(const ghd_model_cfg* cfg, const ghd_kv* kv_host, const int32_t* res_dev,
+                           int M, int kv_len, void* stream)
+{
+    if (!cfg || !kv_host || !res_dev) return GHD_ERR_NULL;
+    ghd_status s = check_cfg(cfg, M, kv_len);
+    if (s) return s;
+    void* k[kMaxLayers];
+    void* v[kMaxLayers];
+    for (int l = 0; l < cfg->L; ++l) {
+        if (!kv_host[l].k || !kv_host[l].v) return GHD_ERR_NULL;
+        if (!aligned16(kv_host[l].k) || !aligned16(kv_host[l].v)) return GHD_ERR_ALIGN;
+        k[l] = kv_host[l].k;
+        v[l] = kv_host[l].v;
+    }
+    return launch_commit_path(k, v, cfg->L, cfg->nh, cfg->d, cfg->kv_capacity, kv_len, M, res_dev,
+                              (hipStream_t)stream);
+}
+
 /* Benchmark support (not part of the documented ABI): time the launches of one kind
  * of the persistent kernel with HIP events on the launch stream.
  * ghd_debug_profile(1) starts a fresh measurement of the linear-layer launches,

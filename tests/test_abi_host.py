@@ -203,3 +203,16 @@ def test_workspace_sizes_grow_with_the_problem(lib):
     assert 0 < a < b < (1 << 30)
     assert lib.ghd_attention_workspace_bytes(64, 2048, 32, 128) > 0
     assert lib.ghd_accept_workspace_bytes(64) >= 64 * 4
+
+
+def test_commit_path_rejects_bad_arguments(lib):
+    cfg = _cfg(wl.TINY, 256)
+    kv = B.KV(FAKE, FAKE)
+    f = lib.ghd_commit_path
+    assert f(None, C.byref(kv), FAKE, 8, 100, None) == B.GHD_ERR_NULL
+    assert f(C.byref(cfg), None, FAKE, 8, 100, None) == B.GHD_ERR_NULL
+    assert f(C.byref(cfg), C.byref(kv), None, 8, 100, None) == B.GHD_ERR_NULL
+    assert f(C.byref(cfg), C.byref(kv), FAKE, 0, 100, None) == B.GHD_ERR_SHAPE
+    assert f(C.byref(cfg), C.byref(kv), FAKE, 8, 250, None) == B.GHD_ERR_CAPACITY
+    assert f(C.byref(cfg), C.byref(B.KV(FAKE + 2, FAKE)), FAKE, 8, 100, None) == B.GHD_ERR_ALIGN
+    assert f(C.byref(cfg), C.byref(B.KV(None, FAKE)), FAKE, 8, 100, None) == B.GHD_ERR_NULL

@@ -361,6 +361,47 @@ def test_accept_greedy_same_logits_bit_exact(B, orc32, M, V):
         assert res[0] == n and res[1] == nxt and np.array_equal(res[2:2 + n], path)
 
 
+# ---- commit of the accepted path: a pure copy, bit-exact -----------------------------
+
+@pytest.mark.parametrize("nh,d,L,M,kv_len,tree,seed", [(4, 64, 1, 8, 128, "rand3", 0), (2, 128, 3, 64, 70, "rand5", 1),
+                                                      (3, 128, 2, 128, 0, "chain", 2), (2, 64, 2, 1, 5, "chain", 3),
+                                                      (32, 128, 2, 64, 2048, "rand5", 4)])
+def test_commit_path_bit_exact(B, model, orc32, nh, d, L, M, kv_len, tree, seed):
+    say("commit", nh, d, L, M, kv_len, tree)
+    shape = wl.ModelShape("c", H=nh * d, nh=nh, d=d, F=8 * d, V=16, L=L)
+    cap = ((kv_len + M + 63) // 64) * 64
+    parent = make_tree(tree, M)
+    depth = orc32.tree_depth(parent)
+    rng = np.random.default_rng(seed)
+    for node in {0, M - 1, int(np.argmax(depth)), int(rng.integers(0, M))}:
+        path = []
+        j = node
+        while j >= 0:
+            path.append(j)
+            j = int(parent[j])
+        path = np.array(path[::-1], dtype=np.int32)
+        # every cache row distinct and recognisable
+        ks = [torch.from_numpy(rng.integers(0, 0x7bff, size=(nh, cap, d)).astype(np.int16)).view(torch.float16)
+              for _ in range(L)]
+        vs = [torch.from_numpy(rng.integers(0, 0x7bff, size=(nh, cap, d)).astype(np.int16)).view(torch.float16)
+              for _ in range(L)]
+        dev = [model.upload_cache(k, v) for k, v in zip(ks, vs)]
+        stack = B.Stack(B.make_cfg(shape, cap), [dict(g_attn=ks[0], Wqkv=ks[0], Wo=ks[0], g_ffn=ks[0],
+                                                      Wgu=ks[0], Wdown=ks[0])] * L, dev,
+                        dict(g_final=ks[0], Wlm=ks[0]))
+        res = np.zeros(2 + M, dtype=np.int32)
+        res[0] = len(path)
+        res[2:2 + len(path)] = path
+        B.ghd_commit_path(stack, torch.from_numpy(res).cuda(), M, kv_len)
+        torch.cuda.synchronize()
+        for l in range(L):
+            k_ref, v_ref = ks[l].numpy().copy(), vs[l].numpy().copy()
+            orc32.commit_path(k_ref, v_ref, kv_len, path)
+            assert np.array_equal(dev[l][0].cpu().numpy().view(np.uint16), k_ref.view(np.uint16)), (node, l)
+            assert np.array_equal(model.rows_of_v(dev[l][1]).cpu().numpy().view(np.uint16),
+                                  v_ref.view(np.uint16)), (node, l)
+
+
 # ---- full-size cases: the benchmark's configuration and the large shapes -------------
 
 def run_big_stack(B, model, orc32, w, L):
