@@ -114,7 +114,7 @@ static ghd_status check_cfg(const ghd_model_cfg* c, int M, int kv_len)
     if (M < 1 || M > GHD_MAX_M || kv_len < 0) return GHD_ERR_SHAPE;
     if ((c->d != 64 && c->d != 128) || c->nh < 1 || c->nh > 256 || c->H != c->nh * c->d)
         return GHD_ERR_SHAPE;
-    if (c->F < 8 || (c->F % 8) != 0 || c->L < 1 || c->L > kMaxLayers || c->V < 1) return GHD_ERR_SHAPE;
+    if (c->F < 8 || (c->F % 8) != 0 || c->F > (1 << 20) || c->L < 1 || c->L > kMaxLayers || c->V < 1) return GHD_ERR_SHAPE;
     if (3 * (int64_t)c->H > 512 * kGroupRows || 2 * (int64_t)c->F > 512 * kGroupRows ||
         (int64_t)c->V > 1024 * kGroupRows)
         return GHD_ERR_SHAPE;
@@ -323,6 +323,8 @@ ghd_status ghd_linear_skinny(void* y, const void* x, const void* Wp, int M, int 
     if (M < 1 || M > GHD_MAX_M || N < 1 || K < 8 || (K % 8) != 0) return GHD_ERR_SHAPE;
     if (ldx < K || ldy < N || flags > GHD_OUT_F16 || (int64_t)N > 1024 * kGroupRows)
         return GHD_ERR_SHAPE;
+    // the kernel counts chunks (256 rows x 128 columns) in 32 bits
+    if (((int64_t)N / kGroupRows + 1) * ((int64_t)K / kChunkCols + 1) >= (1ll << 31)) return GHD_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(Wp) || !aligned16(y) || (ldx % 8) != 0) return GHD_ERR_ALIGN;
     if (!ws) return GHD_ERR_WORKSPACE;
     if (!aligned16(ws)) return GHD_ERR_ALIGN;

@@ -84,10 +84,10 @@ __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
 // 4 us here) is needed anywhere inside a phase.
 struct Share {
     int U;        // units of this XCD (fits 32 bits together with the factor Ge)
-    long base;    // global index of its first unit
+    int base;     // global index of its first unit (the unit count of an operation fits 31 bits)
     int Ge;       // workgroups of this XCD that get units
     int wg0;      // logical index of its first workgroup
-    long c0, c1;  // this workgroup's range of global unit indices (empty if c0 == c1)
+    int c0, c1;   // this workgroup's range of global unit indices (empty if c0 == c1)
     int per_item;
     // local (within-XCD) unit index where workgroup wg's range begins
     __device__ int lbegin(int wg) const { return (int)((unsigned)U * (unsigned)(wg - wg0) / (unsigned)Ge); }
@@ -95,7 +95,7 @@ struct Share {
     {
         return wg0 + (int)(((unsigned)(lunit + 1) * (unsigned)Ge - 1u) / (unsigned)U);
     }
-    __device__ int litem0(int item) const { return (int)((long)item * per_item - base); }
+    __device__ int litem0(int item) const { return item * per_item - base; }
     __device__ int first_of(int item) const { return owner_local(litem0(item)); }
     __device__ int last_of(int item) const { return owner_local(litem0(item) + per_item - 1); }
     // does workgroup wg's range begin inside `item` (and not in an earlier one)?
@@ -106,11 +106,11 @@ __device__ __forceinline__ Share make_share(int items, int per_item, int j, int 
 {
     const int nx = (G % 8 == 0) ? 8 : 1;
     const int Gx = G / nx, x = j / Gx;
-    const int i0 = (int)((long)items * x / nx), i1 = (int)((long)items * (x + 1) / nx);
+    const int i0 = items * x / nx, i1 = items * (x + 1) / nx;
     Share sh;
     sh.per_item = per_item;
     sh.U = (i1 - i0) * per_item;
-    sh.base = (long)i0 * per_item;
+    sh.base = i0 * per_item;
     sh.wg0 = x * Gx;
     sh.Ge = sh.U < Gx ? sh.U : Gx;
     sh.c0 = sh.c1 = 0;
@@ -243,7 +243,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     float* s_tmp = s_rinv + 128;                   // 1024 floats
 
     const Share sh = make_share(op.ngroups, op.ncpg, cx.j, cx.G);
-    const long c0 = sh.c0, c1 = sh.c1;
+    const int c0 = sh.c0, c1 = sh.c1;
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
     // ---- weight stream: linear in the chunk index
@@ -254,7 +254,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     // Loads inside the streaming loop are unconditional (addresses are clamped instead):
     // a load that may or may not be issued makes the number of younger loads unknown, and
     // every wait for an older one then has to drain the whole queue.
-    auto w_fetch = [&](auto slot, int s, long cu) {
+    auto w_fetch = [&](auto slot, int s, int cu) {
         constexpr int R = decltype(slot)::value;
         const half8* p = wbase + ((size_t)cu * kCH + s) * (kTG * 64);
         // streamed once: non-temporal, so the weights do not push x and the partial sums
@@ -279,7 +279,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     }
     half8 xr[PPT];
     bool xok[PPT];
-    auto x_fetch = [&](long cu) {
+    auto x_fetch = [&](int cu) {
         int kbase = (int)(min(cu, c1 - 1) % op.ncpg) * kChunkCols;
 #pragma unroll
         for (int i = 0; i < PPT; ++i) {
@@ -393,7 +393,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
         // One chunk: 4 k-steps of MFMAs on ring slot R, each followed (FW) by the request
         // for the same k-step kWR chunks ahead; then the next x chunk goes to LDS and the
         // one after it is requested.  No branches: the wait counts stay exact.
-        auto chunk_step = [&](auto slot, auto fw, long cu) {
+        auto chunk_step = [&](auto slot, auto fw, int cu) {
             constexpr int R = decltype(slot)::value;
             constexpr bool FW = decltype(fw)::value;
             const char* xb = xs + (int)((cu - c0) & 1) * CHUNK + g4 * 272 + c * 16;
@@ -415,26 +415,26 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
             __syncthreads();
         };
         // chunks [b0, b1) of one row group; the first one uses ring slot P
-        auto span_impl = [&](auto par, auto fw, long b0, long b1) {
+        auto span_impl = [&](auto par, auto fw, int b0, int b1) {
             constexpr int P = (kWR == 2) ? decltype(par)::value : 0;
             constexpr int Q = (kWR == 2) ? 1 - P : 0;
-            long cu = b0;
+            int cu = b0;
             for (; cu + 2 <= b1; cu += 2) {
                 chunk_step(std::integral_constant<int, P>{}, fw, cu);
                 chunk_step(std::integral_constant<int, Q>{}, fw, cu + 1);
             }
             if (cu < b1) chunk_step(std::integral_constant<int, P>{}, fw, cu);
         };
-        auto span = [&](auto fw, long b0, long b1) {
+        auto span = [&](auto fw, int b0, int b1) {
             if (b0 >= b1) return;
             if ((b0 - c0) & 1) span_impl(std::integral_constant<int, 1>{}, fw, b0, b1);
             else span_impl(std::integral_constant<int, 0>{}, fw, b0, b1);
         };
-        const long fend = c1 - kWR;     // chunks from here on have nothing left to prefetch
-        for (long cu = c0; cu < c1;) {
+        const int fend = c1 - kWR;     // chunks from here on have nothing left to prefetch
+        for (int cu = c0; cu < c1;) {
             int grp = (int)(cu / op.ncpg);
-            long se = min(c1, (long)(grp + 1) * op.ncpg);
-            long mid = min(se, max(fend, cu));
+            int se = min(c1, (grp + 1) * op.ncpg);
+            int mid = min(se, max(fend, cu));
             span(std::true_type{}, cu, mid);
             span(std::false_type{}, mid, se);
             flush(grp);
@@ -525,7 +525,7 @@ __device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const ha
     // of a head has no head change in it.
     const int nx = (cx.G % 8 == 0) ? 8 : 1;
     const int Gx = cx.G / nx, x = cx.j / Gx, w = cx.j - x * Gx;
-    const int hx0 = (int)((long)nh * x / nx), Hx = (int)((long)nh * (x + 1) / nx) - hx0;
+    const int hx0 = nh * x / nx, Hx = nh * (x + 1) / nx - hx0;
     if (Hx == 0) return;
     int h_lo, h_hi;          // this workgroup's heads (local to the XCD)
     if (Hx >= Gx) {
