@@ -188,6 +188,26 @@ def test_tree_attention(B, model, orc32, M, nh, d, kv_len, tree):
     assert ok, (ma, mr)
 
 
+@pytest.mark.parametrize("M,kv_len,cap", [(6, 64, 72), (1, 7, 8), (10, 118, 128), (9, 190, 200)])
+def test_tree_attention_tight_capacity(B, model, orc32, M, kv_len, cap):
+    """Capacity not a multiple of the 64-key tile: the last tile's V pieces past the
+    capacity are never read (every piece there is replaced by the last valid one and
+    zeroed), and rows between the tree and the capacity hold NaN."""
+    say("attention tight", M, kv_len, cap)
+    nh, d = 2, 128
+    parent = wl.tree_random(M, 3, 5)
+    q, kc, vc = attention_case(M, nh, d, kv_len, parent, 47, cap=cap)
+    ref = orc32.tree_attention(q.numpy().astype(np.float32), kc.numpy(), vc.numpy(), parent, kv_len)
+    kc[:, kv_len + M:] = float("nan")
+    vc[:, kv_len + M:] = float("nan")
+    ws = B.workspace(B.lib().ghd_attention_workspace_bytes(M, kv_len, nh, d))
+    got = B.ghd_tree_attention(q.cuda(), *model.upload_cache(kc, vc), torch.from_numpy(parent).cuda(),
+                               kv_len, ws=ws)
+    assert B.ghd_step_status(ws) == 0
+    ok, ma, mr = close(got.cpu().numpy(), ref, 5e-3, 5e-3)
+    assert ok, (ma, mr)
+
+
 def test_tree_attention_ignores_rows_past_the_tree(B, model):
     M, nh, d, kv_len = 9, 2, 128, 70
     parent = wl.tree_random(M, 3, 1)
