@@ -399,15 +399,20 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
             const char* xb = xs + (int)((cu - c0) & 1) * CHUNK + g4 * 272 + c * 16;
 #pragma unroll
             for (int s = 0; s < kCH; ++s) {
-                half8 xf[MT];
+                // at most four x fragments live at a time (register budget at M > 64)
+                constexpr int XB = MT > 4 ? 4 : MT;
 #pragma unroll
-                for (int b = 0; b < MT; ++b) xf[b] = *(const half8*)(xb + (s * MT + b) * kFrag);
+                for (int b0 = 0; b0 < MT; b0 += XB) {
+                    half8 xf[XB];
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
+                    for (int b = 0; b < XB; ++b) xf[b] = *(const half8*)(xb + (s * MT + b0 + b) * kFrag);
 #pragma unroll
-                    for (int b = 0; b < MT; ++b)
-                        acc[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wb[R][s][t], xf[b], acc[t][b],
-                                                                          0, 0, 0);
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int b = 0; b < XB; ++b)
+                            acc[t][b0 + b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                                wb[R][s][t], xf[b], acc[t][b0 + b], 0, 0, 0);
+                }
                 if constexpr (FW) w_fetch(slot, s, cu + kWR);
             }
             x_store((int)((cu + 1 - c0) & 1));
@@ -427,8 +432,13 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
         };
         auto span = [&](auto fw, int b0, int b1) {
             if (b0 >= b1) return;
-            if ((b0 - c0) & 1) span_impl(std::integral_constant<int, 1>{}, fw, b0, b1);
-            else span_impl(std::integral_constant<int, 0>{}, fw, b0, b1);
+            if constexpr (kWR == 2) {
+                if ((b0 - c0) & 1) {
+                    span_impl(std::integral_constant<int, 1>{}, fw, b0, b1);
+                    return;
+                }
+            }
+            span_impl(std::integral_constant<int, 0>{}, fw, b0, b1);
         };
         const int fend = c1 - kWR;     // chunks from here on have nothing left to prefetch
         for (int cu = c0; cu < c1;) {
