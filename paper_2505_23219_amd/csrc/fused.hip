@@ -27,15 +27,16 @@
 // (a per-row scalar, so it commutes with the contraction) is applied to the fp32
 // sums in the epilogue.  The 1/16 keeps x * g inside the fp16 range.
 //
-// Tree attention.  The (head, 64-key tile) pairs form the same kind of linear
-// sequence.  A workgroup streams its tiles through LDS (the V cache is kept
+// Tree attention.  A head's 64-key tiles are split over a run of workgroups of
+// one XCD.  A workgroup streams its tiles through LDS (the V cache is kept
 // channel-major, so both K rows and V^T rows go to LDS as they are); wavefronts
 // 0-3 take the first 32 keys of a tile, 4-7 the last 32, each for its own 16 (or
 // 32) query rows.  S^T = K q^T puts one query row in each lane column, so softmax
 // statistics are per-lane scalars, the fp16 probabilities are already in
 // B-operand layout for O^T += V^T P^T, and the ancestor mask (section 2.3) is a
-// 128-bit register per lane.  Sub-tiles no row can see are skipped.  Parts of a
-// head are merged with the online-softmax rescale of section 3.2.2.
+// 128-bit register per lane.  Sub-tiles no row can see are skipped.  The two key
+// halves are merged inside the workgroup, the workgroups of a head through one
+// partial state each, with the online-softmax rescale of section 3.2.2.
 #include "fused.h"
 
 #include <type_traits>
