@@ -248,20 +248,21 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
     // ---- weight stream: linear in the chunk index
-    // kWR chunks of weights are in flight per wavefront (registers); slot (cu - c0) % kWR
+    // One chunk of weights is in flight per wavefront, in registers: k-step s of the next
+    // chunk is requested right after k-step s of the current one has been consumed.  (Two
+    // chunks in flight were measured slower at every M: the extra registers and the longer
+    // fill cost more than the deeper queue gains.)
     const half8* wbase = op.W + (size_t)(wave * 2) * 64 + lane;
-    constexpr int kWR = (MT <= 2) ? 2 : 1;
-    half8 wb[kWR][kCH][2];
-    // Loads inside the streaming loop are unconditional (addresses are clamped instead):
-    // a load that may or may not be issued makes the number of younger loads unknown, and
-    // every wait for an older one then has to drain the whole queue.
-    auto w_fetch = [&](auto slot, int s, int cu) {
-        constexpr int R = decltype(slot)::value;
+    half8 wb[kCH][2];
+    // Loads inside the streaming loop are unconditional (the tail is peeled instead): a load
+    // that may or may not be issued makes the number of younger loads unknown, and every
+    // wait for an older one then has to drain the whole queue.
+    auto w_fetch = [&](int s, int cu) {
         const half8* p = wbase + ((size_t)cu * kCH + s) * (kTG * 64);
         // streamed once: non-temporal, so the weights do not push x and the partial sums
         // out of the L2
-        wb[R][s][0] = __builtin_nontemporal_load(p);
-        wb[R][s][1] = __builtin_nontemporal_load(p + 64);
+        wb[s][0] = __builtin_nontemporal_load(p);
+        wb[s][1] = __builtin_nontemporal_load(p + 64);
     };
     // ---- x staging: piece p -> fragment f = p/64 (k-step s = f/MT, row tile f%MT),
     //      row (p/4)%16, k group p%4
@@ -300,11 +301,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     auto w_first = [&]() {
         if (c0 >= c1) return;
 #pragma unroll
-        for (int s = 0; s < kCH; ++s) w_fetch(std::integral_constant<int, 0>{}, s, c0);
-        if constexpr (kWR == 2) {
-#pragma unroll
-            for (int s = 0; s < kCH; ++s) w_fetch(std::integral_constant<int, 1>{}, s, min(c0 + 1, c1 - 1));
-        }
+        for (int s = 0; s < kCH; ++s) w_fetch(s, c0);
     };
     if (c0 < c1) x_fetch(c0);
     w_first();
@@ -391,11 +388,10 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
         x_store(0);
         x_fetch(c0 + 1);
         __syncthreads();
-        // One chunk: 4 k-steps of MFMAs on ring slot R, each followed (FW) by the request
-        // for the same k-step kWR chunks ahead; then the next x chunk goes to LDS and the
-        // one after it is requested.  No branches: the wait counts stay exact.
-        auto chunk_step = [&](auto slot, auto fw, int cu) {
-            constexpr int R = decltype(slot)::value;
+        // One chunk: 4 k-steps of MFMAs, each followed (FW) by the request for the same
+        // k-step of the next chunk; then the next x chunk goes to LDS and the one after it
+        // is requested.  No branches: the wait counts stay exact.
+        auto chunk_step = [&](auto fw, int cu) {
             constexpr bool FW = decltype(fw)::value;
             const char* xb = xs + (int)((cu - c0) & 1) * CHUNK + g4 * 272 + c * 16;
 #pragma unroll
@@ -412,42 +408,21 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
 #pragma unroll
                         for (int b = 0; b < XB; ++b)
                             acc[t][b0 + b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                                wb[R][s][t], xf[b], acc[t][b0 + b], 0, 0, 0);
+                                wb[s][t], xf[b], acc[t][b0 + b], 0, 0, 0);
                 }
-                if constexpr (FW) w_fetch(slot, s, cu + kWR);
+                if constexpr (FW) w_fetch(s, cu + 1);
             }
             x_store((int)((cu + 1 - c0) & 1));
             x_fetch(cu + 2);
             __syncthreads();
         };
-        // chunks [b0, b1) of one row group; the first one uses ring slot P
-        auto span_impl = [&](auto par, auto fw, int b0, int b1) {
-            constexpr int P = (kWR == 2) ? decltype(par)::value : 0;
-            constexpr int Q = (kWR == 2) ? 1 - P : 0;
-            int cu = b0;
-            for (; cu + 2 <= b1; cu += 2) {
-                chunk_step(std::integral_constant<int, P>{}, fw, cu);
-                chunk_step(std::integral_constant<int, Q>{}, fw, cu + 1);
-            }
-            if (cu < b1) chunk_step(std::integral_constant<int, P>{}, fw, cu);
-        };
-        auto span = [&](auto fw, int b0, int b1) {
-            if (b0 >= b1) return;
-            if constexpr (kWR == 2) {
-                if ((b0 - c0) & 1) {
-                    span_impl(std::integral_constant<int, 1>{}, fw, b0, b1);
-                    return;
-                }
-            }
-            span_impl(std::integral_constant<int, 0>{}, fw, b0, b1);
-        };
-        const int fend = c1 - kWR;     // chunks from here on have nothing left to prefetch
+        const int fend = c1 - 1;        // the last chunk has nothing left to prefetch
         for (int cu = c0; cu < c1;) {
             int grp = (int)(cu / op.ncpg);
             int se = min(c1, (grp + 1) * op.ncpg);
             int mid = min(se, max(fend, cu));
-            span(std::true_type{}, cu, mid);
-            span(std::false_type{}, mid, se);
+            for (int b = cu; b < mid; ++b) chunk_step(std::true_type{}, b);
+            for (int b = mid; b < se; ++b) chunk_step(std::false_type{}, b);
             flush(grp);
             cu = se;
         }
