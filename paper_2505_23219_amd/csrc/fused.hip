@@ -360,7 +360,8 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     };
 
     // Ends the accumulation of row group `grp`: direct epilogue when this workgroup
-    // owns the whole K range, otherwise store the partial and signal.
+    // owns the whole K range, otherwise store the partial (the group's counter is bumped
+    // once the whole share has been streamed).
     auto flush = [&](int grp) {
         int first = group_first(grp), last = group_last(grp);
         if (first == last) {
@@ -378,8 +379,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
 #pragma unroll
                 for (int b = 0; b < MT; ++b)
                     *(floatx4*)(slot + ((size_t)((wave * 2 + t) * MT + b) * 64 + lane) * 4) = acc[t][b];
-            __syncthreads();            // every wavefront's partial has been acknowledged by the L2
-            if (tid == 0) atomicAdd(op.cnt + grp * kCntStride, 1u);
+            // signalled after the loop: no barrier in the middle of the stream
         }
         acc_zero();
     };
@@ -428,8 +428,12 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
         }
 
         // ---- cooperative finish of the split groups this workgroup took part in
-        if (!rinv_ready) compute_rinv();
         int gfirst = (int)(c0 / op.ncpg), glast = (int)((c1 - 1) / op.ncpg);
+        __syncthreads();                // every wavefront's partials have been acknowledged by the L2
+        if (tid == 0)
+            for (int grp = gfirst; grp <= glast; ++grp)
+                if (group_first(grp) != group_last(grp)) atomicAdd(op.cnt + grp * kCntStride, 1u);
+        if (!rinv_ready) compute_rinv();
         for (int grp = gfirst; grp <= glast; ++grp) {
             int first = group_first(grp), last = group_last(grp);
             if (first == last) continue;
