@@ -568,7 +568,10 @@ __device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const ha
             me = w - wl0;
         }
         if (me >= np) continue;                            // more workgroups than tiles
-        const int t0 = ntile * me / np, t1 = ntile * (me + 1) / np;
+        // boundaries rounded up: when the tiles do not divide evenly the longer ranges come
+        // first, and the last workgroup, whose range ends with the (costlier) tree tile, gets
+        // a shorter one
+        const int t0 = (ntile * me + np - 1) / np, t1 = (ntile * (me + 1) + np - 1) / np;
         const half_t* kh_ = kc + (size_t)head * a.stride_head;
         const half_t* vh_ = vc + (size_t)head * a.v_stride_head;
 
