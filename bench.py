@@ -112,7 +112,7 @@ def linear_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w
     achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
     att_ms, att_n = timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, 2, steps)
     kv_bytes = 2 * 2 * s.L * s.nh * s.d * (kv_len + w.M)
-    return {"bound": "hbm", "kernel": "k_linear<MT>", "achieved": round(achieved, 1),
+    return {"bound": "hbm", "kernel": "k_linear<MT, RS>", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": recorded_traffic(), "launches_per_step": per_step,
             "avg_launch_us": round(avg_ms * 1e3, 2),

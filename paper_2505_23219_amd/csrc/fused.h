@@ -38,7 +38,7 @@ struct FusedArgs {
     float eps, scale_log2e;
     // scratch (device)
     uint32_t* sync;        // kSyncWords
-    float* part;           // GEMM partial slots: [G][2][16*MT KiB]
+    float* part;           // GEMM partial slots: [G][2][up to 16*MT KiB]
     float* o_part;         // attention partial states, one per workgroup: [G][Mpad][d]
     float* ml_part;        // [G][Mpad][2]
     float* x;              // residual stream [M, H] fp32
@@ -54,6 +54,7 @@ struct FusedArgs {
     const half_t* lin_x;
     void* lin_y;
     int lin_N, lin_K, lin_epi;
+    int lin_rs;            // row split of the 256-row groups (1, 2 or 4; capped by the LDS at M > 64)
     int lin_rscale;        // the input is xg16: scale output row m by the RMSNorm factor of x[m]
     const half_t* lin_gnext;   // EPI_RESID: gain of the norm that follows (xg16 is rewritten)
     half_t *lin_kc, *lin_vc;   // EPI_QKV: the layer's cache

@@ -78,10 +78,10 @@ __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
 // XCD i % 8 (checked at kernel start), so the logical index j = (i % 8) * G/8 + i / 8
 // puts the G/8 workgroups of an XCD side by side.  An item that is split over several
 // workgroups is therefore always finished inside one XCD, and its partial results are
-// exchanged through that XCD's L2 with plain stores and loads: the writers' stores have
-// been acknowledged by the L2 when they pass __syncthreads(), only then does thread 0
-// bump the item's counter, and a reader's first access to a slot line in a launch cannot
-// hit in its L1.  No device-scope fence (a write-back and invalidate of a whole L2, about
+// exchanged through that XCD's L2 with plain stores and loads: every wavefront waits for
+// the acknowledgement of its own stores before the barrier after which thread 0 bumps the
+// item's counter, and a reader's first access to a slot line in a launch cannot hit in
+// its L1.  No device-scope fence (a write-back and invalidate of a whole L2, about
 // 4 us here) is needed anywhere inside a phase.
 struct Share {
     int U;        // units of this XCD (fits 32 bits together with the factor Ge)
@@ -121,6 +121,12 @@ __device__ __forceinline__ Share make_share(int items, int per_item, int j, int 
     }
     return sh;
 }
+
+// Every wavefront calls this before the barrier that precedes a counter bump: it returns
+// once the wavefront's own stores have been acknowledged by the L2, i.e. are visible to
+// the other compute units of the XCD.  (The barrier alone orders the wavefronts of the
+// workgroup, not their stores still on the way to the L2.)  s_waitcnt vmcnt(0).
+__device__ __forceinline__ void wait_own_stores() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // Waits until *p >= target.  Gives up (and raises the status word to `code`) after
 // kWaitTicks of wall-clock time, or as soon as another workgroup has given up, so that a
@@ -230,15 +236,31 @@ __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, f
 // ---------------------------------------------------------------------------
 // one skinny linear layer
 // ---------------------------------------------------------------------------
-template <int MT>
+//
+// RS (1, 2 or 4) cuts every 256-row group of the packed matrix into RS row slices of
+// TGS = 16 / RS tiles; a slice is the item of the work shares, and a chunk is 4 * RS k-steps
+// of a slice (64 KiB whatever RS).  The 8 wavefronts form 8 / RS tile pairs times RS
+// k-slices: wavefront w streams tiles 2 tp, 2 tp + 1 (tp = w % (8 / RS)) for k-steps
+// 4 ksl .. 4 ksl + 3 (ksl = w / (8 / RS)) of every chunk, and the k-slices are added up
+// through LDS when a row slice ends.  A larger RS means smaller partial sums where the K
+// range of a slice is split between workgroups (their traffic goes with 1 / RS) and more of
+// x staged per workgroup (goes with RS).
+template <int MT, int RS>
 __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op, Ctx& cx)
 {
-    constexpr int CHUNK = kCH * MT * kFrag;        // LDS bytes of one staged x chunk
-    constexpr int PIECES = kCH * MT * 64;          // 16-byte pieces per chunk
+    constexpr int TGS = kTG / RS;                  // tiles of a row slice
+    constexpr int TP = TGS / 2;                    // tile pairs = wavefronts per k-slice
+    constexpr int KS = kCH * RS;                   // k-steps of a chunk
+    constexpr int CHUNK = KS * MT * kFrag;         // LDS bytes of one staged x chunk
+    constexpr int PIECES = KS * MT * 64;           // 16-byte pieces per chunk
     constexpr int PPT = (PIECES + kFT - 1) / kFT;
-    constexpr int NF = kTG * MT;                   // fragments of one row group
+    constexpr int NF = TGS * MT;                   // fragments of one row slice
+    static_assert((8 / RS) * RS == 8 && TP >= 1, "RS is 1, 2 or 4");
+    static_assert((RS - 1) * TP * 2 * MT * 1024 <= CHUNK, "the k-slice sums go through one x buffer");
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c = lane & 15, g4 = lane >> 4;
+    const int tp = wave % TP, ksl = wave / TP;
+    const int nks = ((op.K + kChunkCols - 1) / kChunkCols) * kCH;   // k-steps of the packed matrix
     char* xs = cx.lds;                             // 2 * CHUNK
     float* s_rinv = (float*)(cx.lds + 2 * CHUNK);  // Mpad floats
     float* s_tmp = s_rinv + 128;                   // 1024 floats
@@ -252,13 +274,22 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     // chunk is requested right after k-step s of the current one has been consumed.  (Two
     // chunks in flight were measured slower at every M: the extra registers and the longer
     // fill cost more than the deeper queue gains.)
-    const half8* wbase = op.W + (size_t)(wave * 2) * 64 + lane;
     half8 wb[kCH][2];
+    const half8* wp_next;        // this wavefront's first tile, k-step 0 of its group
+    int ks_next;                 // its first k-step in the chunk w_locate() was called for
+    auto w_locate = [&](int cu) {
+        int sg = cu / op.ncpg, kc = cu - sg * op.ncpg;
+        int grp = sg / RS, q = sg - grp * RS;
+        wp_next = op.W + ((size_t)grp * nks * kTG + q * TGS + tp * 2) * 64 + lane;
+        ks_next = kc * KS + ksl * kCH;
+    };
     // Loads inside the streaming loop are unconditional (the tail is peeled instead): a load
     // that may or may not be issued makes the number of younger loads unknown, and every
     // wait for an older one then has to drain the whole queue.
-    auto w_fetch = [&](int s, int cu) {
-        const half8* p = wbase + ((size_t)cu * kCH + s) * (kTG * 64);
+    // k-steps past the end of the matrix (ragged last chunk of a slice) re-read the last
+    // one: their x is staged as zeros
+    auto w_fetch = [&](int s) {
+        const half8* p = wp_next + (size_t)min(ks_next + s, nks - 1) * (kTG * 64);
         // streamed once: non-temporal, so the weights do not push x and the partial sums
         // out of the L2
         wb[s][0] = __builtin_nontemporal_load(p);
@@ -282,7 +313,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     half8 xr[PPT];
     bool xok[PPT];
     auto x_fetch = [&](int cu) {
-        int kbase = (int)(min(cu, c1 - 1) % op.ncpg) * kChunkCols;
+        int kbase = (int)(min(cu, c1 - 1) % op.ncpg) * (KS * 32);
 #pragma unroll
         for (int i = 0; i < PPT; ++i) {
             int k = kbase + p_koff[i];
@@ -300,8 +331,9 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     // so that staging does not wait behind the ring.
     auto w_first = [&]() {
         if (c0 >= c1) return;
+        w_locate(c0);
 #pragma unroll
-        for (int s = 0; s < kCH; ++s) w_fetch(s, c0);
+        for (int s = 0; s < kCH; ++s) w_fetch(s);
     };
     if (c0 < c1) x_fetch(c0);
     w_first();
@@ -350,36 +382,68 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     };
     acc_zero();
 
-    // A group's parts: workgroups first..last own pieces of its K range.
-    auto group_first = [&](int grp) { return sh.first_of(grp); };
-    auto group_last = [&](int grp) { return sh.last_of(grp); };
-    // slot 0 of a workgroup holds the partial of the group its range begins in, slot 1 that
-    // of the group it ends in (when that is another one)
-    auto slot_of = [&](int wg, int grp) -> float* {
-        return a.part + ((size_t)wg * 2 + (sh.begins_in(wg, grp) ? 0 : 1)) * (size_t)(NF * 256);
+    // The parts of a row slice: workgroups first..last own pieces of its K range.  A
+    // workgroup's range is contiguous, so only the slice it begins in and the slice it ends
+    // in can be shared with others.  Slot 0 of a workgroup holds the partial of the slice
+    // its range begins in, slot 1 that of the slice it ends in (when that is another one).
+    auto slot_of = [&](int wg, int sg) -> float* {
+        return a.part + ((size_t)wg * 2 + (sh.begins_in(wg, sg) ? 0 : 1)) * (size_t)(NF * 256);
+    };
+    // A shared slice is counted on the line of its first part (a workgroup is the first
+    // part of at most one shared slice: the one its range ends in).
+    auto counter_of = [&](int first) { return op.cnt + first * kCntStride; };
+    // first output feature of tile `tile` of slice sg
+    auto row0_of = [&](int sg, int tile) {
+        int grp = sg / RS, q = sg - grp * RS;
+        return (grp * kTG + q * TGS + tile) * 16;
     };
 
-    // Ends the accumulation of row group `grp`: direct epilogue when this workgroup
-    // owns the whole K range, otherwise store the partial (the group's counter is bumped
-    // once the whole share has been streamed).
-    auto flush = [&](int grp) {
-        int first = group_first(grp), last = group_last(grp);
-        if (first == last) {
-            if (!rinv_ready) compute_rinv();
+    // Ends the accumulation of row slice `sg`, whose last chunk was staged in x buffer
+    // `buf`: the k-slices are added up (in index order) in the wavefronts of k-slice 0,
+    // which then run the epilogue when this workgroup owns the whole K range, and otherwise
+    // store the partial (the slice's counter is bumped once the whole share has been streamed).
+    auto flush = [&](int sg, int buf) {
+        const int first = sh.first_of(sg), last = sh.last_of(sg);
+        if (first == last && !rinv_ready) compute_rinv();
+        if constexpr (RS > 1) {
+            // the buffer's x was consumed before the barrier that ended the chunk, and nothing
+            // is staged into it before the next chunk's end
+            floatx4* red = (floatx4*)(xs + buf * CHUNK);
+            if (ksl > 0) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+                for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int b = 0; b < MT; ++b)
-                    epilogue(a, op, acc[t][b], b * 16 + c, (grp * kTG + wave * 2 + t) * 16 + g4 * 4,
-                             lane, s_rinv);
-        } else {
-            float* slot = slot_of(cx.j, grp);
+                    for (int b = 0; b < MT; ++b)
+                        red[((((ksl - 1) * TP + tp) * 2 + t) * MT + b) * 64 + lane] = acc[t][b];
+            }
+            __syncthreads();
+            if (ksl == 0) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+                for (int sl = 1; sl < RS; ++sl)
 #pragma unroll
-                for (int b = 0; b < MT; ++b)
-                    *(floatx4*)(slot + ((size_t)((wave * 2 + t) * MT + b) * 64 + lane) * 4) = acc[t][b];
-            // signalled after the loop: no barrier in the middle of the stream
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int b = 0; b < MT; ++b)
+                            acc[t][b] += red[((((sl - 1) * TP + tp) * 2 + t) * MT + b) * 64 + lane];
+            }
+            __syncthreads();
+        }
+        if (ksl == 0) {
+            if (first == last) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int b = 0; b < MT; ++b)
+                        epilogue(a, op, acc[t][b], b * 16 + c, row0_of(sg, tp * 2 + t) + g4 * 4, lane, s_rinv);
+            } else {
+                float* slot = slot_of(cx.j, sg);
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int b = 0; b < MT; ++b)
+                        *(floatx4*)(slot + ((size_t)((tp * 2 + t) * MT + b) * 64 + lane) * 4) = acc[t][b];
+                // signalled after the loop: no barrier for it in the middle of the stream
+            }
         }
         acc_zero();
     };
@@ -388,12 +452,13 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
         x_store(0);
         x_fetch(c0 + 1);
         __syncthreads();
-        // One chunk: 4 k-steps of MFMAs, each followed (FW) by the request for the same
-        // k-step of the next chunk; then the next x chunk goes to LDS and the one after it
-        // is requested.  No branches: the wait counts stay exact.
+        // One chunk: this wavefront's 4 k-steps of MFMAs, each followed (FW) by the request
+        // for the same k-step of the next chunk; then the next x chunk goes to LDS and the
+        // one after it is requested.  No branches: the wait counts stay exact.
         auto chunk_step = [&](auto fw, int cu) {
             constexpr bool FW = decltype(fw)::value;
-            const char* xb = xs + (int)((cu - c0) & 1) * CHUNK + g4 * 272 + c * 16;
+            const char* xb = xs + (int)((cu - c0) & 1) * CHUNK + ksl * (kCH * MT * kFrag) + g4 * 272 + c * 16;
+            if constexpr (FW) w_locate(cu + 1);
 #pragma unroll
             for (int s = 0; s < kCH; ++s) {
                 // at most four x fragments live at a time (register budget at M > 64)
@@ -410,7 +475,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
                             acc[t][b0 + b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
                                 wb[s][t], xf[b], acc[t][b0 + b], 0, 0, 0);
                 }
-                if constexpr (FW) w_fetch(s, cu + 1);
+                if constexpr (FW) w_fetch(s);
             }
             x_store((int)((cu + 1 - c0) & 1));
             x_fetch(cu + 2);
@@ -418,35 +483,38 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
         };
         const int fend = c1 - 1;        // the last chunk has nothing left to prefetch
         for (int cu = c0; cu < c1;) {
-            int grp = (int)(cu / op.ncpg);
-            int se = min(c1, (grp + 1) * op.ncpg);
+            int sg = (int)(cu / op.ncpg);
+            int se = min(c1, (sg + 1) * op.ncpg);
             int mid = min(se, max(fend, cu));
             for (int b = cu; b < mid; ++b) chunk_step(std::true_type{}, b);
             for (int b = mid; b < se; ++b) chunk_step(std::false_type{}, b);
-            flush(grp);
+            flush(sg, (int)((se - 1 - c0) & 1));
             cu = se;
         }
 
-        // ---- cooperative finish of the split groups this workgroup took part in
+        // ---- cooperative finish of the shared slices this workgroup took part in
         int gfirst = (int)(c0 / op.ncpg), glast = (int)((c1 - 1) / op.ncpg);
+        wait_own_stores();
         __syncthreads();                // every wavefront's partials have been acknowledged by the L2
         if (tid == 0)
-            for (int grp = gfirst; grp <= glast; ++grp)
-                if (group_first(grp) != group_last(grp)) atomicAdd(op.cnt + grp * kCntStride, 1u);
+            for (int sg = gfirst; sg <= glast; ++sg) {
+                int first = sh.first_of(sg);
+                if (first != sh.last_of(sg)) atomicAdd(counter_of(first), 1u);
+            }
         if (!rinv_ready) compute_rinv();
-        for (int grp = gfirst; grp <= glast; ++grp) {
-            int first = group_first(grp), last = group_last(grp);
+        for (int sg = gfirst; sg <= glast; ++sg) {
+            int first = sh.first_of(sg), last = sh.last_of(sg);
             if (first == last) continue;
             int np = last - first + 1, me = cx.j - first;
-            if (tid == 0) bounded_wait(a.sync, op.cnt + grp * kCntStride, (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
+            if (tid == 0) bounded_wait(a.sync, counter_of(first), (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
             __syncthreads();
             int f0 = NF * me / np, f1 = NF * (me + 1) / np;
             for (int f = f0 + wave; f < f1; f += 8) {
                 // Sum the parts in index order (fixed order: the result does not depend on
                 // timing), eight loads in flight at a time.  Parts after the first begin
-                // inside this group, so their partial is in their slot 0.
+                // inside this slice, so their partial is in their slot 0.
                 const size_t foff = ((size_t)f * 64 + lane) * 4;
-                floatx4 v = *(const floatx4*)(slot_of(first, grp) + foff);
+                floatx4 v = *(const floatx4*)(slot_of(first, sg) + foff);
                 for (int p0 = 1; p0 < np; p0 += 8) {
                     floatx4 t[8];
 #pragma unroll
@@ -458,7 +526,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
                         if (p0 + q < np) v += t[q];
                 }
                 int tile = f / MT, b = f % MT;
-                epilogue(a, op, v, b * 16 + c, (grp * kTG + tile) * 16 + g4 * 4, lane, s_rinv);
+                epilogue(a, op, v, b * 16 + c, row0_of(sg, tile) + g4 * 4, lane, s_rinv);
             }
         }
     }
@@ -812,6 +880,7 @@ __device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const ha
                 }
             }
         }
+        wait_own_stores();
         __syncthreads();   // partial state acknowledged by the L2; hand-over buffers free again
         if (tid == 0) atomicAdd(sync + kCntAttn + head * kCntStride, 1u);
 
@@ -882,7 +951,7 @@ __device__ __forceinline__ Ctx make_ctx(const FusedArgs& a, char* lds)
     return cx;
 }
 
-template <int MT>
+template <int MT, int RS>
 __global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -902,9 +971,10 @@ __global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
     op.vc = a.lin_vc;
     op.cnt = a.sync + a.lin_cnt;
     op.epoch = a.lin_epoch;
-    op.ngroups = (op.N + kGroupRows - 1) / kGroupRows;
-    op.ncpg = (op.K + kChunkCols - 1) / kChunkCols;
-    gemm_phase<MT>(a, op, cx);
+    // items of the work shares: row slices, each of ncpg chunks of 4 * RS k-steps
+    op.ngroups = ((op.N + kGroupRows - 1) / kGroupRows) * RS;
+    op.ncpg = (op.K + kChunkCols * RS - 1) / (kChunkCols * RS);
+    gemm_phase<MT, RS>(a, op, cx);
 }
 
 template <int MT, int D>
@@ -932,10 +1002,10 @@ int fused_grid_size()
     return g_num_cu;
 }
 
-template <int MT>
+template <int MT, int RS>
 static size_t linear_lds_bytes()
 {
-    return 2 * (size_t)kCH * MT * kFrag + (128 + 1024) * sizeof(float);
+    return 2 * (size_t)kCH * RS * MT * kFrag + (128 + 1024) * sizeof(float);
 }
 
 // All workgroups must be resident at once (they wait for each other): one per compute unit.
@@ -959,11 +1029,24 @@ static ghd_status launch_resident(Kernel kernel, bool& checked, size_t lds, cons
     return check_launch();
 }
 
-template <int MT>
+template <int MT, int RS>
 static ghd_status launch_linear_t(const FusedArgs& a, hipStream_t st)
 {
     static bool checked = false;
-    return launch_resident(k_linear<MT>, checked, linear_lds_bytes<MT>(), a, st);
+    return launch_resident(k_linear<MT, RS>, checked, linear_lds_bytes<MT, RS>(), a, st);
+}
+
+// Row split of a linear layer (see gemm_phase).  The two x buffers of RS * MT * 4.25 KiB
+// each have to fit the LDS: RS * MT <= 16.
+template <int MT>
+static ghd_status launch_linear_rs(const FusedArgs& a, hipStream_t st)
+{
+    int rs = a.lin_rs;
+    if constexpr (MT * 4 <= 16)
+        if (rs >= 4) return launch_linear_t<MT, 4>(a, st);
+    if constexpr (MT * 2 <= 16)
+        if (rs >= 2) return launch_linear_t<MT, 2>(a, st);
+    return launch_linear_t<MT, 1>(a, st);
 }
 
 template <int MT, int D>
@@ -987,10 +1070,10 @@ ghd_status launch_fused(const FusedArgs& a, hipStream_t st)
 {
     const int mt = (a.M + 15) / 16;
     if (a.mode == MODE_LINEAR) {
-        if (mt <= 1) return launch_linear_t<1>(a, st);
-        if (mt <= 2) return launch_linear_t<2>(a, st);
-        if (mt <= 4) return launch_linear_t<4>(a, st);
-        return launch_linear_t<8>(a, st);
+        if (mt <= 1) return launch_linear_rs<1>(a, st);
+        if (mt <= 2) return launch_linear_rs<2>(a, st);
+        if (mt <= 4) return launch_linear_rs<4>(a, st);
+        return launch_linear_rs<8>(a, st);
     }
     return a.d == 64 ? launch_attention_d<64>(a, mt, st) : launch_attention_d<128>(a, mt, st);
 }

@@ -22,7 +22,7 @@ import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CALIBRATION_BYTES = 1 << 30          # bench.py --pmc-calibrate copies 1 GiB
-LINEAR_KERNEL = re.compile(r"k_linear<4>")
+LINEAR_KERNEL = re.compile(r"k_linear<4, 1>")
 COPY_KERNEL = re.compile(r"k_debug_copy")
 
 
@@ -50,8 +50,8 @@ def stats(path: str, out: str, command: str) -> None:
         f.write("# rocprofv3 kernel statistics: verification step, workload stack7b\n\n")
         f.write("Command (on the GPU box, from the repository root):\n\n    %s\n\n" % command)
         f.write("Kernels of this library only (model set-up and PyTorch fill kernels left out); "
-                "the run holds tree steps (M=64: `k_linear<4>`, `k_attention<4, 128>`) and 1-token "
-                "decode steps (`k_linear<1>`, `k_attention<1, 128>`).\n\n")
+                "the run holds tree steps (M=64: `k_linear<4, 1>`, `k_attention<4, 128>`) and 1-token "
+                "decode steps (`k_linear<1, 2>`, `k_attention<1, 128>`).\n\n")
         f.write("| kernel | calls | avg us | min us | max us | total ms | share |\n|---|---|---|---|---|---|---|\n")
         for r in sorted(rows, key=lambda r: -int(r["TotalDurationNs"])):
             f.write("| `%s` | %s | %.2f | %.2f | %.2f | %.3f | %.1f%% |\n" % (
@@ -82,7 +82,7 @@ def traffic(fetch_csv: str, write_csv: str, out: str, command: str) -> None:
     w_scale = CALIBRATION_BYTES / w_copy
     fetched, written = f_lin * f_scale, w_lin * w_scale
     with open(out, "w") as f:
-        f.write("# HBM traffic of the linear-layer kernel `k_linear<4>`, workload stack7b\n\n")
+        f.write("# HBM traffic of the linear-layer kernel `k_linear<4, 1>`, workload stack7b\n\n")
         f.write("Commands (on the GPU box, from the repository root; one counter per run):\n\n")
         f.write("    %s\n\n" % command.replace("COUNTER", "FETCH_SIZE"))
         f.write("    %s\n\n" % command.replace("COUNTER", "WRITE_SIZE"))
