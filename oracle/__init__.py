@@ -78,8 +78,10 @@ class Oracle:
             getattr(self.lib, fn).restype = C.c_int
         for fn in ("orc_tree_depth", "orc_tree_mask", "orc_linear", "orc_rmsnorm", "orc_rope",
                    "orc_swiglu", "orc_tree_attention", "orc_verify_layer", "orc_lm_head",
-                   "orc_verify_stack", "orc_accept_greedy"):
+                   "orc_verify_stack", "orc_accept_greedy", "orc_commit_path", "orc_embed",
+                   "orc_draft_logits", "orc_topk", "orc_tree_tokens"):
             getattr(self.lib, fn).restype = None
+        self.lib.orc_tree_build.restype = C.c_int
 
     # ---- helpers
     def _r(self, a) -> np.ndarray:
@@ -253,3 +255,81 @@ class Oracle:
         nh, cap, d = kc.shape
         self.lib.orc_commit_path(_p(kc), _p(vc), C.c_int(nh), C.c_int(cap), C.c_int(d),
                                  C.c_int(kv_len), _p(p), C.c_int(len(p)))
+
+    # ---- drafting
+    def embed(self, table16, tokens) -> np.ndarray:
+        """Rows tokens[i] of the embedding table, as uint16 bit patterns [M, H]."""
+        tb, t = _u16(table16), _i32(tokens)
+        assert t.min() >= 0 and t.max() < tb.shape[0]
+        x = np.empty((len(t), tb.shape[1]), dtype=np.uint16)
+        self.lib.orc_embed(_p(x), _p(tb), _p(t), C.c_int(len(t)), C.c_int(tb.shape[1]))
+        return x
+
+    def draft_logits(self, x_row, g_final16, Wheads16, K: int, eps: float, round16: bool) -> np.ndarray:
+        """Logits [K, V] of the K drafting heads (stacked [K*V, H]) for one hidden state [H]."""
+        x = self._r(x_row).reshape(-1)
+        g, W = _u16(g_final16), _u16(Wheads16)
+        H = x.shape[0]
+        assert W.shape[1] == H and W.shape[0] % K == 0
+        V = W.shape[0] // K
+        out = np.empty((K, V), dtype=self.real)
+        self.lib.orc_draft_logits(_p(out), _p(x), _p(g), _p(W), C.c_int(K), C.c_int(V), C.c_int(H),
+                                  self.creal(eps), C.c_int(int(round16)))
+        return out
+
+    def topk(self, v, R: int) -> np.ndarray:
+        """Indices [rows, R] of the R largest entries of every row, best first, lowest index on ties."""
+        a = self._r(v)
+        rows, V = a.shape
+        assert 1 <= R <= V
+        idx = np.empty((rows, R), dtype=np.int32)
+        self.lib.orc_topk(_p(idx), _p(a), C.c_int(rows), C.c_int(V), C.c_int(R))
+        return idx
+
+    def tree_tokens(self, parent, rank, topk, root_token: int) -> np.ndarray:
+        p, r = _i32(parent), _i32(rank)
+        tk = _i32(topk)
+        out = np.empty(len(p), dtype=np.int32)
+        self.lib.orc_tree_tokens(_p(out), _p(p), _p(r), C.c_int(len(p)), _p(tk), C.c_int(tk.shape[1]),
+                                 C.c_int(int(root_token)))
+        return out
+
+    def tree_build(self, acc, M: int):
+        """Greedy tree design from head accuracies acc [K, R].  Returns (parent, rank, expected
+        acceptance length); the tree may have fewer than M nodes when the candidates run out."""
+        a = np.ascontiguousarray(acc, dtype=np.float64)
+        K, R = a.shape
+        parent = np.zeros(M, dtype=np.int32)
+        rank = np.zeros(M, dtype=np.int32)
+        e = C.c_double(0.0)
+        n = self.lib.orc_tree_build(_p(a), C.c_int(K), C.c_int(R), C.c_int(M), _p(parent), _p(rank),
+                                    C.byref(e))
+        return parent[:n].copy(), rank[:n].copy(), float(e.value)
+
+    # ---- one predict-then-verify step (section 2.1), composed of the pieces above
+    def spec_step(self, shape, layers, kcs, vcs, head, table16, tokens, parent, kv_len: int,
+                  round16: bool):
+        """The tree's tokens (root = the last produced token, not yet in the cache) are
+        embedded, verified in one pass, the longest valid root path is accepted and its K/V
+        rows are committed (the caches are updated in place).  Returns a dict: `n` accepted
+        nodes (the context grows by n), `produced` = the n tokens this step adds to the output
+        (the accepted drafted tokens, then the model's next token), `next_token`, `path`,
+        `amax`, `logits`, `x_last` = final hidden state of the last accepted node (input of
+        the drafting heads)."""
+        t, p = _i32(tokens), _i32(parent)
+        x16 = self.embed(table16, t)
+        logits, x_out = self.verify_stack(shape, layers, kcs, vcs, head, x16, p, kv_len, round16)
+        n, nxt, path, amax = self.accept_greedy(logits, t, p)
+        for l in range(shape.L):
+            self.commit_path(kcs[l], vcs[l], kv_len, path)
+        produced = [int(t[i]) for i in path[1:]] + [nxt]
+        return {"n": n, "produced": produced, "next_token": nxt, "path": path, "amax": amax,
+                "logits": logits, "x_last": x_out[path[-1]].copy()}
+
+    def draft(self, x_last, g_final16, Wheads16, K: int, R: int, eps: float, parent, rank,
+              root_token: int, round16: bool):
+        """Tokens of the next tree from the drafting heads' top-R candidates.  Returns
+        (tokens [M], topk [K, R], head logits [K, V])."""
+        hl = self.draft_logits(x_last, g_final16, Wheads16, K, eps, round16)
+        tk = self.topk(hl, R)
+        return self.tree_tokens(parent, rank, tk, root_token), tk, hl

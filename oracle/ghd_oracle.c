@@ -441,3 +441,128 @@ void orc_commit_path(uint16_t *kc, uint16_t *vc, int nh, int cap, int d, int kv_
         }
     free(tmp);
 }
+
+/* -------------------------------------------------------------- drafting -- */
+
+/* The drafting side of a decoding step (section 2.1: predictions for several
+ * future slots are made in parallel and then verified; section 2.3: with
+ * self-drafting, extra heads at the tail of the model predict the tokens of
+ * the future slots, head k the slot k + 1 positions after the next token, each
+ * with several candidates; section 3.3.1: the candidates are combined into a
+ * verification tree).  Pins (tests/test_oracle_draft.py): top-R against a full
+ * sort; head logits against the LM-head routine fed one head at a time; the
+ * tree design against exhaustive search over all trees of the same width; the
+ * decoding loop against plain sequential greedy decoding (drafting and
+ * verification never change the produced tokens). */
+
+/* Embedding: row i of x is row tokens[i] of the table (fp16 bit patterns). */
+void orc_embed(uint16_t *x, const uint16_t *table, const int32_t *tokens, int M, int H)
+{
+    for (int i = 0; i < M; ++i)
+        memcpy(x + (size_t)i * H, table + (size_t)tokens[i] * H, (size_t)H * sizeof(uint16_t));
+}
+
+/* Logits of the K drafting heads for ONE hidden state x_row[H] (the final
+ * residual stream of the last accepted node): every head is a linear layer
+ * [V, H] on the normalised state, the heads' matrices stacked as [K*V, H].
+ * out[k*V + v].  The state is normalised and rounded exactly as for the LM head. */
+void orc_draft_logits(real *out, const real *x_row, const uint16_t *g_final,
+                      const uint16_t *Wheads, int K, int V, int H, real eps, int round16)
+{
+    real *n = (real *)malloc((size_t)H * sizeof(real));
+    orc_rmsnorm(n, x_row, g_final, 1, H, eps);
+    maybe_round(n, (size_t)H, round16);
+    orc_linear(out, n, Wheads, 1, K * V, H);
+    free(n);
+}
+
+/* The R best entries of each row, best first: R times over, the lowest index
+ * of the largest value not yet taken.  idx[row*R + r]. */
+void orc_topk(int32_t *idx, const real *v, int rows, int V, int R)
+{
+    uint8_t *taken = (uint8_t *)malloc((size_t)V);
+    for (int row = 0; row < rows; ++row) {
+        const real *a = v + (size_t)row * V;
+        memset(taken, 0, (size_t)V);
+        for (int r = 0; r < R; ++r) {
+            int best = -1;
+            for (int j = 0; j < V; ++j)
+                if (!taken[j] && (best < 0 || a[j] > a[best]))
+                    best = j;
+            taken[best] = 1;
+            idx[(size_t)row * R + r] = best;
+        }
+    }
+    free(taken);
+}
+
+/* Tokens of the next verification tree: the root carries the token the model
+ * has just produced; a node at depth t >= 1 carries candidate rank[i] of head
+ * t - 1 (its parent fixes the earlier slots).  topk[k*R + r]. */
+void orc_tree_tokens(int32_t *tokens, const int32_t *parent, const int32_t *rank, int M,
+                     const int32_t *topk, int R, int32_t root_token)
+{
+    int32_t depth[ORC_MAX_M];
+    orc_tree_depth(parent, M, depth);
+    tokens[0] = root_token;
+    for (int i = 1; i < M; ++i)
+        tokens[i] = topk[(size_t)(depth[i] - 1) * R + rank[i]];
+}
+
+/* Tree design (section 3.3.1).  acc[k*R + r] is the measured accuracy of
+ * candidate r of head k.  The accuracy of a candidate sequence is estimated as
+ * the product of the accuracies of its tokens; a node is accepted exactly when
+ * its whole sequence is, so the expected acceptance length of a tree is 1 (the
+ * root, always kept) plus the sum of its nodes' sequence accuracies.  Nodes are
+ * added one at a time, each time the candidate with the highest sequence
+ * accuracy whose parent is already in the tree, until the tree has M nodes
+ * (lowest parent, then lowest rank on ties).  Node order = insertion order, so
+ * parent[i] < i.  Stops early when no candidate is left; returns the number of
+ * nodes, *expect gets the expected acceptance length.  (The paper's final
+ * refinement by measured acceptance on a calibration set is outside this
+ * function: it needs data.) */
+int orc_tree_build(const double *acc, int K, int R, int M, int32_t *parent, int32_t *rank,
+                   double *expect)
+{
+    double p[ORC_MAX_M];
+    int depth[ORC_MAX_M];
+    int n = 1;
+    parent[0] = -1;
+    rank[0] = 0;
+    p[0] = 1.0;
+    depth[0] = 0;
+    double e = 1.0;
+    while (n < M) {
+        int bp = -1, br = -1;
+        double best = -1.0;
+        for (int u = 0; u < n; ++u) {
+            if (depth[u] >= K)
+                continue;
+            for (int r = 0; r < R; ++r) {
+                int used = 0;
+                for (int w = 0; w < n; ++w)
+                    if (parent[w] == u && rank[w] == r)
+                        used = 1;
+                if (used)
+                    continue;
+                double q = p[u] * acc[(size_t)depth[u] * R + r];
+                if (q > best) {
+                    best = q;
+                    bp = u;
+                    br = r;
+                }
+            }
+        }
+        if (bp < 0)
+            break;
+        parent[n] = bp;
+        rank[n] = br;
+        p[n] = best;
+        depth[n] = depth[bp] + 1;
+        e += best;
+        ++n;
+    }
+    if (expect)
+        *expect = e;
+    return n;
+}

@@ -17,15 +17,17 @@ enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 
 // The sync block (uint32 words), zeroed by the set-up kernel.  Every item counter has a
 // 128-byte line of its own (kCntStride words apart): the workgroups of one item poll and
-// bump it without disturbing the others.
+// bump it without disturbing the others.  A linear layer's shared row slice is counted on
+// the line of the first workgroup that has a part of it (one line per workgroup is enough);
+// each kind of linear layer has an array of its own, reused layer after layer by epoch.
 constexpr int kSyncStatus = 1;    // 0 = ok, else the code of the wait that gave up
 constexpr int kCntStride = 32;
 constexpr int kSyncCnt = 32;                          // first counter line
-constexpr int kCntQkv = kSyncCnt;                     // up to 512 row groups each
+constexpr int kCntQkv = kSyncCnt;                     // up to 512 workgroups each
 constexpr int kCntWo = kCntQkv + 512 * kCntStride;
 constexpr int kCntGu = kCntWo + 512 * kCntStride;
 constexpr int kCntDown = kCntGu + 512 * kCntStride;
-constexpr int kCntLm = kCntDown + 512 * kCntStride;   // up to 1024 row groups
+constexpr int kCntLm = kCntDown + 512 * kCntStride;   // LM head and stand-alone linear calls
 constexpr int kCntAttn = kCntLm + 1024 * kCntStride;  // up to 256 heads
 constexpr int kSyncWords = kCntAttn + 256 * kCntStride;
 

@@ -1014,7 +1014,7 @@ static ghd_status launch_resident(Kernel kernel, bool& checked, size_t lds, cons
                                   hipStream_t st)
 {
     int G = fused_grid_size();
-    if (G <= 0) return hip_fail(hipErrorInvalidDevice);
+    if (G <= 0 || G > 512) return hip_fail(hipErrorInvalidDevice);   // counter arrays hold 512 lines
     if (!checked) {
         hipError_t e = hipFuncSetAttribute((const void*)kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
