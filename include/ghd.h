@@ -223,6 +223,72 @@ size_t ghd_accept_workspace_bytes(int M);
 ghd_status ghd_commit_path(const ghd_model_cfg *cfg, const ghd_kv *kv_host, const int32_t *res_dev,
                            int M, int kv_len, void *stream);
 
+/* ---- drafting side of a decoding step (section 2.1: tokens for several future
+ *      slots are predicted and then verified together; section 2.3: with
+ *      self-drafting the predictions come from extra heads at the tail of the
+ *      model, each with several candidates; section 3.3.1: the candidates are
+ *      combined into the verification tree) ------------------------------- */
+
+/* x16[i, :] = table16[tokens[i], :]: fp16 hidden states [M, H] of the tree's tokens
+ * from the embedding table fp16 [V, H].  Tokens are clamped to [0, V). */
+ghd_status ghd_embed(void *x16, const void *table16, const int32_t *tokens_dev, int M, int H, int V,
+                     void *stream);
+
+/* Tree design from head accuracies (section 3.3.1), on the host: acc_host[k*R + r]
+ * in [0, 1] is the accuracy of candidate r of head k; a node's score is the
+ * product of the accuracies along its root path, the expected acceptance length
+ * of a tree 1 + the sum of its nodes' scores.  Inserts the best-scoring open
+ * candidate until the tree has M nodes (lower parent, then lower rank on ties);
+ * node order = insertion order.  parent_host, rank_host: int32 [M] (rank[i] =
+ * which candidate of head depth[i]-1 node i carries; rank[0] = 0).  Returns the
+ * number of nodes (< M when K*R levels cannot supply more) or a negative
+ * ghd_status; *expect_host (optional) receives the expected acceptance length.
+ * The paper's last step, a local search by measured acceptance on a calibration
+ * set, needs data and is not part of this call. */
+int ghd_tree_build(const double *acc_host, int K, int R, int M, int32_t *parent_host,
+                   int32_t *rank_host, double *expect_host);
+
+/* Tokens of the next tree.  The K drafting heads are linear layers [V, H] on the
+ * RMS-normalised (gain g_final fp16 [H]) final hidden state of the last accepted
+ * node; Wheads is their stacked matrix [K*V, H] packed with ghd_pack_weight
+ * (plain).  x_final float [M, H] is the final residual stream of the verification
+ * pass (x_out of ghd_verify_stack), res_dev the result of ghd_accept_greedy for
+ * it; the last accepted node is read on the device.  Per head the R best
+ * candidates are taken, best first, lowest index on ties (logits must be finite).
+ * tokens_dev[0] = res_dev[1] (the token the model has just produced);
+ * tokens_dev[i] = candidate rank_dev[i] of head depth[i]-1.  A tree deeper than K
+ * levels or a rank >= R is the caller's error; indices are clamped so that
+ * nothing outside the tables is read.  topk_dev int32 [K, R] and head_logits
+ * float [K*V] are optional outputs.  K <= 16, R <= 32, K*V <= 262144. */
+ghd_status ghd_draft_tokens(const void *g_final, const void *Wheads, int K, int R, int H, int V,
+                            float rms_eps, const float *x_final, const int32_t *res_dev,
+                            const int32_t *parent_dev, const int32_t *rank_dev, int M,
+                            int32_t *tokens_dev, int32_t *topk_dev, float *head_logits, void *ws,
+                            size_t ws_bytes, void *stream);
+size_t ghd_draft_workspace_bytes(int K, int R, int H, int V);
+
+/* One whole predict-then-verify step (section 2.1), enqueued without a host round
+ * trip: embed the tree's tokens, verify (ghd_verify_stack), accept
+ * (ghd_accept_greedy), commit the accepted path (ghd_commit_path), draft the next
+ * tree's tokens (ghd_draft_tokens).  tokens_dev int32 [M]: in, the tree's tokens
+ * (tokens[0] = the last produced token, not yet cached); out, the next tree's.
+ * res_dev int32 [2+M]: out, the acceptance result; the step adds res_dev[0]
+ * tokens to the output (the accepted drafted tokens tokens[path[1..]] as they were
+ * on entry, then res_dev[1]) and the caller's next kv_len is kv_len + res_dev[0]. */
+typedef struct {
+    const ghd_model_cfg *cfg;
+    const ghd_layer_weights *layers_host;   /* host array [cfg->L] */
+    const ghd_kv *kv_host;                  /* host array [cfg->L] */
+    const void *g_final, *Wlm;              /* as for ghd_verify_stack */
+    const void *embed;                      /* fp16 [V, H], row-major */
+    const void *Wheads;                     /* packed from [K*V, H] */
+    int32_t K, R;                           /* drafting heads, candidates per head */
+} ghd_spec_model;
+ghd_status ghd_spec_step(const ghd_spec_model *m, const int32_t *parent_dev, const int32_t *rank_dev,
+                         int M, int kv_len, int32_t *tokens_dev, int32_t *res_dev, void *ws,
+                         size_t ws_bytes, void *stream);
+size_t ghd_spec_workspace_bytes(const ghd_spec_model *m, int M, int kv_len);
+
 #ifdef __cplusplus
 }
 #endif

@@ -47,6 +47,12 @@ class KV(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p)]
 
 
+class SpecModel(C.Structure):
+    _fields_ = [("cfg", C.c_void_p), ("layers_host", C.c_void_p), ("kv_host", C.c_void_p),
+                ("g_final", C.c_void_p), ("Wlm", C.c_void_p), ("embed", C.c_void_p),
+                ("Wheads", C.c_void_p), ("K", C.c_int32), ("R", C.c_int32)]
+
+
 _lib = None
 
 
@@ -79,6 +85,13 @@ def lib() -> C.CDLL:
             "ghd_accept_greedy": (C.c_int32, [vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]),
             "ghd_accept_workspace_bytes": (sz, [i32]),
             "ghd_commit_path": (C.c_int32, [vp, vp, vp, i32, i32, vp]),
+            "ghd_embed": (C.c_int32, [vp, vp, vp, i32, i32, i32, vp]),
+            "ghd_tree_build": (C.c_int, [vp, i32, i32, i32, vp, vp, vp]),
+            "ghd_draft_tokens": (C.c_int32, [vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, i32, vp, vp,
+                                             vp, vp, sz, vp]),
+            "ghd_draft_workspace_bytes": (sz, [i32, i32, i32, i32]),
+            "ghd_spec_step": (C.c_int32, [vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]),
+            "ghd_spec_workspace_bytes": (sz, [vp, i32, i32]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -93,7 +106,9 @@ EXPORTS = ["ghd_status_str", "ghd_last_hip_error", "ghd_tree_validate", "ghd_tre
            "ghd_packed_weight_bytes", "ghd_pack_weight", "ghd_linear_skinny",
            "ghd_linear_workspace_bytes", "ghd_tree_attention", "ghd_attention_workspace_bytes",
            "ghd_verify_layer", "ghd_verify_stack", "ghd_workspace_bytes", "ghd_accept_greedy",
-           "ghd_accept_workspace_bytes", "ghd_commit_path"]
+           "ghd_accept_workspace_bytes", "ghd_commit_path", "ghd_embed", "ghd_tree_build",
+           "ghd_draft_tokens", "ghd_draft_workspace_bytes", "ghd_spec_step",
+           "ghd_spec_workspace_bytes"]
 
 
 def status_str(status: int) -> str:
@@ -275,3 +290,73 @@ def ghd_commit_path(stack: Stack, res: torch.Tensor, M: int, kv_len: int) -> Non
     to rows kv_len.. of every layer's cache, in place."""
     _check(lib().ghd_commit_path(C.byref(stack.cfg), stack.kv, _ptr(_dev(res, torch.int32)), M, kv_len,
                                  _stream()), "ghd_commit_path")
+
+
+# ---- drafting side ------------------------------------------------------------
+def ghd_embed(table: torch.Tensor, tokens: torch.Tensor, x16: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """table fp16 [V, H], tokens int32 [M] on the GPU -> fp16 [M, H]."""
+    V, H = table.shape
+    M = tokens.numel()
+    if x16 is None:
+        x16 = torch.empty((M, H), dtype=torch.float16, device=table.device)
+    _check(lib().ghd_embed(_ptr(x16), _ptr(_dev(table, torch.float16)), _ptr(_dev(tokens, torch.int32)),
+                           M, H, V, _stream()), "ghd_embed")
+    return x16
+
+
+def ghd_tree_build(acc, M: int):
+    """acc: K rows of R head accuracies (host).  Returns (parent, rank, expected acceptance
+    length) as Python lists / float."""
+    K, R = len(acc), len(acc[0])
+    flat = (C.c_double * (K * R))(*[float(a) for row in acc for a in row])
+    parent, rank = (C.c_int32 * M)(), (C.c_int32 * M)()
+    e = C.c_double(0.0)
+    n = lib().ghd_tree_build(C.cast(flat, C.c_void_p), K, R, M, C.cast(parent, C.c_void_p),
+                             C.cast(rank, C.c_void_p), C.cast(C.pointer(e), C.c_void_p))
+    if n < 0:
+        raise GhdError(n, "ghd_tree_build")
+    return list(parent[:n]), list(rank[:n]), float(e.value)
+
+
+def ghd_draft_tokens(g_final: torch.Tensor, Wheads: torch.Tensor, K: int, R: int, V: int, rms_eps: float,
+                     x_final: torch.Tensor, res: torch.Tensor, parent: torch.Tensor, rank: torch.Tensor,
+                     tokens: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """Returns (tokens int32 [M], topk int32 [K, R], head logits float [K, V]) on the GPU."""
+    M, H = x_final.shape
+    dev = x_final.device
+    if tokens is None:
+        tokens = torch.empty(M, dtype=torch.int32, device=dev)
+    topk = torch.empty((K, R), dtype=torch.int32, device=dev)
+    logits = torch.empty((K, V), dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = workspace(lib().ghd_draft_workspace_bytes(K, R, H, V), dev)
+    _check(lib().ghd_draft_tokens(_ptr(_dev(g_final, torch.float16)), _ptr(Wheads), K, R, H, V, rms_eps,
+                                  _ptr(_dev(x_final, torch.float32)), _ptr(_dev(res, torch.int32)),
+                                  _ptr(_dev(parent, torch.int32)), _ptr(_dev(rank, torch.int32)), M,
+                                  _ptr(_dev(tokens, torch.int32)), _ptr(topk), _ptr(logits), _ptr(ws),
+                                  ws.numel(), _stream()), "ghd_draft_tokens")
+    return tokens, topk, logits
+
+
+class SpecState:
+    """Pointer block of ghd_spec_step for a Stack plus embedding table and drafting heads."""
+
+    def __init__(self, stack: Stack, embed: torch.Tensor, Wheads: torch.Tensor, K: int, R: int):
+        self.stack = stack
+        self.keep = (embed, Wheads)
+        self.c = SpecModel(C.addressof(stack.cfg), C.addressof(stack.lw), C.addressof(stack.kv),
+                           stack.g_final.data_ptr(), stack.Wlm.data_ptr(),
+                           _dev(embed, torch.float16).data_ptr(), Wheads.data_ptr(), K, R)
+
+    def workspace_bytes(self, M: int, kv_len: int) -> int:
+        return lib().ghd_spec_workspace_bytes(C.byref(self.c), M, kv_len)
+
+
+def ghd_spec_step(spec: SpecState, parent: torch.Tensor, rank: torch.Tensor, kv_len: int,
+                  tokens: torch.Tensor, res: torch.Tensor, ws: torch.Tensor) -> None:
+    """One predict-then-verify step, enqueued; tokens (in/out) and res (out) on the GPU."""
+    M = parent.numel()
+    _check(lib().ghd_spec_step(C.byref(spec.c), _ptr(_dev(parent, torch.int32)),
+                               _ptr(_dev(rank, torch.int32)), M, kv_len, _ptr(_dev(tokens, torch.int32)),
+                               _ptr(_dev(res, torch.int32)), _ptr(ws), ws.numel(), _stream()),
+           "ghd_spec_step")

@@ -541,6 +541,167 @@ ghd_status ghd_commit_path(const ghd_model_cfg* cfg, const ghd_kv* kv_host, cons
                               (hipStream_t)stream);
 }
 
+// ---- drafting side -------------------------------------------------------------
+ghd_status ghd_embed(void* x16, const void* table16, const int32_t* tokens_dev, int M, int H, int V,
+                     void* stream)
+{
+    if (!x16 || !table16 || !tokens_dev) return GHD_ERR_NULL;
+    if (M < 1 || M > GHD_MAX_M || H < 8 || (H % 8) != 0 || V < 1) return GHD_ERR_SHAPE;
+    if (!aligned16(x16) || !aligned16(table16)) return GHD_ERR_ALIGN;
+    return launch_embed(x16, table16, tokens_dev, M, H, V, (hipStream_t)stream);
+}
+
+int ghd_tree_build(const double* acc_host, int K, int R, int M, int32_t* parent_host,
+                   int32_t* rank_host, double* expect_host)
+{
+    if (!acc_host || !parent_host || !rank_host) return GHD_ERR_NULL;
+    if (K < 1 || R < 1 || M < 1 || M > GHD_MAX_M) return GHD_ERR_SHAPE;
+    for (int i = 0; i < K * R; ++i)
+        if (!(acc_host[i] >= 0.0 && acc_host[i] <= 1.0)) return GHD_ERR_SHAPE;
+    return tree_build_host(acc_host, K, R, M, parent_host, rank_host, expect_host);
+}
+
+struct DraftWs {
+    Ws lin;
+    half_t* n16;
+    float* logits;
+    int32_t* topk;
+    size_t bytes;
+};
+
+static DraftWs carve_draft(void* ws, int H, int K, int V, int R)
+{
+    DraftWs d = {};
+    d.lin = carve(ws, 1, 1, 0, 0, 0);
+    Carver cv(ws);
+    cv.off = d.lin.bytes;
+    d.n16 = cv.take<half_t>((size_t)H);
+    d.logits = cv.take<float>((size_t)K * V);
+    d.topk = cv.take<int32_t>((size_t)K * R);
+    d.bytes = cv.off;
+    return d;
+}
+
+static bool draft_shape_ok(int K, int R, int H, int V)
+{
+    return K >= 1 && K <= 16 && R >= 1 && R <= 32 && R <= V && H >= 8 && (H % 8) == 0 && V >= 1 &&
+           (int64_t)K * V <= 1024 * kGroupRows;
+}
+
+size_t ghd_draft_workspace_bytes(int K, int R, int H, int V)
+{
+    if (!draft_shape_ok(K, R, H, V)) return 0;
+    return carve_draft(nullptr, H, K, V, R).bytes;
+}
+
+ghd_status ghd_draft_tokens(const void* g_final, const void* Wheads, int K, int R, int H, int V,
+                            float rms_eps, const float* x_final, const int32_t* res_dev,
+                            const int32_t* parent_dev, const int32_t* rank_dev, int M,
+                            int32_t* tokens_dev, int32_t* topk_dev, float* head_logits, void* ws,
+                            size_t ws_bytes, void* stream)
+{
+    if (!g_final || !Wheads || !x_final || !res_dev || !parent_dev || !rank_dev || !tokens_dev)
+        return GHD_ERR_NULL;
+    if (!draft_shape_ok(K, R, H, V) || M < 1 || M > GHD_MAX_M || !(rms_eps >= 0.f)) return GHD_ERR_SHAPE;
+    if (!aligned16(g_final) || !aligned16(Wheads) || !aligned16(x_final) ||
+        (head_logits && !aligned16(head_logits)))
+        return GHD_ERR_ALIGN;
+    if (!ws) return GHD_ERR_WORKSPACE;
+    if (!aligned16(ws)) return GHD_ERR_ALIGN;
+    if (ws_bytes < ghd_draft_workspace_bytes(K, R, H, V)) return GHD_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    DraftWs d = carve_draft(ws, H, K, V, R);
+    float* logits = head_logits ? head_logits : d.logits;
+    int32_t* topk = topk_dev ? topk_dev : d.topk;
+    ghd_status s = launch_fused_setup(d.lin.sync, nullptr, 1, mpad_of(1), 0, 0, 1.f, nullptr, nullptr,
+                                      nullptr, nullptr, 0, nullptr, nullptr, nullptr, st);
+    if (s) return s;
+    if ((s = launch_pick_norm(x_final, res_dev, M, H, g_final, rms_eps, d.n16, st))) return s;
+    FusedArgs a = {};
+    a.mode = MODE_LINEAR;
+    a.M = 1;
+    a.Mpad = mpad_of(1);
+    a.d = 128;
+    a.sync = d.lin.sync;
+    a.part = d.lin.part;
+    a.lin_W = (const half8*)Wheads;
+    a.lin_x = d.n16;
+    a.lin_y = logits;
+    a.lin_N = K * V;
+    a.lin_K = H;
+    a.lin_epi = EPI_STORE_F32;
+    a.lin_rs = row_split(1, K * V, H);
+    a.lin_cnt = kCntLm;
+    a.lin_epoch = 0;
+    a.lin_ldx = H;
+    a.lin_ldy = (int64_t)K * V;
+    if ((s = timed_fused(a, st))) return s;
+    if ((s = launch_topk(logits, K, V, R, topk, st))) return s;
+    return launch_tree_tokens(tokens_dev, parent_dev, rank_dev, M, topk, K, R, res_dev, V, st);
+}
+
+struct SpecWs {
+    void* verify;
+    void* accept;
+    void* draft;
+    half_t* x16;
+    float* logits;
+    float* x_out;
+    size_t verify_bytes, accept_bytes, draft_bytes, bytes;
+};
+
+static SpecWs carve_spec(void* ws, const ghd_spec_model* m, int M, int kv_len)
+{
+    SpecWs w = {};
+    const ghd_model_cfg* c = m->cfg;
+    w.verify_bytes = ghd_workspace_bytes(c, M, kv_len);
+    w.accept_bytes = ghd_accept_workspace_bytes(M);
+    w.draft_bytes = ghd_draft_workspace_bytes(m->K, m->R, c->H, c->V);
+    Carver cv(ws);
+    w.verify = cv.take<char>(w.verify_bytes);
+    w.accept = cv.take<char>(w.accept_bytes);
+    w.draft = cv.take<char>(w.draft_bytes);
+    w.x16 = cv.take<half_t>((size_t)M * c->H);
+    w.logits = cv.take<float>((size_t)M * c->V);
+    w.x_out = cv.take<float>((size_t)M * c->H);
+    w.bytes = cv.off;
+    return w;
+}
+
+size_t ghd_spec_workspace_bytes(const ghd_spec_model* m, int M, int kv_len)
+{
+    if (!m || !m->cfg || check_cfg(m->cfg, M, kv_len) != GHD_OK) return 0;
+    if (!draft_shape_ok(m->K, m->R, m->cfg->H, m->cfg->V)) return 0;
+    return carve_spec(nullptr, m, M, kv_len).bytes;
+}
+
+ghd_status ghd_spec_step(const ghd_spec_model* m, const int32_t* parent_dev, const int32_t* rank_dev,
+                         int M, int kv_len, int32_t* tokens_dev, int32_t* res_dev, void* ws,
+                         size_t ws_bytes, void* stream)
+{
+    if (!m || !m->cfg || !m->embed || !m->Wheads || !parent_dev || !rank_dev || !tokens_dev || !res_dev)
+        return GHD_ERR_NULL;
+    ghd_status s = check_cfg(m->cfg, M, kv_len);
+    if (s) return s;
+    if (!draft_shape_ok(m->K, m->R, m->cfg->H, m->cfg->V)) return GHD_ERR_SHAPE;
+    if (!ws) return GHD_ERR_WORKSPACE;
+    if (!aligned16(ws)) return GHD_ERR_ALIGN;
+    if (ws_bytes < ghd_spec_workspace_bytes(m, M, kv_len)) return GHD_ERR_WORKSPACE;
+    const ghd_model_cfg* c = m->cfg;
+    SpecWs w = carve_spec(ws, m, M, kv_len);
+    if ((s = ghd_embed(w.x16, m->embed, tokens_dev, M, c->H, c->V, stream))) return s;
+    if ((s = ghd_verify_stack(c, m->layers_host, m->kv_host, m->g_final, m->Wlm, w.x16, parent_dev, M,
+                              kv_len, w.logits, w.x_out, w.verify, w.verify_bytes, stream)))
+        return s;
+    if ((s = ghd_accept_greedy(w.logits, tokens_dev, parent_dev, M, c->V, res_dev, nullptr, w.accept,
+                               w.accept_bytes, stream)))
+        return s;
+    if ((s = ghd_commit_path(c, m->kv_host, res_dev, M, kv_len, stream))) return s;
+    return ghd_draft_tokens(m->g_final, m->Wheads, m->K, m->R, c->H, c->V, c->rms_eps, w.x_out, res_dev,
+                            parent_dev, rank_dev, M, tokens_dev, nullptr, nullptr, w.draft,
+                            w.draft_bytes, stream);
+}
+
 /* Benchmark support (not part of the documented ABI): time the launches of one kind
  * of the persistent kernel with HIP events on the launch stream.
  * ghd_debug_profile(1) starts a fresh measurement of the linear-layer launches,

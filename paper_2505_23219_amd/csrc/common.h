@@ -27,4 +27,17 @@ size_t accept_workspace_bytes();
 ghd_status launch_commit_path(void* const* k, void* const* v, int L, int nh, int d, int cap,
                               int kv_len, int M, const int32_t* res, hipStream_t st);
 
+
+// drafting side (draft.hip)
+ghd_status launch_embed(void* x16, const void* table16, const int32_t* tokens, int M, int H, int V,
+                        hipStream_t st);
+ghd_status launch_pick_norm(const float* x_final, const int32_t* res, int M, int H, const void* g,
+                            float eps, void* n16, hipStream_t st);
+ghd_status launch_topk(const float* logits, int rows, int V, int R, int32_t* topk, hipStream_t st);
+ghd_status launch_tree_tokens(int32_t* tokens, const int32_t* parent, const int32_t* rank, int M,
+                              const int32_t* topk, int K, int R, const int32_t* res, int V,
+                              hipStream_t st);
+int tree_build_host(const double* acc, int K, int R, int M, int32_t* parent, int32_t* rank,
+                    double* expect);
+
 }  // namespace ghd

@@ -231,6 +231,28 @@ def activations(M: int, width: int, seed: int, tag: str = "x", std: float = 1.0,
     return _normal_fp16((M, width), std, 0.0, _gen(seed, tag, M, width, device=device), device)
 
 
+def embedding_table(shape: ModelShape, seed: int, device: str = "cpu") -> torch.Tensor:
+    """Token embeddings [V, H] fp16 ~ N(0, 1)."""
+    return _normal_fp16((shape.V, shape.H), 1.0, 0.0, _gen(seed, shape.name, "embed", device=device),
+                        device)
+
+
+def drafting_heads(shape: ModelShape, K: int, seed: int, device: str = "cpu") -> torch.Tensor:
+    """The K drafting heads as one stacked matrix [K*V, H] fp16 ~ N(0, 0.02) (untrained:
+    their candidates are as good as random)."""
+    return _normal_fp16((K * shape.V, shape.H), 0.02, 0.0,
+                        _gen(seed, shape.name, "heads", K, device=device), device)
+
+
+def head_accuracies(K: int, R: int) -> np.ndarray:
+    """Synthetic per-head, per-candidate accuracies [K, R] of the shape reported for
+    multi-head drafting: the first candidate of the first head is right most often, and
+    accuracy falls with the head index and, faster, with the candidate rank."""
+    k = np.arange(K)[:, None]
+    r = np.arange(R)[None, :]
+    return 0.6 * 0.8 ** k * 0.35 ** r
+
+
 def draft_tokens(M: int, V: int, seed: int) -> np.ndarray:
     rng = np.random.default_rng([seed, 7919])
     return rng.integers(0, V, size=M, dtype=np.int32)

@@ -216,3 +216,77 @@ def test_commit_path_rejects_bad_arguments(lib):
     assert f(C.byref(cfg), C.byref(kv), FAKE, 8, 250, None) == B.GHD_ERR_CAPACITY
     assert f(C.byref(cfg), C.byref(B.KV(FAKE + 2, FAKE)), FAKE, 8, 100, None) == B.GHD_ERR_ALIGN
     assert f(C.byref(cfg), C.byref(B.KV(None, FAKE)), FAKE, 8, 100, None) == B.GHD_ERR_NULL
+
+
+# ---- drafting side -----------------------------------------------------------------------
+@pytest.mark.parametrize("K,R,M,seed", [(4, 3, 16, 0), (5, 10, 64, 1), (2, 2, 7, 2), (3, 1, 9, 3), (5, 4, 128, 4)])
+def test_tree_build_equals_the_oracle(lib, orc32, K, R, M, seed):
+    rng = np.random.default_rng(seed)
+    acc = np.sort(rng.uniform(0.01, 0.95, size=(K, R)), axis=1)[:, ::-1].copy()
+    parent, rank, e = B.ghd_tree_build(acc.tolist(), M)
+    p0, r0, e0 = orc32.tree_build(acc, M)
+    assert parent == p0.tolist() and rank == r0.tolist() and e == e0
+    assert B.ghd_tree_validate(parent) == B.GHD_OK
+
+
+def test_tree_build_with_equal_accuracies_breaks_ties_like_the_oracle(lib, orc32):
+    acc = np.full((3, 3), 0.5)
+    parent, rank, e = B.ghd_tree_build(acc.tolist(), 12)
+    p0, r0, e0 = orc32.tree_build(acc, 12)
+    assert parent == p0.tolist() and rank == r0.tolist() and e == e0
+
+
+def test_tree_build_rejects_bad_arguments(lib):
+    acc = (C.c_double * 4)(0.5, 0.4, 0.3, 0.2)
+    out = (C.c_int32 * 8)()
+    ap, op = C.cast(acc, C.c_void_p), C.cast(out, C.c_void_p)
+    assert lib.ghd_tree_build(None, 2, 2, 4, op, op, None) == B.GHD_ERR_NULL
+    assert lib.ghd_tree_build(ap, 0, 2, 4, op, op, None) == B.GHD_ERR_SHAPE
+    assert lib.ghd_tree_build(ap, 2, 2, 129, op, op, None) == B.GHD_ERR_SHAPE
+    bad = (C.c_double * 4)(0.5, 1.5, 0.3, 0.2)
+    assert lib.ghd_tree_build(C.cast(bad, C.c_void_p), 2, 2, 4, op, op, None) == B.GHD_ERR_SHAPE
+    nan = (C.c_double * 4)(0.5, float("nan"), 0.3, 0.2)
+    assert lib.ghd_tree_build(C.cast(nan, C.c_void_p), 2, 2, 4, op, op, None) == B.GHD_ERR_SHAPE
+
+
+def test_drafting_calls_reject_bad_arguments(lib):
+    assert lib.ghd_embed(None, FAKE, FAKE, 4, 64, 100, None) == B.GHD_ERR_NULL
+    assert lib.ghd_embed(FAKE, FAKE, FAKE, 4, 60, 100, None) == B.GHD_ERR_SHAPE
+    assert lib.ghd_embed(FAKE, FAKE, FAKE, 129, 64, 100, None) == B.GHD_ERR_SHAPE
+    assert lib.ghd_embed(FAKE + 8, FAKE, FAKE, 4, 64, 100, None) == B.GHD_ERR_ALIGN
+    assert lib.ghd_draft_workspace_bytes(5, 10, 4096, 32000) > 5 * 32000 * 4
+    assert lib.ghd_draft_workspace_bytes(17, 10, 4096, 32000) == 0      # K <= 16
+    assert lib.ghd_draft_workspace_bytes(5, 33, 4096, 32000) == 0       # R <= 32
+    assert lib.ghd_draft_workspace_bytes(9, 4, 4096, 32000) == 0        # K*V <= 262144
+
+    def draft(**kw):
+        a = dict(g=FAKE, W=FAKE, K=2, R=3, H=64, V=100, eps=1e-6, x=FAKE, res=FAKE, parent=FAKE,
+                 rank=FAKE, M=8, tokens=FAKE, topk=None, logits=None, ws=FAKE, ws_bytes=1 << 30)
+        a.update(kw)
+        return lib.ghd_draft_tokens(a["g"], a["W"], a["K"], a["R"], a["H"], a["V"], a["eps"], a["x"],
+                                    a["res"], a["parent"], a["rank"], a["M"], a["tokens"], a["topk"],
+                                    a["logits"], a["ws"], a["ws_bytes"], None)
+
+    assert draft(W=None) == B.GHD_ERR_NULL
+    assert draft(tokens=None) == B.GHD_ERR_NULL
+    assert draft(R=101) == B.GHD_ERR_SHAPE
+    assert draft(M=0) == B.GHD_ERR_SHAPE
+    assert draft(H=60) == B.GHD_ERR_SHAPE
+    assert draft(x=FAKE + 4) == B.GHD_ERR_ALIGN
+    assert draft(ws=None) == B.GHD_ERR_WORKSPACE
+    assert draft(ws_bytes=1024) == B.GHD_ERR_WORKSPACE
+
+
+def test_spec_step_rejects_bad_arguments(lib):
+    cfg = B.make_cfg(wl.TINY, 256)
+    m = B.SpecModel(C.addressof(cfg), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 3)
+    need = lib.ghd_spec_workspace_bytes(C.byref(m), 8, 100)
+    assert need > lib.ghd_workspace_bytes(C.byref(cfg), 8, 100)
+    assert lib.ghd_spec_step(None, FAKE, FAKE, 8, 100, FAKE, FAKE, FAKE, need, None) == B.GHD_ERR_NULL
+    assert lib.ghd_spec_step(C.byref(m), FAKE, FAKE, 8, 100, None, FAKE, FAKE, need, None) == B.GHD_ERR_NULL
+    assert lib.ghd_spec_step(C.byref(m), FAKE, FAKE, 8, 250, FAKE, FAKE, FAKE, need, None) == B.GHD_ERR_CAPACITY
+    assert lib.ghd_spec_step(C.byref(m), FAKE, FAKE, 8, 100, FAKE, FAKE, FAKE, need - 1, None) == B.GHD_ERR_WORKSPACE
+    assert lib.ghd_spec_step(C.byref(m), FAKE, FAKE, 8, 100, FAKE, FAKE, None, need, None) == B.GHD_ERR_WORKSPACE
+    m.K = 0
+    assert lib.ghd_spec_step(C.byref(m), FAKE, FAKE, 8, 100, FAKE, FAKE, FAKE, need, None) == B.GHD_ERR_SHAPE
+    assert lib.ghd_spec_workspace_bytes(C.byref(m), 8, 100) == 0

@@ -1,0 +1,211 @@
+"""GPU-vs-oracle parity of the drafting side and of whole predict-then-verify steps,
+through the C ABI, on the same seeded inputs.
+
+Integer results (embedding rows, candidate indices, tree tokens, produced tokens) must be
+identical wherever the oracle's decision is clear: a candidate is compared only where the
+oracle's logit gap to its neighbours in the sorted order exceeds 1e-3 (the GPU's logits
+differ from the oracle's by accumulation order); the test inputs are chosen so that this
+covers every decision, and the tests assert that it does.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_23219_amd import workloads as wl
+
+from test_gpu_parity import B, model, say, close, _capture_manager  # noqa: F401  (fixtures)
+
+pytestmark = pytest.mark.gpu
+
+
+def test_embed_bit_exact(B, orc32):
+    shape = wl.ModelShape("e", H=264, nh=1, d=64, F=8, V=777, L=1)
+    table = wl.embedding_table(shape, 3)
+    tokens = wl.draft_tokens(77, shape.V, 3)
+    tokens[:3] = [0, shape.V - 1, 5]
+    say("embed")
+    got = B.ghd_embed(table.cuda(), torch.from_numpy(tokens).cuda())
+    want = orc32.embed(table.numpy(), tokens)
+    assert np.array_equal(got.cpu().numpy().view(np.uint16), want)
+
+
+def clear_candidates(ref_logits, R, gap=1e-3):
+    """Per head: are the R + 1 largest oracle logits pairwise more than `gap` apart?"""
+    top = -np.sort(-ref_logits, axis=1)[:, :R + 1]
+    return (top[:, :-1] - top[:, 1:]).min(axis=1) > gap
+
+
+@pytest.mark.parametrize("H,V,K,R,M,seed", [(256, 1000, 3, 4, 8, 0), (512, 3000, 5, 10, 64, 5),
+                                            (4096, 32000, 2, 8, 16, 2)])
+def test_draft_tokens(B, orc32, H, V, K, R, M, seed):
+    shape = wl.ModelShape("d%d" % H, H=H, nh=H // 128 if H >= 128 else 1, d=128, F=8, V=V, L=1)
+    Wheads = wl.drafting_heads(shape, K, seed)
+    g = wl.head_weights(wl.ModelShape("g", H=H, nh=1, d=128, F=8, V=8, L=1), seed)["g_final"]
+    x_final = wl.activations(M, H, seed, tag="xf", std=3.0).float()
+    acc = wl.head_accuracies(K, R)
+    parent, rank, _ = orc32.tree_build(acc, M)
+    # an accepted path of three nodes ending in node `last`
+    depth = orc32.tree_depth(parent)
+    last = int(np.where(depth == 2)[0][0])
+    path = [int(parent[parent[last]]), int(parent[last]), last]
+    res = np.zeros(2 + M, dtype=np.int32)
+    res[0], res[1], res[2:5] = 3, 123 % V, path
+    ref_tokens, ref_topk, ref_logits = orc32.draft(x_final[last].numpy(), g.numpy(), Wheads.numpy(), K, R,
+                                                   shape.rms_eps, parent, rank, int(res[1]), True)
+    assert clear_candidates(ref_logits, R).all(), "pick another seed: near ties in the oracle's logits"
+    say("draft tokens H=%d V=%d K=%d R=%d M=%d" % (H, V, K, R, M))
+    Wp = B.ghd_pack_weight(Wheads.cuda())
+    tokens, topk, logits = B.ghd_draft_tokens(g.cuda(), Wp, K, R, V, shape.rms_eps, x_final.cuda(),
+                                              torch.from_numpy(res).cuda(), torch.from_numpy(parent).cuda(),
+                                              torch.from_numpy(rank).cuda())
+    ok, ma, mr = close(logits.cpu().numpy(), ref_logits, 2e-2, 1e-2)
+    assert ok, ("head logits", ma, mr)
+    assert np.array_equal(topk.cpu().numpy(), ref_topk)
+    assert np.array_equal(tokens.cpu().numpy(), ref_tokens)
+
+
+def test_topk_ties_take_the_lowest_index(B, orc32):
+    """Rows of the head matrix that are copies of each other give exactly equal logits on
+    both sides; among equal candidates the lowest index comes first."""
+    H, V, K, R, M = 256, 500, 2, 6, 4
+    shape = wl.ModelShape("tie", H=H, nh=2, d=128, F=8, V=V, L=1)
+    Wheads = wl.drafting_heads(shape, K, 5)
+    x_final = wl.activations(M, H, 5, tag="xf", std=2.0).float()
+    g = wl.head_weights(shape, 5)["g_final"]
+    res = np.zeros(2 + M, dtype=np.int32)
+    res[0], res[1], res[2] = 1, 9, 0
+    parent = np.array([-1, 0, 0, 1], dtype=np.int32)
+    rank = np.array([0, 0, 1, 0], dtype=np.int32)
+    # find each head's best row with the oracle and copy it to three other rows
+    base = orc32.draft_logits(x_final[0].numpy(), g.numpy(), Wheads.numpy(), K, shape.rms_eps, True)
+    W = Wheads.clone()
+    for k in range(K):
+        best = int(np.argmax(base[k]))
+        for other in (7, 123, 499):
+            W[k * V + other] = W[k * V + best]
+    ref_tokens, ref_topk, ref_logits = orc32.draft(x_final[0].numpy(), g.numpy(), W.numpy(), K, R,
+                                                   shape.rms_eps, parent, rank, 9, True)
+    for k in range(K):
+        assert len(set(ref_logits[k][ref_topk[k][:4]])) == 1        # a four-way tie at the top
+        assert list(ref_topk[k][:4]) == sorted(ref_topk[k][:4])
+    say("top-R ties")
+    tokens, topk, _ = B.ghd_draft_tokens(g.cuda(), B.ghd_pack_weight(W.cuda()), K, R, V, shape.rms_eps,
+                                         x_final.cuda(), torch.from_numpy(res).cuda(),
+                                         torch.from_numpy(parent).cuda(), torch.from_numpy(rank).cuda())
+    got = topk.cpu().numpy()
+    assert np.array_equal(got[:, :4], ref_topk[:, :4])
+    assert np.array_equal(tokens.cpu().numpy()[:3], ref_tokens[:3])
+
+
+class Loop:
+    """A model on both sides: numpy copies for the oracle, device tables for the library."""
+
+    def __init__(self, B, model, shape, K, R, M, kv_len, cap, seed):
+        self.shape, self.K, self.R, self.M, self.cap, self.seed = shape, K, R, M, cap, seed
+        layers = [wl.layer_weights(shape, seed, l) for l in range(shape.L)]
+        head = wl.head_weights(shape, seed)
+        self.table = wl.embedding_table(shape, seed)
+        self.Wheads = wl.drafting_heads(shape, K, seed)
+        caches = [wl.kv_cache(shape, cap, kv_len, seed, l) for l in range(shape.L)]
+        self.np_layers = [{k: v.numpy() for k, v in w.items()} for w in layers]
+        self.np_head = {k: v.numpy() for k, v in head.items()}
+        self.kcs = [c[0].numpy().copy() for c in caches]
+        self.vcs = [c[1].numpy().copy() for c in caches]
+        self.stack = model.build_stack(shape, cap, [model.upload_layer(w, shape.d) for w in layers],
+                                       [model.upload_cache(k, v) for k, v in caches],
+                                       model.upload_head(head))
+        self.spec = B.SpecState(self.stack, self.table.cuda(), B.ghd_pack_weight(self.Wheads.cuda()), K, R)
+
+
+def margins_ok(st, R, ref_head_logits):
+    """Every decision of the step is clear in the oracle: argmax of every node, and the
+    candidates of every head."""
+    top2 = np.sort(st["logits"], axis=1)[:, -2:]
+    return bool(((top2[:, 1] - top2[:, 0]) > 1e-3).all()) and bool(clear_candidates(ref_head_logits, R).all())
+
+
+@pytest.mark.parametrize("shape,K,R,M,kv_len,seed,steps", [
+    (wl.TINY, 3, 4, 8, 100, 7, 6),
+    (wl.ModelShape("loop2", H=512, nh=4, d=128, F=1376, V=3000, L=2), 4, 5, 24, 333, 1, 5),
+])
+def test_spec_steps_follow_the_oracle(B, model, orc32, shape, K, R, M, kv_len, seed, steps):
+    cap = ((kv_len + steps * M + M + 63) // 64) * 64
+    lp = Loop(B, model, shape, K, R, M, kv_len, cap, seed)
+    parent, rank, _ = orc32.tree_build(wl.head_accuracies(K, R), M)
+    tokens = wl.draft_tokens(M, shape.V, seed)
+    pd, rd = torch.from_numpy(parent).cuda(), torch.from_numpy(rank).cuda()
+    td = torch.from_numpy(tokens).cuda()
+    res = torch.zeros(2 + M, dtype=torch.int32, device="cuda")
+    ws = B.workspace(lp.spec.workspace_bytes(M, cap - M))
+    kv = kv_len
+    for step in range(steps):
+        st = orc32.spec_step(shape, lp.np_layers, lp.kcs, lp.vcs, lp.np_head, lp.table.numpy(), tokens,
+                             parent, kv, True)
+        nxt_tokens, ref_topk, ref_hl = orc32.draft(st["x_last"], lp.np_head["g_final"], lp.Wheads.numpy(),
+                                                   K, R, shape.rms_eps, parent, rank, st["next_token"], True)
+        assert margins_ok(st, R, ref_hl), "pick another seed: a near tie in the oracle at step %d" % step
+        say("spec step %d of %s: kv_len %d" % (step, shape.name, kv))
+        B.ghd_spec_step(lp.spec, pd, rd, kv, td, res, ws)
+        r = res.cpu().numpy()
+        assert r[0] == st["n"] and r[1] == st["next_token"]
+        assert np.array_equal(r[2:2 + r[0]], st["path"])
+        assert np.array_equal(td.cpu().numpy(), nxt_tokens)
+        kv += st["n"]
+        tokens = nxt_tokens
+        # the committed cache rows agree with the oracle's (fp16 values, within tolerance)
+        for l in range(shape.L):
+            k_dev, v_dev = lp.stack.keep[1][l]
+            ok, ma, _ = close(k_dev[:, :kv].float().cpu().numpy(),
+                              lp.kcs[l][:, :kv].astype(np.float32), 2e-2, 1e-2)
+            assert ok, ("k cache", l, ma)
+            ok, ma, _ = close(model.rows_of_v(v_dev)[:, :kv].float().cpu().numpy(),
+                              lp.vcs[l][:, :kv].astype(np.float32), 2e-2, 1e-2)
+            assert ok, ("v cache", l, ma)
+
+
+def test_spec_steps_with_planted_drafts_accept_them(B, model, orc32):
+    """Drafts that are right along one root path are accepted to that depth on the GPU as in
+    the oracle, and the tokens produced are those of one-token-at-a-time decoding on the GPU."""
+    shape = wl.ModelShape("plant", H=512, nh=4, d=128, F=1376, V=3000, L=2)
+    K, R, M, kv_len, seed = 4, 3, 16, 200, 4
+    cap = 512
+    parent = np.array([-1, 0, 0, 1, 1, 3, 3, 5, 5, 7, 2, 2, 10, 10, 12, 9], dtype=np.int32)
+    rank = np.zeros(M, dtype=np.int32)
+    chain = [0, 1, 3, 5, 7, 9, 15]
+    # one-token-at-a-time decoding on the GPU: the sequence the model produces
+    seq = Loop(B, model, shape, K, R, 1, kv_len, cap, seed)
+    one = torch.tensor([-1], dtype=torch.int32, device="cuda")
+    zero = torch.zeros(1, dtype=torch.int32, device="cuda")
+    td = torch.tensor([17], dtype=torch.int32, device="cuda")
+    res1 = torch.zeros(3, dtype=torch.int32, device="cuda")
+    ws1 = B.workspace(seq.spec.workspace_bytes(1, cap - 1))
+    want, kv = [], kv_len
+    say("planted drafts: sequential decoding")
+    for _ in range(24):
+        B.ghd_spec_step(seq.spec, one, zero, kv, td, res1, ws1)
+        r = res1.cpu().numpy()
+        assert r[0] == 1
+        want.append(int(r[1]))
+        td[0] = int(r[1])
+        kv += 1
+    # tree decoding with the right continuation planted along `chain`
+    lp = Loop(B, model, shape, K, R, M, kv_len, cap, seed)
+    pd, rd = torch.from_numpy(parent).cuda(), torch.from_numpy(rank).cuda()
+    res = torch.zeros(2 + M, dtype=torch.int32, device="cuda")
+    ws = B.workspace(lp.spec.workspace_bytes(M, cap - M))
+    depth = orc32.tree_depth(parent)
+    got, kv, tok = [], kv_len, 17
+    for planted in (3, 6, 1, 4):
+        future = want[len(got):]
+        tokens = np.array([(future[depth[i] - 1] + 1) % shape.V if i else tok for i in range(M)], dtype=np.int32)
+        for j in range(1, planted + 1):
+            tokens[chain[j]] = future[j - 1]
+        say("planted drafts: depth %d" % planted)
+        td = torch.from_numpy(tokens).cuda()
+        B.ghd_spec_step(lp.spec, pd, rd, kv, td, res, ws)
+        r = res.cpu().numpy()
+        assert r[0] == planted + 1 and list(r[2:2 + r[0]]) == chain[:planted + 1]
+        got += [int(tokens[i]) for i in r[3:2 + r[0]]] + [int(r[1])]
+        kv += int(r[0])
+        tok = int(r[1])
+    assert got == want[:len(got)]
