@@ -25,17 +25,63 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_gpu_model(wl, B, model, w, device):
+def build_gpu_model(wl, B, model, w, device, capacity=None):
     s = w.shape
+    capacity = capacity or w.capacity
     layers, caches = [], []
     for l in range(s.L):
         layers.append(model.upload_layer(wl.layer_weights(s, w.seed, l, device=device), s.d, device))
-        caches.append(model.upload_cache(*wl.kv_cache(s, w.capacity, w.kv_len, w.seed, l, device=device),
+        caches.append(model.upload_cache(*wl.kv_cache(s, capacity, w.kv_len, w.seed, l, device=device),
                                          device=device))
         if l % 8 == 7:
             log("  built layer %d/%d" % (l + 1, s.L))
     head = model.upload_head(wl.head_weights(s, w.seed, device=device), device)
-    return model.build_stack(s, w.capacity, layers, caches, head)
+    return model.build_stack(s, capacity, layers, caches, head)
+
+
+def decode_loop(torch, B, wl, stack, w, stream, steps, K=5, R=10):
+    """Whole predict-then-verify steps back to back (ghd_spec_step: embed, verify, accept,
+    commit, draft), with the one host read per step that tells the caller how far the
+    context grew.  The drafting heads are untrained synthetic matrices, so acceptance stays
+    near one token per step: the figure shows what a full step costs, not what trained heads
+    would accept."""
+    dev = "cuda"
+    s = w.shape
+    acc = wl.head_accuracies(K, R)
+    parent, rank, expect = B.ghd_tree_build(acc.tolist(), w.M)
+    M = len(parent)
+    embed = wl.embedding_table(s, w.seed, device=dev)
+    heads = B.ghd_pack_weight(wl.drafting_heads(s, K, w.seed, device=dev))
+    spec = B.SpecState(stack, embed, heads, K, R)
+    pd = torch.tensor(parent, dtype=torch.int32, device=dev)
+    rd = torch.tensor(rank, dtype=torch.int32, device=dev)
+    tokens = torch.from_numpy(wl.draft_tokens(M, s.V, w.seed)).to(dev)
+    res = torch.zeros(2 + M, dtype=torch.int32, device=dev)
+    cap = stack.cfg.kv_capacity
+    ws = B.workspace(spec.workspace_bytes(M, cap - M))
+    res_host = torch.zeros(2 + M, dtype=torch.int32).pin_memory()
+    kv, produced, done = w.kv_len, 0, 0
+    with torch.cuda.stream(stream):
+        for _ in range(3):                       # warm-up on the same cache rows
+            B.ghd_spec_step(spec, pd, rd, w.kv_len, tokens, res, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        while done < steps and kv + M <= cap:
+            B.ghd_spec_step(spec, pd, rd, kv, tokens, res, ws)
+            res_host.copy_(res, non_blocking=True)
+            stream.synchronize()
+            n = int(res_host[0])
+            kv += n
+            produced += n
+            done += 1
+        dt = time.perf_counter() - t0
+    head_bytes = 2 * K * s.V * s.H
+    return {"steps": done, "tokens": produced, "tokens_per_s": round(produced / dt, 1),
+            "us_per_step": round(dt / done * 1e6, 1), "mean_accepted": round(produced / done, 3),
+            "tree_nodes": M, "heads": K, "candidates_per_head": R,
+            "expected_accepted_at_synthetic_accuracies": round(expect, 3),
+            "drafting_head_bytes": head_bytes,
+            "note": "untrained synthetic heads; one 4-byte host read per step included"}
 
 
 def time_steps(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, res, amax, stream,
@@ -201,6 +247,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="also time one 7B-shaped layer at tree sizes 1..128 (adds a \"sweep\" list)")
+    ap.add_argument("--loop", type=int, default=0,
+                    help="also run this many whole predict-then-verify steps (adds \"decode_loop\")")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also launch one plain 1 GiB copy kernel (for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -217,7 +265,9 @@ def main():
     w = wl.workload(args.workload)
     s = w.shape
     log("building %s: L=%d H=%d F=%d V=%d M=%d kv_len=%d" % (w.name, s.L, s.H, s.F, s.V, w.M, w.kv_len))
-    stack = build_gpu_model(wl, B, model, w, dev)
+    # a decode loop needs cache rows for the tokens it will produce
+    capacity = w.capacity + (64 * ((args.loop * 8 + 63) // 64) if args.loop else 0)
+    stack = build_gpu_model(wl, B, model, w, dev, capacity)
     cfg = stack.cfg
     stream = torch.cuda.Stream()
 
@@ -274,6 +324,9 @@ def main():
         "tree_over_decode": round(ms / dec_ms, 3),
         "roofline": roof,
     }
+    if args.loop:
+        out["decode_loop"] = decode_loop(torch, B, wl, stack, w, stream, args.loop)
+        log("decode loop:", out["decode_loop"])
     if args.sweep:
         del stack
         torch.cuda.empty_cache()
