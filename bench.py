@@ -331,6 +331,14 @@ def main():
         del stack
         torch.cuda.empty_cache()
         out["sweep"] = sweep(torch, B, model, wl, stream)
+        # the width with the most expected accepted tokens per layer-time, for the synthetic
+        # head accuracies (5 heads, 10 candidates) and the latencies just measured
+        rows = [r for r in out["sweep"] if r["tree"] == ("chain" if r["M"] == 1 else "bushy")]
+        widths = [r["M"] for r in rows]
+        i, rate = B.ghd_choose_width(wl.head_accuracies(5, 10).tolist(), widths, [r["layer_us"] for r in rows])
+        out["width_choice"] = {"widths": widths, "chosen": widths[i],
+                               "expected_tokens_per_layer_ms": [round(x * 1e3, 3) for x in rate]}
+        log("width choice:", out["width_choice"])
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on %d layers ..." % args.cpu_sample_layers)
         out["cpu_baseline"] = cpu_baseline(wl, w, args.cpu_sample_layers)

@@ -248,6 +248,16 @@ ghd_status ghd_embed(void *x16, const void *table16, const int32_t *tokens_dev, 
 int ghd_tree_build(const double *acc_host, int K, int R, int M, int32_t *parent_host,
                    int32_t *rank_host, double *expect_host);
 
+/* Choice of the verification width (section 3.3.1: width and tree together fix
+ * the acceptance length; section 3.3.2: candidate widths, powers of two in the
+ * paper, are profiled on the hardware).  For every candidate width widths_host[i]
+ * with measured step time latency_host[i] > 0 the tree is designed as by
+ * ghd_tree_build; returns the index of the width with the most expected accepted
+ * tokens per unit of step time (the first on ties), or a negative ghd_status.
+ * rate_host (optional, double [n]) receives every candidate's rate.  Host only. */
+int ghd_choose_width(const double *acc_host, int K, int R, const int32_t *widths_host,
+                     const double *latency_host, int n, double *rate_host);
+
 /* Tokens of the next tree.  The K drafting heads are linear layers [V, H] on the
  * RMS-normalised (gain g_final fp16 [H]) final hidden state of the last accepted
  * node; Wheads is their stacked matrix [K*V, H] packed with ghd_pack_weight

@@ -82,6 +82,7 @@ class Oracle:
                    "orc_draft_logits", "orc_topk", "orc_tree_tokens"):
             getattr(self.lib, fn).restype = None
         self.lib.orc_tree_build.restype = C.c_int
+        self.lib.orc_choose_width.restype = C.c_int
 
     # ---- helpers
     def _r(self, a) -> np.ndarray:
@@ -305,6 +306,17 @@ class Oracle:
         n = self.lib.orc_tree_build(_p(a), C.c_int(K), C.c_int(R), C.c_int(M), _p(parent), _p(rank),
                                     C.byref(e))
         return parent[:n].copy(), rank[:n].copy(), float(e.value)
+
+    def choose_width(self, acc, widths, latency):
+        """Index of the width with the most expected accepted tokens per unit of step time,
+        and the rate of every candidate."""
+        a = np.ascontiguousarray(acc, dtype=np.float64)
+        w = _i32(widths)
+        lat = np.ascontiguousarray(latency, dtype=np.float64)
+        rate = np.zeros(len(w), dtype=np.float64)
+        i = self.lib.orc_choose_width(_p(a), C.c_int(a.shape[0]), C.c_int(a.shape[1]), _p(w), _p(lat),
+                                      C.c_int(len(w)), _p(rate))
+        return int(i), rate
 
     # ---- one predict-then-verify step (section 2.1), composed of the pieces above
     def spec_step(self, shape, layers, kcs, vcs, head, table16, tokens, parent, kv_len: int,

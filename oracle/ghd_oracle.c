@@ -566,3 +566,31 @@ int orc_tree_build(const double *acc, int K, int R, int M, int32_t *parent, int3
         *expect = e;
     return n;
 }
+
+/* Choice of the verification width (section 3.3.1: both the width and the tree
+ * determine the acceptance length, and a larger width costs a longer step;
+ * section 3.3.2: the candidate widths are profiled on the hardware).  For
+ * every candidate width the tree is designed as above; the width kept is the
+ * one with the most expected accepted tokens per unit of measured step time
+ * (the first such width on ties).  latency[i] is the measured step time at
+ * widths[i].  Returns the index of the chosen width; rate[i] (optional) gets
+ * expected tokens per unit time for every candidate. */
+int orc_choose_width(const double *acc, int K, int R, const int32_t *widths,
+                     const double *latency, int n, double *rate)
+{
+    int32_t parent[ORC_MAX_M], rank[ORC_MAX_M];
+    int best = 0;
+    double best_rate = -1.0;
+    for (int i = 0; i < n; ++i) {
+        double e;
+        orc_tree_build(acc, K, R, widths[i], parent, rank, &e);
+        double r = e / latency[i];
+        if (rate)
+            rate[i] = r;
+        if (r > best_rate) {
+            best_rate = r;
+            best = i;
+        }
+    }
+    return best;
+}

@@ -87,6 +87,7 @@ def lib() -> C.CDLL:
             "ghd_commit_path": (C.c_int32, [vp, vp, vp, i32, i32, vp]),
             "ghd_embed": (C.c_int32, [vp, vp, vp, i32, i32, i32, vp]),
             "ghd_tree_build": (C.c_int, [vp, i32, i32, i32, vp, vp, vp]),
+            "ghd_choose_width": (C.c_int, [vp, i32, i32, vp, vp, i32, vp]),
             "ghd_draft_tokens": (C.c_int32, [vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, i32, vp, vp,
                                              vp, vp, sz, vp]),
             "ghd_draft_workspace_bytes": (sz, [i32, i32, i32, i32]),
@@ -107,6 +108,7 @@ EXPORTS = ["ghd_status_str", "ghd_last_hip_error", "ghd_tree_validate", "ghd_tre
            "ghd_linear_workspace_bytes", "ghd_tree_attention", "ghd_attention_workspace_bytes",
            "ghd_verify_layer", "ghd_verify_stack", "ghd_workspace_bytes", "ghd_accept_greedy",
            "ghd_accept_workspace_bytes", "ghd_commit_path", "ghd_embed", "ghd_tree_build",
+           "ghd_choose_width",
            "ghd_draft_tokens", "ghd_draft_workspace_bytes", "ghd_spec_step",
            "ghd_spec_workspace_bytes"]
 
@@ -316,6 +318,20 @@ def ghd_tree_build(acc, M: int):
     if n < 0:
         raise GhdError(n, "ghd_tree_build")
     return list(parent[:n]), list(rank[:n]), float(e.value)
+
+
+def ghd_choose_width(acc, widths: Sequence[int], latency: Sequence[float]):
+    """Returns (index of the chosen width, expected accepted tokens per unit time of each)."""
+    K, R, n = len(acc), len(acc[0]), len(widths)
+    flat = (C.c_double * (K * R))(*[float(a) for row in acc for a in row])
+    w = (C.c_int32 * n)(*[int(x) for x in widths])
+    lat = (C.c_double * n)(*[float(x) for x in latency])
+    rate = (C.c_double * n)()
+    i = lib().ghd_choose_width(C.cast(flat, C.c_void_p), K, R, C.cast(w, C.c_void_p),
+                               C.cast(lat, C.c_void_p), n, C.cast(rate, C.c_void_p))
+    if i < 0:
+        raise GhdError(i, "ghd_choose_width")
+    return i, list(rate)
 
 
 def ghd_draft_tokens(g_final: torch.Tensor, Wheads: torch.Tensor, K: int, R: int, V: int, rms_eps: float,

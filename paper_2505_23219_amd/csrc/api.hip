@@ -561,6 +561,31 @@ int ghd_tree_build(const double* acc_host, int K, int R, int M, int32_t* parent_
     return tree_build_host(acc_host, K, R, M, parent_host, rank_host, expect_host);
 }
 
+int ghd_choose_width(const double* acc_host, int K, int R, const int32_t* widths_host,
+                     const double* latency_host, int n, double* rate_host)
+{
+    if (!acc_host || !widths_host || !latency_host) return GHD_ERR_NULL;
+    if (K < 1 || R < 1 || n < 1) return GHD_ERR_SHAPE;
+    for (int i = 0; i < K * R; ++i)
+        if (!(acc_host[i] >= 0.0 && acc_host[i] <= 1.0)) return GHD_ERR_SHAPE;
+    for (int i = 0; i < n; ++i)
+        if (widths_host[i] < 1 || widths_host[i] > GHD_MAX_M || !(latency_host[i] > 0.0)) return GHD_ERR_SHAPE;
+    int32_t parent[GHD_MAX_M], rank[GHD_MAX_M];
+    int best = 0;
+    double best_rate = -1.0;
+    for (int i = 0; i < n; ++i) {
+        double e = 0.0;
+        tree_build_host(acc_host, K, R, widths_host[i], parent, rank, &e);
+        const double r = e / latency_host[i];
+        if (rate_host) rate_host[i] = r;
+        if (r > best_rate) {
+            best_rate = r;
+            best = i;
+        }
+    }
+    return best;
+}
+
 struct DraftWs {
     Ws lin;
     half_t* n16;

@@ -290,3 +290,21 @@ def test_spec_step_rejects_bad_arguments(lib):
     m.K = 0
     assert lib.ghd_spec_step(C.byref(m), FAKE, FAKE, 8, 100, FAKE, FAKE, FAKE, need, None) == B.GHD_ERR_SHAPE
     assert lib.ghd_spec_workspace_bytes(C.byref(m), 8, 100) == 0
+
+
+def test_choose_width_equals_the_oracle(lib, orc32):
+    acc = wl.head_accuracies(5, 10)
+    widths = [1, 2, 4, 8, 16, 32, 64, 128]
+    for latency in ([110.0, 110.2, 110.5, 111.0, 112.5, 120.6, 141.6, 230.0], [1.0] * 8,
+                    [float(w) for w in widths]):
+        i, rate = B.ghd_choose_width(acc.tolist(), widths, latency)
+        i0, rate0 = orc32.choose_width(acc, widths, latency)
+        assert i == i0 and rate == rate0.tolist()
+    assert lib.ghd_choose_width(None, 1, 1, None, None, 1, None) == B.GHD_ERR_NULL
+    a = (C.c_double * 1)(0.5)
+    w = (C.c_int32 * 1)(200)
+    t = (C.c_double * 1)(1.0)
+    cast = lambda x: C.cast(x, C.c_void_p)
+    assert lib.ghd_choose_width(cast(a), 1, 1, cast(w), cast(t), 1, None) == B.GHD_ERR_SHAPE
+    w[0], t[0] = 4, 0.0
+    assert lib.ghd_choose_width(cast(a), 1, 1, cast(w), cast(t), 1, None) == B.GHD_ERR_SHAPE

@@ -197,3 +197,25 @@ def test_tree_decoding_with_planted_drafts_accepts_them_and_equals_sequential(or
         kv_len += st["n"]
         tok = st["next_token"]
     assert got == want[:len(got)]
+
+
+# ---- choice of the width (sections 3.3.1, 3.3.2) -------------------------------------------------
+def test_width_choice_closed_forms(orc32):
+    acc = np.array([[0.8], [0.5], [0.25]])          # one candidate per head: chains
+    widths = [1, 2, 3, 4]
+    expect = np.array([1.0, 1.8, 2.2, 2.3])
+    # the same step time at every width: the widest tree wins
+    i, rate = orc32.choose_width(acc, widths, [2.0] * 4)
+    assert i == 3 and np.allclose(rate, expect / 2.0, rtol=0, atol=1e-15)
+    # step time proportional to the width: one token at a time wins
+    i, rate = orc32.choose_width(acc, widths, [1.0, 2.0, 3.0, 4.0])
+    assert i == 0 and np.allclose(rate, expect / np.arange(1, 5), rtol=0, atol=1e-15)
+    # a step that gets 10% slower per extra node: rates 1, 1.636, 1.833, 1.769
+    i, rate = orc32.choose_width(acc, widths, [1.0, 1.1, 1.2, 1.3])
+    assert i == 2
+
+
+def test_width_choice_takes_the_first_of_equal_rates(orc32):
+    acc = np.array([[1.0]])                         # expected lengths 1, 2
+    i, _ = orc32.choose_width(acc, [1, 2], [1.0, 2.0])
+    assert i == 0
