@@ -106,6 +106,22 @@ def time_steps(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, r
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
+def step_spread(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, res, amax, stream, steps):
+    """Per-step durations (an event between every two steps, no host synchronisation inside):
+    median, 10th and 90th percentile in microseconds."""
+    with torch.cuda.stream(stream):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        ev[0].record(stream)
+        for i in range(steps):
+            B.ghd_verify_stack(stack, x_in, parent, kv_len, logits=logits, ws=ws)
+            B.ghd_accept_greedy(logits, tokens, parent, res=res, amax=amax, ws=aws)
+            ev[i + 1].record(stream)
+        torch.cuda.synchronize()
+    us = sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(steps))
+    pick = lambda q: us[min(steps - 1, int(round(q * (steps - 1))))]
+    return {"median_us": round(pick(0.5), 1), "p10_us": round(pick(0.1), 1), "p90_us": round(pick(0.9), 1)}
+
+
 def recorded_traffic():
     """HBM bytes per launch of the linear-layer kernel from the committed counter
     summary (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known
@@ -296,6 +312,10 @@ def main():
                              tree["ws"], tree["aws"], tree["logits"], tree["res"], tree["amax"],
                              stream, args.steps, args.warmup)
     log("tree step: %.1f us (wall %.1f us)" % (ms * 1e3, wall_ms * 1e3))
+    spread = step_spread(torch, B, stack, tree["x_in"], tree["parent"], tree["tokens"], w.kv_len,
+                         tree["ws"], tree["aws"], tree["logits"], tree["res"], tree["amax"], stream,
+                         max(args.steps, 20))
+    log("per-step spread:", spread)
     # the same model as a plain 1-token decode step: denominator of the "within 1.3x" target
     dec = inputs(1, wl.tree_chain(1))
     dec_ms, _ = time_steps(torch, B, stack, dec["x_in"], dec["parent"], dec["tokens"], w.kv_len,
@@ -317,6 +337,7 @@ def main():
                                "kv_len %d, greedy acceptance" % (w.name, s.L, w.M, w.kv_len)
                    if w.name == "stack7b" else w.name,
                    "M": w.M, "kv_len": w.kv_len, "L": s.L, "H": s.H, "F": s.F, "V": s.V},
+        "step_spread": spread,
         "step_algorithmic_bytes": step_bytes,
         "step_hbm_gbps": round(gbps, 1),
         "step_hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),

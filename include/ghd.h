@@ -163,6 +163,21 @@ ghd_status ghd_tree_attention(void *out, const void *q, const void *k_cache, con
                               void *stream);
 size_t ghd_attention_workspace_bytes(int M, int kv_len, int nh, int d);
 
+/* The same attention under an arbitrary verification pattern (section 2.3 shows
+ * three: the token tree, the several sequences of a draft model, the n-gram
+ * pattern of Lookahead).  mask_dev: uint64 [M][2], 8-byte aligned; bit j of row i
+ * (bits 0..63 in word 0, 64..127 in word 1) says that drafted token i sees
+ * drafted token j (cache row kv_len + j); every drafted token sees the committed
+ * rows [0, kv_len).  Bits from M on are ignored.  A row that sees no key at all
+ * (kv_len == 0 and no bit set) gives zeros.  ghd_tree_attention is the special
+ * case mask = ancestor-or-self (ghd_tree_mask writes that mask).  Everything else,
+ * workspace size included, as for ghd_tree_attention. */
+ghd_status ghd_masked_attention(void *out, const void *q, const void *k_cache, const void *v_cache,
+                                const uint64_t *mask_dev, int M, int kv_len, int nh, int d,
+                                int64_t k_stride_head, int64_t k_stride_tok, int64_t v_stride_head,
+                                int64_t v_stride_ch, float scale, void *ws, size_t ws_bytes,
+                                void *stream);
+
 /* ---- decoder layer and stack (section 2.2.2; model details as in the
  *      LLaMA architecture of section 4.1: RMSNorm, rotary positions at
  *      kv_len + depth, SwiGLU, no biases) -------------------------------- */

@@ -79,7 +79,7 @@ class Oracle:
         for fn in ("orc_tree_depth", "orc_tree_mask", "orc_linear", "orc_rmsnorm", "orc_rope",
                    "orc_swiglu", "orc_tree_attention", "orc_verify_layer", "orc_lm_head",
                    "orc_verify_stack", "orc_accept_greedy", "orc_commit_path", "orc_embed",
-                   "orc_draft_logits", "orc_topk", "orc_tree_tokens"):
+                   "orc_draft_logits", "orc_topk", "orc_tree_tokens", "orc_masked_attention"):
             getattr(self.lib, fn).restype = None
         self.lib.orc_tree_build.restype = C.c_int
         self.lib.orc_choose_width.restype = C.c_int
@@ -159,6 +159,24 @@ class Oracle:
         self.lib.orc_tree_attention(_p(out), _p(q), _p(kc), _p(vc), _p(p), C.c_int(M),
                                     C.c_int(kv_len), C.c_int(nh), C.c_int(d),
                                     C.c_int64(kc.shape[1] * d), C.c_int64(d), self.creal(scale))
+        return out
+
+    def masked_attention(self, q, kc16, vc16, mask, kv_len: int, scale: Optional[float] = None
+                         ) -> np.ndarray:
+        """As tree_attention, with the relation between the drafted tokens given as a 0/1
+        matrix mask [M, M] (row i: the drafted tokens that token i sees)."""
+        q = self._r(q)
+        kc, vc = _u16(kc16), _u16(vc16)
+        mk = np.ascontiguousarray(mask, dtype=np.uint8)
+        M, nh, d = q.shape
+        assert mk.shape == (M, M)
+        assert kc.shape[0] == nh and kc.shape[2] == d and kc.shape[1] >= kv_len + M
+        if scale is None:
+            scale = 1.0 / np.sqrt(d)
+        out = np.empty_like(q)
+        self.lib.orc_masked_attention(_p(out), _p(q), _p(kc), _p(vc), _p(mk), C.c_int(M),
+                                      C.c_int(kv_len), C.c_int(nh), C.c_int(d),
+                                      C.c_int64(kc.shape[1] * d), C.c_int64(d), self.creal(scale))
         return out
 
     # ---- layer / stack

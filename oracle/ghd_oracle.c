@@ -594,3 +594,59 @@ int orc_choose_width(const double *acc, int K, int R, const int32_t *widths,
     }
     return best;
 }
+
+/* ------------------------------------------- attention under a given mask -- */
+
+/* Eq. (1) under an arbitrary verification pattern (section 2.3 shows three:
+ * the token tree of multi-head drafting, the several sequences of a draft
+ * model, the n-gram pattern of Lookahead): mask[i*M + j] != 0 says that drafted
+ * token i is related to drafted token j; every drafted token sees the whole
+ * committed cache.  Same layout and arithmetic as orc_tree_attention, which is
+ * the special case mask = ancestor-or-self.  A row that sees no key at all
+ * (empty cache and an all-zero mask row) gives zeros. */
+void orc_masked_attention(real *out, const real *q, const uint16_t *kc, const uint16_t *vc,
+                          const uint8_t *mask, int M, int kv_len, int nh, int d,
+                          int64_t stride_head, int64_t stride_tok, real scale)
+{
+    int T = kv_len + M;
+    real *s = (real *)malloc((size_t)T * sizeof(real));
+    for (int h = 0; h < nh; ++h)
+        for (int i = 0; i < M; ++i) {
+            const real *qi = q + ((size_t)i * nh + h) * d;
+            real *oi = out + ((size_t)i * nh + h) * d;
+            real mx = -INFINITY;
+            int seen = 0;
+            for (int t = 0; t < T; ++t) {
+                if (t >= kv_len && !mask[(size_t)i * M + (t - kv_len)])
+                    continue;
+                const uint16_t *kt = kc + h * stride_head + t * stride_tok;
+                real dot = 0;
+                for (int c = 0; c < d; ++c)
+                    dot += qi[c] * widen(kt[c]);
+                s[t] = dot * scale;
+                if (s[t] > mx)
+                    mx = s[t];
+                ++seen;
+            }
+            for (int c = 0; c < d; ++c)
+                oi[c] = 0;
+            if (!seen)
+                continue;
+            real denom = 0;
+            for (int t = 0; t < T; ++t) {
+                if (t >= kv_len && !mask[(size_t)i * M + (t - kv_len)])
+                    continue;
+                s[t] = (real)exp((double)(s[t] - mx));
+                denom += s[t];
+            }
+            for (int t = 0; t < T; ++t) {
+                if (t >= kv_len && !mask[(size_t)i * M + (t - kv_len)])
+                    continue;
+                real p = s[t] / denom;
+                const uint16_t *vt = vc + h * stride_head + t * stride_tok;
+                for (int c = 0; c < d; ++c)
+                    oi[c] += p * widen(vt[c]);
+            }
+        }
+    free(s);
+}

@@ -78,6 +78,8 @@ def lib() -> C.CDLL:
             "ghd_tree_attention": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, i64, i64, f32,
                                                vp, sz, vp]),
             "ghd_attention_workspace_bytes": (sz, [i32, i32, i32, i32]),
+            "ghd_masked_attention": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, i64, i64, f32,
+                                                 vp, sz, vp]),
             "ghd_verify_layer": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]),
             "ghd_verify_stack": (C.c_int32, [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, sz,
                                              vp]),
@@ -106,6 +108,7 @@ EXPORTS = ["ghd_status_str", "ghd_last_hip_error", "ghd_tree_validate", "ghd_tre
            "ghd_tree_mask_workspace_bytes", "ghd_step_status",
            "ghd_packed_weight_bytes", "ghd_pack_weight", "ghd_linear_skinny",
            "ghd_linear_workspace_bytes", "ghd_tree_attention", "ghd_attention_workspace_bytes",
+           "ghd_masked_attention",
            "ghd_verify_layer", "ghd_verify_stack", "ghd_workspace_bytes", "ghd_accept_greedy",
            "ghd_accept_workspace_bytes", "ghd_commit_path", "ghd_embed", "ghd_tree_build",
            "ghd_choose_width",
@@ -212,6 +215,28 @@ def ghd_tree_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Te
                                     k_cache.stride(0), k_cache.stride(1), v_cache.stride(0),
                                     v_cache.stride(1), scale, _ptr(ws), ws.numel(),
                                     _stream()), "ghd_tree_attention")
+    return out
+
+
+def ghd_masked_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                         mask: torch.Tensor, kv_len: int, scale: Optional[float] = None,
+                         ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """As ghd_tree_attention with the relation between the drafted tokens given as int64
+    [M, 2] bit masks (bit j of row i: token i sees token j)."""
+    M, nh, d = q.shape
+    out = torch.empty_like(q)
+    if scale is None:
+        scale = 1.0 / (d ** 0.5)
+    if ws is None:
+        ws = workspace(lib().ghd_attention_workspace_bytes(M, kv_len, nh, d), q.device)
+    assert mask.shape == (M, 2)
+    _check(lib().ghd_masked_attention(_ptr(out), _ptr(_dev(q, torch.float16)),
+                                      _ptr(_dev(k_cache, torch.float16)),
+                                      _ptr(_dev(v_cache, torch.float16)),
+                                      _ptr(_dev(mask, torch.int64)), M, kv_len, nh, d,
+                                      k_cache.stride(0), k_cache.stride(1), v_cache.stride(0),
+                                      v_cache.stride(1), scale, _ptr(ws), ws.numel(),
+                                      _stream()), "ghd_masked_attention")
     return out
 
 

@@ -371,13 +371,16 @@ size_t ghd_attention_workspace_bytes(int M, int kv_len, int nh, int d)
     return carve(nullptr, 2, M, 0, 0, d).bytes;
 }
 
-ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, const void* v_cache,
-                              const int32_t* parent_dev, int M, int kv_len, int nh, int d,
-                              int64_t k_stride_head, int64_t k_stride_tok, int64_t v_stride_head,
-                              int64_t v_stride_ch, float scale, void* ws, size_t ws_bytes,
-                              void* stream)
+// the visibility of the tree rows comes either from parent[] (masks built by the set-up
+// kernel) or from the caller's masks
+static ghd_status attention_call(void* out, const void* q, const void* k_cache, const void* v_cache,
+                                 const int32_t* parent_dev, const uint64_t* mask_dev, int M, int kv_len,
+                                 int nh, int d, int64_t k_stride_head, int64_t k_stride_tok,
+                                 int64_t v_stride_head, int64_t v_stride_ch, float scale, void* ws,
+                                 size_t ws_bytes, void* stream)
 {
-    if (!out || !q || !k_cache || !v_cache || !parent_dev) return GHD_ERR_NULL;
+    if (!out || !q || !k_cache || !v_cache || (!parent_dev && !mask_dev)) return GHD_ERR_NULL;
+    if (mask_dev && ((uintptr_t)mask_dev & 7) != 0) return GHD_ERR_ALIGN;
     if (M < 1 || M > GHD_MAX_M || kv_len < 0 || nh < 1 || nh > 256 || (d != 64 && d != 128))
         return GHD_ERR_SHAPE;
     if (k_stride_tok < d || k_stride_head < 0 || v_stride_head < 0) return GHD_ERR_SHAPE;
@@ -414,12 +417,34 @@ ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, con
     a.sync = w.sync;
     a.o_part = w.o_part;
     a.ml_part = w.ml_part;
-    a.mask = w.mask;
+    a.mask = mask_dev ? mask_dev : w.mask;
     a.att_q = (const half_t*)q;
     a.att_k = (const half_t*)k_cache;
     a.att_v = (const half_t*)v_cache;
     a.att_out = (half_t*)out;
     return timed_fused(a, st);
+}
+
+ghd_status ghd_tree_attention(void* out, const void* q, const void* k_cache, const void* v_cache,
+                              const int32_t* parent_dev, int M, int kv_len, int nh, int d,
+                              int64_t k_stride_head, int64_t k_stride_tok, int64_t v_stride_head,
+                              int64_t v_stride_ch, float scale, void* ws, size_t ws_bytes,
+                              void* stream)
+{
+    if (!parent_dev) return GHD_ERR_NULL;
+    return attention_call(out, q, k_cache, v_cache, parent_dev, nullptr, M, kv_len, nh, d, k_stride_head,
+                          k_stride_tok, v_stride_head, v_stride_ch, scale, ws, ws_bytes, stream);
+}
+
+ghd_status ghd_masked_attention(void* out, const void* q, const void* k_cache, const void* v_cache,
+                                const uint64_t* mask_dev, int M, int kv_len, int nh, int d,
+                                int64_t k_stride_head, int64_t k_stride_tok, int64_t v_stride_head,
+                                int64_t v_stride_ch, float scale, void* ws, size_t ws_bytes,
+                                void* stream)
+{
+    if (!mask_dev) return GHD_ERR_NULL;
+    return attention_call(out, q, k_cache, v_cache, nullptr, mask_dev, M, kv_len, nh, d, k_stride_head,
+                          k_stride_tok, v_stride_head, v_stride_ch, scale, ws, ws_bytes, stream);
 }
 
 size_t ghd_workspace_bytes(const ghd_model_cfg* cfg, int M, int kv_len)

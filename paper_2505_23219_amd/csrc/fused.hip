@@ -607,6 +607,9 @@ __device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const ha
         wave_active = wave_active || (mt * 16 < M);
         alo[t] = mok[t] ? a.mask[2 * mrow[t]] : 0;
         ahi[t] = mok[t] ? a.mask[2 * mrow[t] + 1] : 0;
+        // bits from M on name no row of the tree (a caller's mask may have them set)
+        if (M < 64) alo[t] &= (1ull << M) - 1;
+        if (M < 128) ahi[t] &= (M <= 64) ? 0ull : (1ull << (M - 64)) - 1;
     }
     // K piece id -> (row id / CPR, 8 channels id % CPR); V^T piece id -> (channel id / 8,
     // 8 keys id % 8).  Offsets inside a head fit 32 bits (checked on the host).
@@ -923,7 +926,9 @@ __device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const ha
             }
 #pragma unroll
             for (int e = 0; e < D / 64; ++e)
-                out[((size_t)m * nh + head) * D + e * 64 + lane] = (half_t)(num[e] / den);
+                // a row that sees no key at all (possible with a caller's mask and an empty
+                // cache) gets zeros
+                out[((size_t)m * nh + head) * D + e * 64 + lane] = (half_t)(den > 0.f ? num[e] / den : 0.f);
         }
         // a workgroup that goes on to another head reuses its partial-state slot: wait until
         // the other parts have read it

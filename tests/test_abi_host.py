@@ -308,3 +308,20 @@ def test_choose_width_equals_the_oracle(lib, orc32):
     assert lib.ghd_choose_width(cast(a), 1, 1, cast(w), cast(t), 1, None) == B.GHD_ERR_SHAPE
     w[0], t[0] = 4, 0.0
     assert lib.ghd_choose_width(cast(a), 1, 1, cast(w), cast(t), 1, None) == B.GHD_ERR_SHAPE
+
+
+def test_masked_attention_rejects_bad_arguments(lib):
+    def call(**kw):
+        a = dict(out=FAKE, q=FAKE, k=FAKE, v=FAKE, mask=FAKE, M=8, kv_len=64, nh=2, d=128, ksh=128 * 128,
+                 kst=128, vsh=128 * 128, vsc=128, scale=0.1, ws=FAKE, ws_bytes=1 << 30)
+        a.update(kw)
+        return lib.ghd_masked_attention(a["out"], a["q"], a["k"], a["v"], a["mask"], a["M"], a["kv_len"],
+                                        a["nh"], a["d"], a["ksh"], a["kst"], a["vsh"], a["vsc"], a["scale"],
+                                        a["ws"], a["ws_bytes"], None)
+
+    assert call(mask=None) == B.GHD_ERR_NULL
+    assert call(mask=FAKE + 4) == B.GHD_ERR_ALIGN
+    assert call(M=129) == B.GHD_ERR_SHAPE
+    assert call(d=96) == B.GHD_ERR_SHAPE
+    assert call(vsc=64) == B.GHD_ERR_CAPACITY
+    assert call(ws=None) == B.GHD_ERR_WORKSPACE

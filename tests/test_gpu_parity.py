@@ -517,3 +517,68 @@ def test_verify_layer_7b_shape_tree_sizes(B, model, orc32, M, tree):
     say("layer 7b sweep", M, tree)
     shape = wl.with_layers(wl.LLAMA_7B, 1)
     run_layer_case(B, model, orc32, shape, M, 2048, make_tree(tree, M), 3)
+
+
+# ---- attention under a caller's mask (the other verification patterns of section 2.3) -----------
+def mask_words(mask, extra_bits=False):
+    """0/1 matrix [M, M] -> int64 [M, 2] bit masks (bit j of row i: token i sees token j);
+    with extra_bits every bit from M on is set as well (must be ignored)."""
+    M = mask.shape[0]
+    words = np.zeros((M, 2), dtype=np.uint64)
+    for i in range(M):
+        for j in range(128):
+            if (j < M and mask[i, j]) or (j >= M and extra_bits):
+                words[i, j // 64] |= np.uint64(1) << np.uint64(j % 64)
+    return torch.from_numpy(words.view(np.int64))
+
+
+def pattern(kind, M, seed):
+    rng = np.random.default_rng(seed)
+    if kind == "random":                 # any relation, self included
+        m = rng.random((M, M)) < 0.3
+        m[np.arange(M), np.arange(M)] = True
+    elif kind == "sequences":            # draft-model style: independent sequences side by side
+        m = np.zeros((M, M), bool)
+        L = 8
+        for i in range(M):
+            m[i, (i // L) * L:i + 1] = True
+    elif kind == "ngram":                # Lookahead style: a causal window plus a few n-gram rows
+        m = np.zeros((M, M), bool)
+        for i in range(M):
+            m[i, max(0, i - 5):i + 1] = True
+            m[i, 0] = True
+    else:                                # "sparse": most rows see only themselves
+        m = np.eye(M, dtype=bool)
+        m[::7, :3] = True
+    return m.astype(np.uint8)
+
+
+@pytest.mark.parametrize("M,nh,d,kv_len,kind,extra", [
+    (40, 3, 128, 333, "random", False), (64, 4, 128, 1000, "sequences", True), (64, 2, 64, 70, "ngram", False),
+    (128, 2, 128, 257, "random", False), (100, 2, 64, 0, "sparse", True), (16, 2, 128, 2048, "random", True),
+    (1, 2, 128, 5, "random", True)])
+def test_masked_attention(B, model, orc32, M, nh, d, kv_len, kind, extra):
+    say("masked attention", M, nh, d, kv_len, kind)
+    mask = pattern(kind, M, 13)
+    q, kc, vc = attention_case(M, nh, d, kv_len, wl.tree_chain(M), 43)
+    ref = orc32.masked_attention(q.numpy().astype(np.float32), kc.numpy(), vc.numpy(), mask, kv_len)
+    ws = B.workspace(B.lib().ghd_attention_workspace_bytes(M, kv_len, nh, d))
+    got = B.ghd_masked_attention(q.cuda(), *model.upload_cache(kc, vc), mask_words(mask, extra).cuda(),
+                                 kv_len, ws=ws)
+    assert B.ghd_step_status(ws) == 0
+    ok, ma, mr = close(got.cpu().numpy(), ref, 5e-3, 5e-3)
+    assert ok, (ma, mr)
+
+
+def test_masked_attention_rows_without_keys_give_zeros(B, model, orc32):
+    M, nh, d = 70, 2, 128
+    mask = pattern("random", M, 5)
+    mask[[3, 64, 69]] = 0
+    say("masked attention, empty rows")
+    q, kc, vc = attention_case(M, nh, d, 0, wl.tree_chain(M), 44)
+    ref = orc32.masked_attention(q.numpy().astype(np.float32), kc.numpy(), vc.numpy(), mask, 0)
+    got = B.ghd_masked_attention(q.cuda(), *model.upload_cache(kc, vc), mask_words(mask).cuda(), 0)
+    got = got.cpu().numpy()
+    assert np.all(got[[3, 64, 69]] == 0)
+    ok, ma, mr = close(got, ref, 5e-3, 5e-3)
+    assert ok, (ma, mr)

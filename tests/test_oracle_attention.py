@@ -200,3 +200,60 @@ def test_strided_cache_capacity_is_respected(orc64):
     vc[:, kv_len + M:] = np.float16(-100.0)
     b = orc64.tree_attention(q, kc, vc, parent, kv_len)
     assert np.array_equal(a, b)
+
+
+# ---- attention under a given mask (the other verification patterns of section 2.3) -------------
+def random_mask(M, seed, density=0.4):
+    rng = np.random.default_rng(seed)
+    m = rng.random((M, M)) < density
+    m[np.arange(M), np.arange(M)] = True
+    return m.astype(np.uint8)
+
+
+def draft_model_mask(n_seq, length):
+    """Several drafted sequences verified side by side: a token sees the earlier tokens of
+    its own sequence and itself."""
+    M = n_seq * length
+    m = np.zeros((M, M), np.uint8)
+    for s in range(n_seq):
+        for a in range(length):
+            m[s * length + a, s * length:s * length + a + 1] = 1
+    return m
+
+
+def test_masked_attention_with_the_tree_mask_is_tree_attention(orc32):
+    M, nh, d, kv_len = 21, 2, 16, 30
+    parent = wl.tree_random(M, 4, 6)
+    q, kc, vc = make_case(M, nh, d, kv_len, 6)
+    got = orc32.masked_attention(q, kc, vc, orc32.tree_mask(parent), kv_len)
+    assert np.array_equal(got, orc32.tree_attention(q, kc, vc, parent, kv_len))
+
+
+@pytest.mark.parametrize("kind,kv_len", [("random", 17), ("random", 0), ("sequences", 40), ("full", 5)])
+def test_masked_attention_matches_torch_sdpa(orc64, kind, kv_len):
+    M, nh, d = 12, 2, 32
+    mask = {"random": random_mask(M, 3), "sequences": draft_model_mask(3, 4),
+            "full": np.ones((M, M), np.uint8)}[kind]
+    q, kc, vc = make_case(M, nh, d, kv_len, 11)
+    T = kv_len + M
+    vis = torch.from_numpy(np.concatenate([np.ones((M, kv_len), bool), mask.astype(bool)], 1))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q).permute(1, 0, 2), torch.from_numpy(kc[:, :T].astype(np.float64)),
+        torch.from_numpy(vc[:, :T].astype(np.float64)), attn_mask=vis)
+    got = orc64.masked_attention(q, kc, vc, mask, kv_len)
+    np.testing.assert_allclose(got, ref.permute(1, 0, 2).numpy(), atol=1e-12)
+    np.testing.assert_allclose(got, dense_masked_attention(q, kc, vc, vis.numpy(), 1 / np.sqrt(d)), atol=1e-12)
+
+
+def test_masked_attention_row_without_keys_gives_zeros(orc32):
+    M, nh, d = 5, 2, 16
+    mask = random_mask(M, 1)
+    mask[3] = 0
+    q, kc, vc = make_case(M, nh, d, 0, 2)
+    got = orc32.masked_attention(q, kc, vc, mask, 0)
+    assert np.all(got[3] == 0) and np.all(np.isfinite(got))
+    # one visible key: the output is that key's value row
+    mask[2] = 0
+    mask[2, 4] = 1
+    got = orc32.masked_attention(q, kc, vc, mask, 0)
+    assert np.allclose(got[2], vc[:, 4].astype(np.float32), atol=1e-6)
