@@ -295,16 +295,18 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
         wb[s][0] = __builtin_nontemporal_load(p);
         wb[s][1] = __builtin_nontemporal_load(p + 64);
     };
-    // ---- x staging: piece p -> fragment f = p/64 (k-step s = f/MT, row tile f%MT),
-    //      row (p/4)%16, k group p%4
+    // ---- x staging: the chunk of a row is KS * 4 pieces of 16 bytes, contiguous in memory;
+    //      piece p -> row p / (KS*4), piece kp = p % (KS*4) of it (k-step s = kp / 4, k group
+    //      kp % 4): a wavefront's 64 pieces are whole 128-byte lines of a few rows
     int p_row[PPT], p_koff[PPT], p_dst[PPT];
     bool p_ok[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
         int p = tid + i * kFT;
-        int f = p >> 6, pc = (p >> 2) & 15, pg = p & 3;
-        int s = f / MT, mt = f % MT;
-        int m = mt * 16 + pc;
+        int m = p / (KS * 4), kp = p % (KS * 4);
+        int s = kp >> 2, pg = kp & 3;
+        int mt = m >> 4, pc = m & 15;
+        int f = s * MT + mt;
         p_ok[i] = (p < PIECES) && (m < a.M);
         p_row[i] = min(m, a.M - 1);
         p_koff[i] = s * 32 + pg * 8;
