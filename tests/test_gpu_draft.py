@@ -209,3 +209,48 @@ def test_spec_steps_with_planted_drafts_accept_them(B, model, orc32):
         kv += int(r[0])
         tok = int(r[1])
     assert got == want[:len(got)]
+
+
+def test_spec_step_7b_shape(B, model, orc32):
+    """One whole step at 7B layer shapes in the benchmark's configuration (64-node tree, 2048
+    cached tokens, 5 heads x 10 candidates, vocabulary 32000), two layers deep.  Candidate
+    positions whose oracle logit is within 1e-3 of a neighbour's in the sorted order may come
+    out either way; every other decision must agree."""
+    shape = wl.with_layers(wl.LLAMA_7B, 2)
+    K, R, M, kv_len, seed = 5, 10, 64, 2048, 6
+    cap = 2176
+    lp = Loop(B, model, shape, K, R, M, kv_len, cap, seed)
+    parent, rank, _ = orc32.tree_build(wl.head_accuracies(K, R), M)
+    tokens = wl.draft_tokens(M, shape.V, seed)
+    st = orc32.spec_step(shape, lp.np_layers, lp.kcs, lp.vcs, lp.np_head, lp.table.numpy(), tokens,
+                         parent, kv_len, True)
+    ref_tokens, ref_topk, ref_hl = orc32.draft(st["x_last"], lp.np_head["g_final"], lp.Wheads.numpy(), K, R,
+                                               shape.rms_eps, parent, rank, st["next_token"], True)
+    top2 = np.sort(st["logits"], axis=1)[:, -2:]
+    assert ((top2[:, 1] - top2[:, 0]) > 1e-3).all(), "pick another seed: argmax near tie"
+    top = -np.sort(-ref_hl, axis=1)[:, :R + 1]
+    gaps = top[:, :-1] - top[:, 1:]                                  # gap below position r
+    clear = np.ones((K, R), bool)
+    clear[:, :] &= gaps > 1e-3                                       # well above the next one
+    clear[:, 1:] &= gaps[:, :-1] > 1e-3                              # and well below the previous one
+    assert clear.mean() > 0.9
+    say("spec step at 7B layer shapes")
+    pd, rd = torch.from_numpy(parent).cuda(), torch.from_numpy(rank).cuda()
+    td = torch.from_numpy(tokens).cuda()
+    res = torch.zeros(2 + M, dtype=torch.int32, device="cuda")
+    ws = B.workspace(lp.spec.workspace_bytes(M, kv_len))
+    B.ghd_spec_step(lp.spec, pd, rd, kv_len, td, res, ws)
+    r = res.cpu().numpy()
+    assert r[0] == st["n"] and r[1] == st["next_token"] and np.array_equal(r[2:2 + r[0]], st["path"])
+    got = td.cpu().numpy()
+    depth = orc32.tree_depth(parent)
+    assert got[0] == ref_tokens[0]
+    checked = 0
+    for i in range(1, M):
+        if clear[depth[i] - 1, rank[i]]:
+            assert got[i] == ref_tokens[i], i
+            checked += 1
+        else:                                                        # a near tie: one of the tied candidates
+            v = ref_hl[depth[i] - 1]
+            assert abs(v[got[i]] - v[ref_tokens[i]]) <= 2e-3, i
+    assert checked >= 0.8 * (M - 1)
