@@ -122,11 +122,12 @@ def step_spread(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, 
     return {"median_us": round(pick(0.5), 1), "p10_us": round(pick(0.1), 1), "p90_us": round(pick(0.9), 1)}
 
 
-def recorded_traffic():
+def recorded_traffic(workload):
     """HBM bytes per launch of the linear-layer kernel from the committed counter
     summary (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known
-    size); None when the kernel sources have changed since."""
-    path = os.path.join(ROOT, "profiles", "k_linear_stack7b_hbm_traffic.md")
+    size); None when the kernel sources have changed since, or for a workload the
+    counters were not taken on."""
+    path = os.path.join(ROOT, "profiles", "k_linear_%s_hbm_traffic.md" % workload)
     if not os.path.exists(path):
         return None
     from paper_2505_23219_amd.profile_summary import source_digest
@@ -176,7 +177,7 @@ def linear_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w
     kv_bytes = 2 * 2 * s.L * s.nh * s.d * (kv_len + w.M)
     return {"bound": "hbm", "kernel": "k_linear<MT, RS>", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": recorded_traffic(), "launches_per_step": per_step,
+            "traffic": recorded_traffic(w.name), "launches_per_step": per_step,
             "avg_launch_us": round(avg_ms * 1e3, 2),
             "algorithmic_bytes_per_launch": int(per_launch_bytes),
             "attention": {"kernel": "k_attention<MT, D>", "launches_per_step": att_n // steps,
