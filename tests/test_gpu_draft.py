@@ -36,7 +36,8 @@ def clear_candidates(ref_logits, R, gap=1e-3):
 
 
 @pytest.mark.parametrize("H,V,K,R,M,seed", [(256, 1000, 3, 4, 8, 0), (512, 3000, 5, 10, 64, 5),
-                                            (4096, 32000, 2, 8, 16, 2)])
+                                            (4096, 32000, 2, 8, 16, 2), (512, 3000, 5, 10, 128, 9),
+                                            (256, 1000, 4, 6, 100, 3)])
 def test_draft_tokens(B, orc32, H, V, K, R, M, seed):
     shape = wl.ModelShape("d%d" % H, H=H, nh=H // 128 if H >= 128 else 1, d=128, F=8, V=V, L=1)
     Wheads = wl.drafting_heads(shape, K, seed)
