@@ -609,9 +609,8 @@ __device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const ha
         wave_active = wave_active || (mt * 16 < M);
         alo[t] = mok[t] ? a.mask[2 * mrow[t]] : 0;
         ahi[t] = mok[t] ? a.mask[2 * mrow[t] + 1] : 0;
-        // bits from M on name no row of the tree (a caller's mask may have them set)
-        if (M < 64) alo[t] &= (1ull << M) - 1;
-        if (M < 128) ahi[t] &= (M <= 64) ? 0ull : (1ull << (M - 64)) - 1;
+        // (bits from M on, which a caller's mask may have set, are never looked at: a mask bit
+        // is only consulted for keys kv_len <= key < kv_len + M)
     }
     // K piece id -> (row id / CPR, 8 channels id % CPR); V^T piece id -> (channel id / 8,
     // 8 keys id % 8).  Offsets inside a head fit 32 bits (checked on the host).
@@ -944,6 +943,20 @@ __device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const ha
 // Workgroups are dealt round-robin to the 8 XCDs; neighbours in the work sequence (which
 // share row groups, or heads, and exchange partial results) get the same XCD.  The
 // exchange relies on workgroup i running on XCD i % 8, which is checked here.
+// The argument block is a few 64-byte lines of kernel-argument memory, which the compiler
+// reads field by field as the code needs them, one memory round trip after the other.  One
+// word of every line is requested here, back to back at the start of the kernel, so that
+// the lines arrive together and the later reads find them in the scalar cache.
+__device__ __forceinline__ uint32_t touch_kernel_arguments()
+{
+    typedef const __attribute__((address_space(4))) uint32_t* kernarg_words;
+    kernarg_words kp = (kernarg_words)__builtin_amdgcn_kernarg_segment_ptr();
+    uint32_t t = 0;
+#pragma unroll
+    for (int i = 0; i < (int)((sizeof(FusedArgs) + 63) / 64); ++i) t ^= kp[i * 16];
+    return t;
+}
+
 __device__ __forceinline__ Ctx make_ctx(const FusedArgs& a, char* lds)
 {
     Ctx cx;
@@ -962,6 +975,7 @@ template <int MT, int RS>
 __global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t touched = touch_kernel_arguments();
     Ctx cx = make_ctx(a, lds);
     GemmOp op;
     op.W = a.lin_W;
@@ -982,14 +996,19 @@ __global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
     op.ngroups = ((op.N + kGroupRows - 1) / kGroupRows) * RS;
     op.ncpg = (op.K + kChunkCols * RS - 1) / (kChunkCols * RS);
     gemm_phase<MT, RS>(a, op, cx);
+    // (keeps the early reads alive; never true: lin_N is positive)
+    if (touched == 0x9e3779b9u && a.lin_N < 0) a.sync[kSyncStatus] = 4u;
 }
 
 template <int MT, int D>
 __global__ __launch_bounds__(kFT) void k_attention(const FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t touched = touch_kernel_arguments();
     Ctx cx = make_ctx(a, lds);
     attn_phase<MT, D>(a, cx, a.att_q, a.att_k, a.att_v, a.att_out, a.att_epoch);
+    // (keeps the early reads alive; never true: nh is positive)
+    if (touched == 0x9e3779b9u && a.nh < 0) a.sync[kSyncStatus] = 4u;
 }
 
 // ---------------------------------------------------------------------------
