@@ -759,6 +759,18 @@ ghd_status ghd_spec_step(const ghd_spec_model* m, const int32_t* parent_dev, con
  * synchronising the stream, ghd_debug_profile_read returns the number of launches and
  * their summed duration in milliseconds.  ghd_debug_copy is a plain copy kernel of known
  * traffic (bytes read + bytes written) used to calibrate the profiler's byte counters. */
+/* Test support (not part of the documented ABI): the kernels' work-share arithmetic on the
+ * host; see share_on_host. */
+void ghd_debug_share(int items, int per_item, int j, int G, int item, int* out5)
+{
+    share_on_host(items, per_item, j, G, item, out5);
+}
+
+void ghd_debug_attn_share(int nh, int ntile, int j, int G, int head, int* out6)
+{
+    attn_share_on_host(nh, ntile, j, G, head, out6);
+}
+
 void ghd_debug_profile(int what)
 {
     g_prof_mode = what == 1 ? MODE_LINEAR : what == 2 ? MODE_ATTN : -1;

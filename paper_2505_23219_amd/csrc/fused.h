@@ -71,6 +71,8 @@ struct FusedArgs {
 
 ghd_status launch_fused(const FusedArgs& a, hipStream_t st);
 int fused_grid_size();
+void share_on_host(int items, int per_item, int j, int G, int item, int* out);
+void attn_share_on_host(int nh, int ntile, int j, int G, int head, int* out);
 
 // setup kernel: zero the sync block, tree tables, and (optionally) the residual stream
 // with its sums of squares and its gain-scaled fp16 image

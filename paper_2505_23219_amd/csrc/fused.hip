@@ -91,19 +91,19 @@ struct Share {
     int c0, c1;   // this workgroup's range of global unit indices (empty if c0 == c1)
     int per_item;
     // local (within-XCD) unit index where workgroup wg's range begins
-    __device__ int lbegin(int wg) const { return (int)((unsigned)U * (unsigned)(wg - wg0) / (unsigned)Ge); }
-    __device__ int owner_local(int lunit) const
+    __host__ __device__ int lbegin(int wg) const { return (int)((unsigned)U * (unsigned)(wg - wg0) / (unsigned)Ge); }
+    __host__ __device__ int owner_local(int lunit) const
     {
         return wg0 + (int)(((unsigned)(lunit + 1) * (unsigned)Ge - 1u) / (unsigned)U);
     }
-    __device__ int litem0(int item) const { return item * per_item - base; }
-    __device__ int first_of(int item) const { return owner_local(litem0(item)); }
-    __device__ int last_of(int item) const { return owner_local(litem0(item) + per_item - 1); }
+    __host__ __device__ int litem0(int item) const { return item * per_item - base; }
+    __host__ __device__ int first_of(int item) const { return owner_local(litem0(item)); }
+    __host__ __device__ int last_of(int item) const { return owner_local(litem0(item) + per_item - 1); }
     // does workgroup wg's range begin inside `item` (and not in an earlier one)?
-    __device__ bool begins_in(int wg, int item) const { return lbegin(wg) >= litem0(item); }
+    __host__ __device__ bool begins_in(int wg, int item) const { return lbegin(wg) >= litem0(item); }
 };
 
-__device__ __forceinline__ Share make_share(int items, int per_item, int j, int G)
+__host__ __device__ __forceinline__ Share make_share(int items, int per_item, int j, int G)
 {
     const int nx = (G % 8 == 0) ? 8 : 1;
     const int Gx = G / nx, x = j / Gx;
@@ -537,6 +537,63 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
 // ---------------------------------------------------------------------------
 // tree attention
 // ---------------------------------------------------------------------------
+// Work shares of the attention (see attn_phase): which heads workgroup j works on, and for
+// one of them which workgroups share it and which key tiles are this workgroup's.
+struct AttnHeads {
+    int Gx, x, w;      // workgroups per XCD, this workgroup's XCD and its index inside it
+    int hx0, Hx;       // first head and number of heads of the XCD
+    int h_lo, h_hi;    // this workgroup's heads, local to the XCD (empty if h_lo == h_hi)
+};
+
+__host__ __device__ __forceinline__ AttnHeads attn_heads(int nh, int j, int G)
+{
+    AttnHeads s;
+    const int nx = (G % 8 == 0) ? 8 : 1;
+    s.Gx = G / nx;
+    s.x = j / s.Gx;
+    s.w = j - s.x * s.Gx;
+    s.hx0 = nh * s.x / nx;
+    s.Hx = nh * (s.x + 1) / nx - s.hx0;
+    s.h_lo = s.h_hi = 0;
+    if (s.Hx == 0) return s;
+    if (s.Hx >= s.Gx) {
+        s.h_lo = s.Hx * s.w / s.Gx;
+        s.h_hi = s.Hx * (s.w + 1) / s.Gx;
+    } else {
+        s.h_lo = ((s.w + 1) * s.Hx - 1) / s.Gx;    // the head whose run of workgroups contains w
+        s.h_hi = s.h_lo + 1;
+    }
+    return s;
+}
+
+struct AttnTiles {
+    int first, np, me;   // the head's parts are workgroups first .. first + np - 1; this one is part `me`
+    int t0, t1;          // its key tiles (empty, with me >= np, when there are more workgroups than tiles)
+};
+
+__host__ __device__ __forceinline__ AttnTiles attn_tiles(const AttnHeads& s, int hl, int ntile)
+{
+    AttnTiles t;
+    t.first = s.x * s.Gx + s.w;
+    t.np = 1;
+    t.me = 0;
+    if (s.Hx < s.Gx) {
+        int wl0 = s.Gx * hl / s.Hx;                        // head hl's run of local workgroups
+        int wl1 = s.Gx * (hl + 1) / s.Hx;
+        t.first = s.x * s.Gx + wl0;
+        t.np = (wl1 - wl0 < ntile) ? wl1 - wl0 : ntile;
+        t.me = s.w - wl0;
+    }
+    // boundaries rounded up: when the tiles do not divide evenly the longer ranges come first,
+    // and the last workgroup, whose range ends with the (costlier) tree tile, gets a shorter one
+    t.t0 = t.t1 = 0;
+    if (t.me < t.np) {
+        t.t0 = (ntile * t.me + t.np - 1) / t.np;
+        t.t1 = (ntile * (t.me + 1) + t.np - 1) / t.np;
+    }
+    return t;
+}
+
 // 2^x for x <= 0 (softmax weights): the hardware instruction; results below the smallest
 // normal number flush to zero, which is what a weight that small should be.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -583,18 +640,8 @@ __device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const ha
     // tiles; otherwise every workgroup takes whole heads.  A head is therefore always
     // finished inside one XCD (partial states go through that XCD's L2), and the tile loop
     // of a head has no head change in it.
-    const int nx = (cx.G % 8 == 0) ? 8 : 1;
-    const int Gx = cx.G / nx, x = cx.j / Gx, w = cx.j - x * Gx;
-    const int hx0 = nh * x / nx, Hx = nh * (x + 1) / nx - hx0;
-    if (Hx == 0) return;
-    int h_lo, h_hi;          // this workgroup's heads (local to the XCD)
-    if (Hx >= Gx) {
-        h_lo = Hx * w / Gx;
-        h_hi = Hx * (w + 1) / Gx;
-    } else {
-        h_lo = ((w + 1) * Hx - 1) / Gx;    // the head whose run of workgroups contains w
-        h_hi = h_lo + 1;
-    }
+    const AttnHeads hs = attn_heads(nh, cx.j, cx.G);
+    const int hx0 = hs.hx0, h_lo = hs.h_lo, h_hi = hs.h_hi;
 
     // per-wave query rows
     int mrow[MTW];
@@ -631,19 +678,9 @@ __device__ __forceinline__ void attn_phase(const FusedArgs& a, Ctx& cx, const ha
     for (int hl = h_lo; hl < h_hi; ++hl) {
         const int head = hx0 + hl;
         // the workgroups first .. first + np - 1 split this head's tiles
-        int first = x * Gx + w, np = 1, me = 0;
-        if (Hx < Gx) {
-            int wl0 = Gx * hl / Hx;                        // head hl's run of local workgroups
-            int wl1 = Gx * (hl + 1) / Hx;
-            first = x * Gx + wl0;
-            np = min(wl1 - wl0, ntile);
-            me = w - wl0;
-        }
+        const AttnTiles ts = attn_tiles(hs, hl, ntile);
+        const int first = ts.first, np = ts.np, me = ts.me, t0 = ts.t0, t1 = ts.t1;
         if (me >= np) continue;                            // more workgroups than tiles
-        // boundaries rounded up: when the tiles do not divide evenly the longer ranges come
-        // first, and the last workgroup, whose range ends with the (costlier) tree tile, gets
-        // a shorter one
-        const int t0 = (ntile * me + np - 1) / np, t1 = (ntile * (me + 1) + np - 1) / np;
         const half_t* kh_ = kc + (size_t)head * a.stride_head;
         const half_t* vh_ = vc + (size_t)head * a.v_stride_head;
 
@@ -1102,6 +1139,42 @@ ghd_status launch_fused(const FusedArgs& a, hipStream_t st)
         return launch_linear_rs<8>(a, st);
     }
     return a.d == 64 ? launch_attention_d<64>(a, mt, st) : launch_attention_d<128>(a, mt, st);
+}
+
+// The work-share arithmetic evaluated on the host (for tests of its invariants): the unit
+// range of workgroup j, and for `item` its first and last part and whether j's range begins
+// in it.  out[0..4] = c0, c1, first_of(item), last_of(item), begins_in(j, item).
+void share_on_host(int items, int per_item, int j, int G, int item, int* out)
+{
+    const Share sh = make_share(items, per_item, j, G);
+    out[0] = sh.c0;
+    out[1] = sh.c1;
+    out[2] = out[3] = out[4] = -1;
+    // only items of j's XCD can be asked about
+    if (sh.U > 0 && item * per_item >= sh.base && item * per_item < sh.base + sh.U) {
+        out[2] = sh.first_of(item);
+        out[3] = sh.last_of(item);
+        out[4] = sh.begins_in(j, item) ? 1 : 0;
+    }
+}
+
+// The attention's work shares on the host: for workgroup j and head `head`,
+// out[0..5] = first part, number of parts, this part's index, t0, t1, and whether `head` is
+// one of j's heads at all (otherwise the first five are -1).
+void attn_share_on_host(int nh, int ntile, int j, int G, int head, int* out)
+{
+    const AttnHeads hs = attn_heads(nh, j, G);
+    for (int i = 0; i < 6; ++i) out[i] = -1;
+    out[5] = 0;
+    const int hl = head - hs.hx0;
+    if (hl < hs.h_lo || hl >= hs.h_hi) return;
+    const AttnTiles ts = attn_tiles(hs, hl, ntile);
+    out[0] = ts.first;
+    out[1] = ts.np;
+    out[2] = ts.me;
+    out[3] = ts.t0;
+    out[4] = ts.t1;
+    out[5] = 1;
 }
 
 // ---- setup kernel ------------------------------------------------------------
