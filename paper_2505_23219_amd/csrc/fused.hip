@@ -1197,21 +1197,39 @@ __global__ __launch_bounds__(256) void k_fused_setup(uint32_t* __restrict__ sync
 {
     int tid = threadIdx.x;
     if (blockIdx.x < kTreeBlocks) {
-        __shared__ int32_t s_parent[GHD_MAX_M];
+        // Ancestor sets and depths by pointer doubling: after round k a node knows its 2^k
+        // nearest ancestors-or-self, how many edges lead to the farthest of them, and the
+        // node 2^k edges up (-1 past the root).  ceil(log2 M) rounds whatever the depth; a
+        // parent that is not an earlier node is taken as "no parent".
+        __shared__ int32_t s_up[GHD_MAX_M];
         __shared__ int32_t s_depth[GHD_MAX_M];
+        __shared__ uint64_t s_lo[GHD_MAX_M], s_hi[GHD_MAX_M];
         if (!parent) return;
-        if (tid < M) s_parent[tid] = parent[tid];
-        __syncthreads();
+        int up = -1, dep = 0;
+        uint64_t lo = 0, hi = 0;
         if (tid < M) {
-            uint64_t lo = 0, hi = 0;
-            int dep = 0, j = tid;
-            for (int step = 0; step < M; ++step) {
-                if (j < 64) lo |= 1ull << j; else hi |= 1ull << (j - 64);
-                int p = s_parent[j];
-                if (p < 0 || p >= j) break;
-                j = p;
-                ++dep;
+            up = parent[tid];
+            if (up < 0 || up >= tid) up = -1;
+            dep = up >= 0 ? 1 : 0;
+            if (tid < 64) lo = 1ull << tid; else hi = 1ull << (tid - 64);
+        }
+        for (int span = 1; span < M; span <<= 1) {
+            if (tid < M) {
+                s_up[tid] = up;
+                s_depth[tid] = dep;
+                s_lo[tid] = lo;
+                s_hi[tid] = hi;
             }
+            __syncthreads();
+            if (tid < M && up >= 0) {
+                lo |= s_lo[up];
+                hi |= s_hi[up];
+                dep += s_depth[up];
+                up = s_up[up];
+            }
+            __syncthreads();
+        }
+        if (tid < M) {
             s_depth[tid] = dep;
             if (blockIdx.x == 0) {
                 mask[2 * tid] = lo;
