@@ -1051,18 +1051,28 @@ __global__ __launch_bounds__(kFT) void k_attention(const FusedArgs a)
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-static int g_num_cu = 0;
+// What is cached about a device (its compute units, which kernels have had their LDS size
+// set on it) is kept per device: the current device of the calling thread decides.
+constexpr int kMaxDevices = 64;
+static int g_num_cu[kMaxDevices] = {};
+
+static int current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    return dev;
+}
 
 int fused_grid_size()
 {
-    if (g_num_cu == 0) {
-        int dev = 0;
+    const int dev = current_device();
+    if (dev < 0) return 0;
+    if (g_num_cu[dev] == 0) {
         hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-            return 0;
-        g_num_cu = prop.multiProcessorCount;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+        g_num_cu[dev] = prop.multiProcessorCount;
     }
-    return g_num_cu;
+    return g_num_cu[dev];
 }
 
 template <int MT, int RS>
@@ -1073,11 +1083,13 @@ static size_t linear_lds_bytes()
 
 // All workgroups must be resident at once (they wait for each other): one per compute unit.
 template <class Kernel>
-static ghd_status launch_resident(Kernel kernel, bool& checked, size_t lds, const FusedArgs& a,
-                                  hipStream_t st)
+static ghd_status launch_resident(Kernel kernel, bool (&checked_on)[kMaxDevices], size_t lds,
+                                  const FusedArgs& a, hipStream_t st)
 {
+    const int dev = current_device();
     int G = fused_grid_size();
-    if (G <= 0 || G > 512) return hip_fail(hipErrorInvalidDevice);   // counter arrays hold 512 lines
+    if (dev < 0 || G <= 0 || G > 512) return hip_fail(hipErrorInvalidDevice);   // counter arrays hold 512 lines
+    bool& checked = checked_on[dev];
     if (!checked) {
         hipError_t e = hipFuncSetAttribute((const void*)kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1095,7 +1107,7 @@ static ghd_status launch_resident(Kernel kernel, bool& checked, size_t lds, cons
 template <int MT, int RS>
 static ghd_status launch_linear_t(const FusedArgs& a, hipStream_t st)
 {
-    static bool checked = false;
+    static bool checked[kMaxDevices] = {};
     return launch_resident(k_linear<MT, RS>, checked, linear_lds_bytes<MT, RS>(), a, st);
 }
 
@@ -1115,7 +1127,7 @@ static ghd_status launch_linear_rs(const FusedArgs& a, hipStream_t st)
 template <int MT, int D>
 static ghd_status launch_attention_t(const FusedArgs& a, hipStream_t st)
 {
-    static bool checked = false;
+    static bool checked[kMaxDevices] = {};
     return launch_resident(k_attention<MT, D>, checked, sizeof(AttnLds<MT, D>), a, st);
 }
 
