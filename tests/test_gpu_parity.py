@@ -582,3 +582,47 @@ def test_masked_attention_rows_without_keys_give_zeros(B, model, orc32):
     assert np.all(got[[3, 64, 69]] == 0)
     ok, ma, mr = close(got, ref, 5e-3, 5e-3)
     assert ok, (ma, mr)
+
+
+def test_step_can_be_captured_in_a_graph(B, model, orc32):
+    """The step allocates nothing and records no memset: captured in a HIP graph it gives,
+    on every replay (with eager steps and synchronisations in between), exactly the eager
+    result."""
+    shape = wl.ModelShape("graph2", H=512, nh=4, d=128, F=1376, V=3000, L=2)
+    M, kv_len, seed = 24, 200, 12
+    parent = wl.tree_random(M, 4, seed)
+    say("graph capture")
+    stack, logits_eager, _, pd = run_stack_case(B, model, orc32, shape, M, kv_len, parent, seed)
+    x16 = wl.activations(M, shape.H, seed).cuda()
+    tokens = torch.from_numpy(wl.draft_tokens(M, shape.V, seed)).cuda()
+    ws = B.workspace(B.ghd_workspace_bytes(stack.cfg, M, kv_len))
+    aws = B.workspace(B.lib().ghd_accept_workspace_bytes(M))
+    logits = torch.empty((M, shape.V), dtype=torch.float32, device="cuda")
+    res = torch.zeros(2 + M, dtype=torch.int32, device="cuda")
+    amax = torch.empty(M, dtype=torch.int32, device="cuda")
+
+    def step():
+        B.ghd_verify_stack(stack, x16, pd, kv_len, logits=logits, ws=ws)
+        B.ghd_accept_greedy(logits, tokens, pd, res=res, amax=amax, ws=aws)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        step()
+        torch.cuda.synchronize()
+        want_logits, want_res = logits.clone(), res.clone()
+        assert torch.equal(want_logits, logits_eager)            # the step is deterministic
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            step()
+        torch.cuda.synchronize()
+        for rep in range(4):
+            logits.fill_(float("nan"))
+            res.zero_()
+            if rep % 2:
+                step()                                           # eager work between replays
+                torch.cuda.synchronize()
+                logits.fill_(float("nan"))
+            g.replay()
+            torch.cuda.synchronize()
+            assert B.ghd_step_status(ws) == 0
+            assert torch.equal(logits, want_logits) and torch.equal(res, want_res), rep
