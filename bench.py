@@ -271,7 +271,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the verification step runs on a single MI355X and "
-                 "no multi-GPU path exists in this build (--gpus %d refused)" % args.gpus)
+                 "there is no multi-GPU path (--gpus %d refused)" % args.gpus)
 
     import torch
     from paper_2505_23219_amd import binding as B, model, workloads as wl

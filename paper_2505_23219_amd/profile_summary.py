@@ -48,7 +48,7 @@ def stats(path: str, out: str, command: str) -> None:
     total = sum(int(r["TotalDurationNs"]) for r in rows)
     with open(out, "w") as f:
         f.write("# rocprofv3 kernel statistics: verification step, workload stack7b\n\n")
-        f.write("Command (on the GPU box, from the repository root):\n\n    %s\n\n" % command)
+        f.write("Command (on an MI355X, from the repository root):\n\n    %s\n\n" % command)
         f.write("Kernels of this library only (model set-up and PyTorch fill kernels left out); "
                 "the run holds tree steps (M=64: `k_linear<4, 1>`, `k_attention<4, 128>`) and 1-token "
                 "decode steps (`k_linear<1, 2>`, `k_attention<1, 128>`).\n\n")
@@ -83,7 +83,7 @@ def traffic(fetch_csv: str, write_csv: str, out: str, command: str) -> None:
     fetched, written = f_lin * f_scale, w_lin * w_scale
     with open(out, "w") as f:
         f.write("# HBM traffic of the linear-layer kernel `k_linear<4, 1>`, workload stack7b\n\n")
-        f.write("Commands (on the GPU box, from the repository root; one counter per run):\n\n")
+        f.write("Commands (on an MI355X, from the repository root; one counter per run):\n\n")
         f.write("    %s\n\n" % command.replace("COUNTER", "FETCH_SIZE"))
         f.write("    %s\n\n" % command.replace("COUNTER", "WRITE_SIZE"))
         f.write("Calibration: the 1 GiB copy kernel of the same run (reads 1 GiB, writes 1 GiB) "
@@ -107,7 +107,7 @@ def counter(path: str, name: str, out: str, command: str) -> None:
         sys.exit("%s: no %s rows for this library's kernels" % (path, name))
     with open(out, "w") as f:
         f.write("# %s per kernel, workload stack7b\n\n" % name)
-        f.write("Command (on the GPU box, from the repository root):\n\n    %s\n\n" % command)
+        f.write("Command (on an MI355X, from the repository root):\n\n    %s\n\n" % command)
         f.write("| kernel | dispatches | avg %s | min | max |\n|---|---|---|---|---|\n" % name)
         for k, v in sorted(acc.items(), key=lambda kv: -len(kv[1])):
             f.write("| `%s` | %d | %.2f | %.2f | %.2f |\n" % (k, len(v), sum(v) / len(v), min(v), max(v)))
