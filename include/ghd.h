@@ -28,6 +28,15 @@
  *     they never synchronise.  `ws` is caller-provided device scratch of at
  *     least the size the matching *_workspace_bytes function returns, 256-byte
  *     aligned.
+ *   - Concurrency: the persistent kernels need every compute unit (all their
+ *     workgroups wait for each other), so two calls that overlap in time on one
+ *     GPU - from two streams or two threads - slow each other down and may run
+ *     into the bounded waits (reported through ghd_step_status, never a hang).
+ *     Calls that share a workspace must be ordered on one stream.  The library
+ *     keeps no state between calls apart from per-device facts it caches (number
+ *     of compute units, kernel attributes) and the error code of
+ *     ghd_last_hip_error; it may be called from several host threads as long as
+ *     their GPU work is ordered as said.
  *   - Argument checks run on the host before the first GPU call.  A negative
  *     return value means nothing was enqueued (except GHD_ERR_HIP, which
  *     reports a failing launch; ghd_last_hip_error gives the HIP code).
