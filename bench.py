@@ -260,7 +260,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="stack7b")
-    ap.add_argument("--cpu-sample-layers", type=int, default=8)
+    ap.add_argument("--cpu-sample-layers", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="also time one 7B-shaped layer at tree sizes 1..128 (adds a \"sweep\" list)")
