@@ -325,3 +325,20 @@ def test_masked_attention_rejects_bad_arguments(lib):
     assert call(d=96) == B.GHD_ERR_SHAPE
     assert call(vsc=64) == B.GHD_ERR_CAPACITY
     assert call(ws=None) == B.GHD_ERR_WORKSPACE
+
+
+def test_benchmark_loop_tree_is_pinned(lib, orc32):
+    """The tree the decoding-loop benchmark verifies: the library's design equals the
+    oracle's, and both equal the committed fixture (written by tests/golden/make_loop_tree.py
+    from the oracle alone)."""
+    import json
+    with open(os.path.join(ROOT, "tests", "golden", "loop_tree.json")) as f:
+        gold = json.load(f)
+    acc = wl.head_accuracies(gold["heads"], gold["candidates"])
+    parent, rank, e = B.ghd_tree_build(acc.tolist(), gold["nodes"])
+    assert parent == gold["parent"] and rank == gold["rank"]
+    assert abs(e - gold["expected_acceptance_length"]) < 1e-12
+    p0, r0, e0 = orc32.tree_build(acc, gold["nodes"])
+    assert p0.tolist() == gold["parent"] and r0.tolist() == gold["rank"] and e0 == e
+    # a tree over 5 heads never goes deeper than 5 drafted levels
+    assert orc32.tree_depth(p0).max() <= gold["heads"]
