@@ -76,12 +76,90 @@ def decode_loop(torch, B, wl, stack, w, stream, steps, K=5, R=10):
             done += 1
         dt = time.perf_counter() - t0
     head_bytes = 2 * K * s.V * s.H
-    return {"steps": done, "tokens": produced, "tokens_per_s": round(produced / dt, 1),
-            "us_per_step": round(dt / done * 1e6, 1), "mean_accepted": round(produced / done, 3),
-            "tree_nodes": M, "heads": K, "candidates_per_head": R,
-            "expected_accepted_at_synthetic_accuracies": round(expect, 3),
-            "drafting_head_bytes": head_bytes,
-            "note": "untrained synthetic heads; one 4-byte host read per step included"}
+    out = {"steps": done, "tokens": produced, "tokens_per_s": round(produced / dt, 1),
+           "us_per_step": round(dt / done * 1e6, 1), "mean_accepted": round(produced / done, 3),
+           "tree_nodes": M, "heads": K, "candidates_per_head": R,
+           "expected_accepted_at_synthetic_accuracies": round(expect, 3),
+           "drafting_head_bytes": head_bytes,
+           "note": "untrained synthetic heads; one 4-byte host read per step included"}
+    out["drafts_right_at_synthetic_accuracies"] = planted_loop(
+        torch, B, wl, spec, stack, embed, heads, w, stream, steps, K, R, acc, parent, rank, pd, rd, ws)
+    return out
+
+
+def planted_loop(torch, B, wl, spec, stack, embed, heads, w, stream, steps, K, R, acc, parent, rank,
+                 pd, rd, ws):
+    """The same loop with drafts that are right as often as the synthetic accuracy table
+    says: the model's own continuation is first produced one token at a time (same
+    library, one-node tree); in every tree step candidate r of head k then carries the true
+    token of its slot with probability acc[k][r] (at most one candidate per head), a wrong
+    one otherwise.  The drafting heads still run (their cost is in the time); their output
+    is replaced by these drafts.  Shows the loop accepting several tokens per step, as
+    trained heads would make it, and reports whether the produced tokens are those of
+    one-at-a-time decoding."""
+    import numpy as np
+    dev = "cuda"
+    s = w.shape
+    M = len(parent)
+    cap = stack.cfg.kv_capacity
+    need = min(steps * (K + 1) + K + 1, cap - w.kv_len - M)
+    # one token at a time
+    one_p = torch.tensor([-1], dtype=torch.int32, device=dev)
+    one_r = torch.zeros(1, dtype=torch.int32, device=dev)
+    tok1 = torch.tensor([int(wl.draft_tokens(M, s.V, w.seed)[0])], dtype=torch.int32, device=dev)
+    res1 = torch.zeros(3, dtype=torch.int32, device=dev)
+    ws1 = B.workspace(spec.workspace_bytes(1, cap - 1))
+    first = int(tok1[0])
+    with torch.cuda.stream(stream):
+        seq = torch.zeros(need, dtype=torch.int32, device=dev)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(need):
+            B.ghd_spec_step(spec, one_p, one_r, w.kv_len + i, tok1, res1, ws1)
+            seq[i:i + 1].copy_(res1[1:2])          # tok1 already holds it for the next step
+        torch.cuda.synchronize()
+        seq_dt = time.perf_counter() - t0
+    want = seq.cpu().numpy().tolist()
+    # the tree loop
+    depth = [0] * M
+    for i in range(1, M):
+        depth[i] = depth[parent[i]] + 1
+    rng = np.random.default_rng([w.seed, 4242])
+    cum = np.cumsum(acc, axis=1)
+    tokens_host = torch.zeros(M, dtype=torch.int32).pin_memory()
+    tokens = torch.zeros(M, dtype=torch.int32, device=dev)
+    res = torch.zeros(2 + M, dtype=torch.int32, device=dev)
+    res_host = torch.zeros(2 + M, dtype=torch.int32).pin_memory()
+    kv, got, done, last = w.kv_len, [], 0, first
+    with torch.cuda.stream(stream):
+        t0 = time.perf_counter()
+        while done < steps and len(got) + K + 1 <= need:
+            future = want[len(got):len(got) + K]
+            u = rng.random(K)
+            right = [int(np.searchsorted(cum[k], u[k], side="right")) for k in range(K)]   # == R: none
+            th = tokens_host.numpy()
+            th[0] = last
+            for i in range(1, M):
+                k = depth[i] - 1
+                th[i] = future[k] if rank[i] == right[k] else (future[k] + 1 + rank[i]) % s.V
+            tokens.copy_(tokens_host, non_blocking=True)
+            B.ghd_spec_step(spec, pd, rd, kv, tokens, res, ws)
+            res_host.copy_(res, non_blocking=True)
+            stream.synchronize()
+            n = int(res_host[0])
+            path = res_host[2:2 + n].tolist()
+            got += [int(th[i]) for i in path[1:]] + [int(res_host[1])]
+            last = int(res_host[1])
+            kv += n
+            done += 1
+        dt = time.perf_counter() - t0
+    return {"steps": done, "tokens": len(got), "tokens_per_s": round(len(got) / dt, 1),
+            "us_per_step": round(dt / done * 1e6, 1), "mean_accepted": round(len(got) / done, 3),
+            "equals_one_at_a_time_decoding": got == want[:len(got)],
+            "one_at_a_time_tokens_per_s": round(need / seq_dt, 1),
+            "speedup_over_one_at_a_time": round(len(got) / dt / (need / seq_dt), 2),
+            "note": "drafts planted from the model's own continuation with the synthetic "
+                    "accuracies; host builds and uploads the 64 draft tokens every step"}
 
 
 def time_steps(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, res, amax, stream,
