@@ -25,11 +25,24 @@ def np_cache(shape, cap, kv_len, seed, layer):
     return k.numpy().copy(), v.numpy().copy()
 
 
-def library_layer(shape, w, kc, vc, x, parent, kv_len):
-    """One layer from torch library routines, fp64, no fp16 rounding."""
+ROUNDING_POINTS = ("n_attn", "q", "o", "n_ffn", "a")
+NOT_ROUNDED = ("wo_out", "gu", "down_out")     # places the oracle must not round at
+
+
+def library_layer(shape, w, kc, vc, x, parent, kv_len, casts=()):
+    """One layer from torch library routines in fp64.  `casts` names the intermediate
+    results that are rounded to fp16 on the way (numpy's direct double -> half
+    conversion): the normalised activations of the two blocks, the rotated queries, the
+    attention output and the SwiGLU activation.  The rows appended to the cache are fp16
+    in every variant, because the cache is."""
     H, nh, d, F = shape.H, shape.nh, shape.d, shape.F
     M = len(parent)
     t = lambda a: torch.from_numpy(np.asarray(a).astype(np.float64))
+    assert set(casts) <= set(ROUNDING_POINTS + NOT_ROUNDED)
+
+    def cast(name, v):
+        return t(v.numpy().astype(np.float16)) if name in casts else v
+
     x = t(x)
     depth = [0] * M
     for i in range(1, M):
@@ -42,9 +55,9 @@ def library_layer(shape, w, kc, vc, x, parent, kv_len):
         z = torch.complex(v[..., :d // 2], v[..., d // 2:]) * torch.polar(torch.ones_like(ang), ang)[:, None, :]
         return torch.cat([z.real, z.imag], dim=-1)
 
-    n = Fn.rms_norm(x, (H,), t(w["g_attn"]), shape.rms_eps)
+    n = cast("n_attn", Fn.rms_norm(x, (H,), t(w["g_attn"]), shape.rms_eps))
     qkv = Fn.linear(n, t(w["Wqkv"]))
-    q = rot(qkv[:, :H].reshape(M, nh, d))
+    q = cast("q", rot(qkv[:, :H].reshape(M, nh, d)))
     k = rot(qkv[:, H:2 * H].reshape(M, nh, d))
     v = qkv[:, 2 * H:].reshape(M, nh, d)
     # the cache holds fp16: the tree rows are attended as stored
@@ -53,12 +66,12 @@ def library_layer(shape, w, kc, vc, x, parent, kv_len):
     V = torch.cat([t(vc[:, :kv_len]), h16(v).permute(1, 0, 2)], dim=1)
     vis = torch.cat([torch.ones(M, kv_len, dtype=torch.bool),
                      torch.from_numpy(mask_by_recurrence(parent).astype(bool))], dim=1)
-    o = Fn.scaled_dot_product_attention(q.permute(1, 0, 2), K, V, attn_mask=vis)
-    x = x + Fn.linear(o.permute(1, 0, 2).reshape(M, H), t(w["Wo"]))
-    n2 = Fn.rms_norm(x, (H,), t(w["g_ffn"]), shape.rms_eps)
-    gu = Fn.linear(n2, t(w["Wgu"]))
-    a = Fn.silu(gu[:, :F]) * gu[:, F:]
-    x = x + Fn.linear(a, t(w["Wdown"]))
+    o = cast("o", Fn.scaled_dot_product_attention(q.permute(1, 0, 2), K, V, attn_mask=vis))
+    x = x + cast("wo_out", Fn.linear(o.permute(1, 0, 2).reshape(M, H), t(w["Wo"])))
+    n2 = cast("n_ffn", Fn.rms_norm(x, (H,), t(w["g_ffn"]), shape.rms_eps))
+    gu = cast("gu", Fn.linear(n2, t(w["Wgu"])))
+    a = cast("a", Fn.silu(gu[:, :F]) * gu[:, F:])
+    x = x + cast("down_out", Fn.linear(a, t(w["Wdown"])))
     return x.numpy(), k.numpy(), v.numpy()
 
 
@@ -86,6 +99,56 @@ def test_layer_matches_library_composition(orc32, orc64, M, depth, kv_len, seed)
     got16 = orc32.verify_layer(SHAPE, w, kc.copy(), vc.copy(), x, parent, kv_len, round16=True)
     err = np.abs(got16 - ref).max()
     assert 0 < err < 5e-3
+
+
+@pytest.mark.parametrize("M,depth,kv_len,seed", [(1, 1, 9, 0), (7, 3, 20, 1), (16, 4, 0, 2)])
+def test_rounded_layer_rounds_at_exactly_the_documented_points(orc32, orc64, M, depth, kv_len, seed):
+    """The variant with fp16 rounding points (the truth of every GPU layer and stack
+    comparison) is the library composition with casts at exactly five places.  In the fp64
+    build the casts are then the only difference, so the two agree to accumulation noise;
+    with any one cast left out, or with none, they do not."""
+    parent = wl.tree_random(M, depth, seed)
+    w = np_weights(SHAPE, seed, 0)
+    x = wl.activations(M, SHAPE.H, seed).numpy()
+    kc, vc = np_cache(SHAPE, kv_len + M + 3, kv_len, seed, 0)
+    ref, k_ref, v_ref = library_layer(SHAPE, w, kc, vc, x, parent, kv_len, ROUNDING_POINTS)
+    kc64, vc64 = kc.copy(), vc.copy()
+    got = orc64.verify_layer(SHAPE, w, kc64, vc64, x, parent, kv_len, round16=True)
+    np.testing.assert_allclose(got, ref, atol=1e-9, rtol=0)
+    np.testing.assert_array_equal(kc64[:, kv_len:kv_len + M], k_ref.transpose(1, 0, 2).astype(np.float16))
+    np.testing.assert_array_equal(vc64[:, kv_len:kv_len + M], v_ref.transpose(1, 0, 2).astype(np.float16))
+    # the fp32 build of the same variant: accumulation noise, now and then carried across
+    # a rounding boundary of one element (an fp16 ulp of an O(1) value times a weight)
+    got32 = orc32.verify_layer(SHAPE, w, kc.copy(), vc.copy(), x, parent, kv_len, round16=True)
+    np.testing.assert_allclose(got32, ref, atol=3e-4, rtol=0)
+    assert np.abs(got32 - ref).mean() < 5e-6
+    # negatives: a missing rounding point is seen
+    for missing in ROUNDING_POINTS:
+        fewer = tuple(p for p in ROUNDING_POINTS if p != missing)
+        other, _, _ = library_layer(SHAPE, w, kc, vc, x, parent, kv_len, fewer)
+        assert np.abs(got - other).max() > 1e-6, missing
+    none, _, _ = library_layer(SHAPE, w, kc, vc, x, parent, kv_len)
+    assert np.abs(got - none).max() > 1e-5
+    # ... and so is a sixth one
+    for extra in NOT_ROUNDED:
+        other, _, _ = library_layer(SHAPE, w, kc, vc, x, parent, kv_len, ROUNDING_POINTS + (extra,))
+        assert np.abs(got - other).max() > 1e-6, extra
+
+
+def test_rounded_lm_head_rounds_the_normalised_input_only(orc64):
+    M, seed = 5, 6
+    head = {k: v.numpy() for k, v in wl.head_weights(SHAPE, seed).items()}
+    x = (3.0 * wl.activations(M, SHAPE.H, seed).numpy().astype(np.float64))
+    t = lambda a: torch.from_numpy(np.asarray(a).astype(np.float64))
+    n = Fn.rms_norm(t(x), (SHAPE.H,), t(head["g_final"]), SHAPE.rms_eps)
+    n16 = t(n.numpy().astype(np.float16))
+    ref = Fn.linear(n16, t(head["Wlm"])).numpy()
+    got = orc64.lm_head(SHAPE, head["g_final"], head["Wlm"], x, True)
+    np.testing.assert_allclose(got, ref, atol=1e-10, rtol=0)
+    plain = Fn.linear(n, t(head["Wlm"])).numpy()
+    assert np.abs(got - plain).max() > 1e-6
+    # logits are not rounded to fp16
+    assert np.abs(got - got.astype(np.float16)).max() > 1e-7
 
 
 def test_width1_tree_equals_sequential_decode(orc32):
