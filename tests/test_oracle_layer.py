@@ -132,7 +132,7 @@ def test_rounded_layer_rounds_at_exactly_the_documented_points(orc32, orc64, M, 
     # ... and so is a sixth one
     for extra in NOT_ROUNDED:
         other, _, _ = library_layer(SHAPE, w, kc, vc, x, parent, kv_len, ROUNDING_POINTS + (extra,))
-        assert np.abs(got - other).max() > 1e-6, extra
+        assert np.abs(got - other).max() > 1e-7, extra   # (the match above holds to 1e-9)
 
 
 def test_rounded_lm_head_rounds_the_normalised_input_only(orc64):
