@@ -292,6 +292,7 @@ def sweep(torch, B, model, wl, stream, sets=4, iters=40):
                     B.ghd_verify_layer(cfg, layers[i % sets], *caches[i % sets], x, parent, 2048, ws=ws)
                 e1.record(stream)
                 torch.cuda.synchronize()
+            require_clean_status(B, ws, "the sweep at M=%d (%s)" % (M, kind))
             us = e0.elapsed_time(e1) / iters * 1e3
             nbytes = 2 * (4 * shape.H * shape.H + 3 * shape.H * shape.F) + 4 * shape.H * (2048 + M)
             rows.append({"M": M, "tree": kind, "layer_us": round(us, 1),
@@ -300,36 +301,62 @@ def sweep(torch, B, model, wl, stream, sets=4, iters=40):
     return rows
 
 
+def cpu_model_name():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(wl, w, sample_layers):
-    """The CPU oracle, as it stands, timed on the host cores on a bounded sample of
-    the same workload: `sample_layers` decoder layers + the LM head; the step
-    latency is extrapolated linearly to all layers."""
+    """The CPU oracle, as it stands, timed on the host cores on the same workload:
+    `sample_layers` decoder layers (all of them by default), one after the other as the
+    oracle's stack routine runs them, then the LM head and the acceptance.  Weights and
+    cache of a layer are drawn right before its call and dropped after it (not timed), so
+    the host never holds more than one layer.  If fewer layers than the model has are
+    timed, the figure is scaled and says so."""
     import numpy as np
     from oracle import Oracle
     orc = Oracle("f32")
-    s = wl.with_layers(w.shape, sample_layers)
-    layers = [{k: v.numpy() for k, v in wl.layer_weights(s, w.seed, l).items()}
-              for l in range(sample_layers)]
+    s = w.shape
+    n = min(sample_layers, s.L) if sample_layers > 0 else s.L
+    x = wl.activations(w.M, s.H, w.seed).numpy().astype(np.float32)
+    t_layers = 0.0
+    for l in range(n):
+        lw = {k: v.numpy() for k, v in wl.layer_weights(s, w.seed, l).items()}
+        kc, vc = wl.kv_cache(s, w.capacity, w.kv_len, w.seed, l)
+        kc, vc = kc.numpy(), vc.numpy()
+        t0 = time.perf_counter()
+        x = orc.verify_layer(s, lw, kc, vc, x, w.parent, w.kv_len, True)
+        t_layers += time.perf_counter() - t0
+        del lw, kc, vc
     head = {k: v.numpy() for k, v in wl.head_weights(s, w.seed).items()}
-    kcs, vcs = [], []
-    for l in range(sample_layers):
-        k, v = wl.kv_cache(s, w.capacity, w.kv_len, w.seed, l)
-        kcs.append(k.numpy())
-        vcs.append(v.numpy())
-    x16 = wl.activations(w.M, s.H, w.seed).numpy()
     t0 = time.perf_counter()
-    _, x_out = orc.verify_stack(s, layers, kcs, vcs, None, x16, w.parent, w.kv_len, True)
-    t_layers = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    logits = orc.lm_head(s, head["g_final"], head["Wlm"], x_out, True)
+    logits = orc.lm_head(s, head["g_final"], head["Wlm"], x, True)
     orc.accept_greedy(logits, wl.draft_tokens(w.M, s.V, w.seed), w.parent)
     t_head = time.perf_counter() - t0
-    full = t_layers * (w.shape.L / sample_layers) + t_head
-    cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
-    return {"value": round(full * 1e6, 1), "unit": "us", "cores": cores, "kind": "oracle",
-            "sample": "%d of %d layers + LM head + acceptance, M=%d, kv_len=%d; %.2f s measured, "
-                      "layers scaled x%g" % (sample_layers, w.shape.L, w.M, w.kv_len,
-                                             t_layers + t_head, w.shape.L / sample_layers)}
+    full = t_layers * (s.L / n) + t_head
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
+    sample = "%d of %d layers + LM head + acceptance, M=%d, kv_len=%d; %.2f s of oracle time" % (
+        n, s.L, w.M, w.kv_len, t_layers + t_head)
+    if n != s.L:
+        sample += ", layers scaled x%g" % (s.L / n)
+    return {"value": round(full * 1e6, 1), "unit": "us", "cores": threads, "kind": "oracle",
+            "sample": sample, "cpu_model": cpu_model_name(),
+            "omp_num_threads": os.environ.get("OMP_NUM_THREADS"),
+            "host_logical_cpus": os.cpu_count()}
+
+
+def require_clean_status(B, ws, what):
+    """A bounded wait that gave up inside the timed region leaves its code in the step's
+    status word: such a region is not a measurement."""
+    st = B.ghd_step_status(ws)
+    if st != 0:
+        sys.exit("bench.py: %s ended with step status %d (a workgroup wait gave up); no figure printed"
+                 % (what, st))
 
 
 def main():
@@ -338,10 +365,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="stack7b")
-    ap.add_argument("--cpu-sample-layers", type=int, default=16)
+    ap.add_argument("--cpu-sample-layers", type=int, default=0,
+                    help="decoder layers the CPU oracle is timed on (0 = all of them)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sweep", action="store_true",
-                    help="also time one 7B-shaped layer at tree sizes 1..128 (adds a \"sweep\" list)")
+    ap.add_argument("--no-sweep", dest="sweep", action="store_false",
+                    help="skip the tree-size sweep (one 7B-shaped layer at tree sizes 1..128, the \"sweep\" list)")
     ap.add_argument("--loop", type=int, default=0,
                     help="also run this many whole predict-then-verify steps (adds \"decode_loop\")")
     ap.add_argument("--pmc-calibrate", action="store_true",
@@ -390,19 +418,23 @@ def main():
     ms, wall_ms = time_steps(torch, B, stack, tree["x_in"], tree["parent"], tree["tokens"], w.kv_len,
                              tree["ws"], tree["aws"], tree["logits"], tree["res"], tree["amax"],
                              stream, args.steps, args.warmup)
+    require_clean_status(B, tree["ws"], "the timed tree steps")
     log("tree step: %.1f us (wall %.1f us)" % (ms * 1e3, wall_ms * 1e3))
     spread = step_spread(torch, B, stack, tree["x_in"], tree["parent"], tree["tokens"], w.kv_len,
                          tree["ws"], tree["aws"], tree["logits"], tree["res"], tree["amax"], stream,
                          max(args.steps, 20))
+    require_clean_status(B, tree["ws"], "the per-step spread run")
     log("per-step spread:", spread)
     # the same model as a plain 1-token decode step: denominator of the "within 1.3x" target
     dec = inputs(1, wl.tree_chain(1))
     dec_ms, _ = time_steps(torch, B, stack, dec["x_in"], dec["parent"], dec["tokens"], w.kv_len,
                            dec["ws"], dec["aws"], dec["logits"], dec["res"], dec["amax"], stream,
                            args.steps, args.warmup)
+    require_clean_status(B, dec["ws"], "the timed decode steps")
     log("decode step: %.1f us" % (dec_ms * 1e3))
     roof = linear_roofline(torch, B, stack, tree["x_in"], tree["parent"], w.kv_len, tree["ws"],
                            tree["logits"], stream, w, max(2, min(args.steps, 5)))
+    require_clean_status(B, tree["ws"], "the per-launch timing run")
     log("roofline:", roof)
 
     step_bytes = w.algorithmic_bytes()
@@ -440,7 +472,7 @@ def main():
                                "expected_tokens_per_layer_ms": [round(x * 1e3, 3) for x in rate]}
         log("width choice:", out["width_choice"])
     if not args.no_cpu_baseline:
-        log("timing the CPU oracle on %d layers ..." % args.cpu_sample_layers)
+        log("timing the CPU oracle on %s layers ..." % (args.cpu_sample_layers or "all"))
         out["cpu_baseline"] = cpu_baseline(wl, w, args.cpu_sample_layers)
     print(json.dumps(out), flush=True)
 

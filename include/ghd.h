@@ -14,8 +14,8 @@
  *   - fp16 tensors are IEEE binary16.  Activations are row-major [M, width].
  *   - Weight matrices are passed in the PACKED layout written by
  *     ghd_pack_weight (the bytes of the row-major [N, K] matrix, zero padded to
- *     N%256 == 0 and K%128 == 0 and reordered so that every workgroup streams
- *     one contiguous range in 1 KiB MFMA-operand blocks).
+ *     whole 16-row tiles and 32-column k-steps and reordered into 1 KiB
+ *     MFMA-operand blocks so that every workgroup streams contiguous runs).
  *   - The KV cache of one layer is fp16.  K is row-major per head: element
  *     (head h, row t, channel c) at h*k_stride_head + t*k_stride_tok + c.  V is
  *     kept channel-major, (h, c, t) at h*v_stride_head + c*v_stride_ch + t, so
@@ -120,10 +120,13 @@ size_t ghd_tree_mask_workspace_bytes(void);
 size_t ghd_packed_weight_bytes(int N, int K);
 
 /* dst (packed) <- src (row-major [N, K] fp16, device).  One-off, offline.
- * Layout: packed row p and column k live in row group p/256, k-step k/32, tile
- * (p%256)/16; the 1 KiB block of (group, k-step, tile) sits at block index
- * (group*KS + k-step)*16 + tile with KS = 4*ceil(K/128); inside a block the
- * 16-byte chunk number ((k%32)/8)*16 + p%16 holds row p, columns k-k%8 .. +8.
+ * Layout: the unit is the 1 KiB block of 16 packed rows (a tile, T = p/16) by 32
+ * columns (a k-step, s = k/32); inside a block the 16-byte chunk number
+ * ((k%32)/8)*16 + p%16 holds row p, columns k-k%8 .. +8.  With KS = ceil(K/32)
+ * k-steps and NT = ceil(N/16) tiles, tiles are stored in blocks of B tiles,
+ * B = 8 if NT >= 640 (wide matrices) else 4, k-step major inside a block: the
+ * 1 KiB block (T, s) sits at block index ((T/B)*KS + s)*B + T%B.  The last
+ * block is padded to B tiles.
  * Padding is zero.  `kind` chooses which source row packed row p holds:
  *   GHD_PACK_PLAIN    row p
  *   GHD_PACK_QKV      src is [3H, K] (q, k, v rows; heads of head_dim rows): in

@@ -58,13 +58,24 @@ static int mpad_of(int M)
     return (mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : 8) * 16;
 }
 
-// Row split of a linear layer's 256-row groups.  Halving the groups halves the partial
-// sums that split groups exchange and doubles the x a workgroup stages; measured on 7B
-// shapes that pays (2-3%) at every tree size except 33..64 nodes, where it costs 1%.
-static int row_split(int M, int N, int K)
+// Is a linear layer of this shape within what the kernel's 32-bit share arithmetic covers?
+static bool linear_shape_ok(int N, int K)
 {
-    (void)N; (void)K;
-    return (M > 32 && M <= 64) ? 1 : 2;
+    if (N < 1 || K < 8 || (K % 8) != 0) return false;
+    const WLayout lay = w_layout(N, K);
+    // units of one XCD times shares of one XCD must fit 32 bits
+    return ((int64_t)lay.nitems * lay.nks / 8 + lay.nks) * (kMaxShares / 8) < (1ll << 31);
+}
+
+// Fills in how the launch is cut (see plan_linear); false if the shape needs more work shares
+// than the counters are laid out for.
+static bool fill_plan(FusedArgs& a, int M, int N, int K)
+{
+    LinPlan pl;
+    if (!plan_linear(M, N, K, grid_for_sizing(), &pl)) return false;
+    a.lin_slots = pl.slots;
+    a.lin_passes = pl.passes;
+    return true;
 }
 
 // ---- workspace carving ---------------------------------------------------------
@@ -84,21 +95,23 @@ struct Carver {
 struct Ws {
     uint32_t* sync;
     float *part, *o_part, *ml_part, *x, *ss;
-    half_t *q16, *o16, *a16, *xg16;
+    half_t *q16, *o16, *a16, *xg16, *xpk;
     float2* rope;
     uint64_t* mask;
     size_t bytes;
 };
 
-// what: 0 = whole model (layer / stack), 1 = linear only, 2 = attention only
-static Ws carve(void* ws, int what, int M, int H, int F, int d)
+// what: 0 = whole model (layer / stack), 1 = linear only (K = its input features),
+// 2 = attention only
+static Ws carve(void* ws, int what, int M, int H, int F, int d, int K = 0)
 {
     Carver cv(ws);
     Ws w = {};
     const int G = grid_for_sizing();
-    const int Mpad = mpad_of(M);
+    const int Mpad = mpad_of(M), mtp = Mpad / 16;
     w.sync = cv.take<uint32_t>(kSyncWords);
-    if (what != 2) w.part = cv.take<float>((size_t)G * 2 * kTG * (Mpad / 16) * 256);
+    if (what != 2) w.part = cv.take<float>(linear_part_floats(M, G));
+    if (what == 1) w.xpk = cv.take<half_t>(xpk_halves(K, mtp));
     if (what != 1) {
         w.mask = cv.take<uint64_t>(2 * GHD_MAX_M);
         w.o_part = cv.take<float>((size_t)G * Mpad * d);
@@ -109,9 +122,9 @@ static Ws carve(void* ws, int what, int M, int H, int F, int d)
         w.x = cv.take<float>((size_t)M * H);
         w.ss = cv.take<float>((size_t)(H / 16) * Mpad);
         w.q16 = cv.take<half_t>((size_t)M * H);
-        w.o16 = cv.take<half_t>((size_t)M * H);
-        w.a16 = cv.take<half_t>((size_t)M * F);
-        w.xg16 = cv.take<half_t>((size_t)M * H);
+        w.o16 = cv.take<half_t>(xpk_halves(H, mtp));
+        w.a16 = cv.take<half_t>(xpk_halves(F, mtp));
+        w.xg16 = cv.take<half_t>(xpk_halves(H, mtp));
     }
     w.bytes = cv.off;
     return w;
@@ -124,9 +137,19 @@ static ghd_status check_cfg(const ghd_model_cfg* c, int M, int kv_len)
     if ((c->d != 64 && c->d != 128) || c->nh < 1 || c->nh > 256 || c->H != c->nh * c->d)
         return GHD_ERR_SHAPE;
     if (c->F < 8 || (c->F % 8) != 0 || c->F > (1 << 20) || c->L < 1 || c->L > kMaxLayers || c->V < 1) return GHD_ERR_SHAPE;
-    if (3 * (int64_t)c->H > 512 * kGroupRows || 2 * (int64_t)c->F > 512 * kGroupRows ||
-        (int64_t)c->V > 1024 * kGroupRows)
+    if (c->H > 65536 || c->V > (1 << 20)) return GHD_ERR_SHAPE;
+    if (!linear_shape_ok(3 * c->H, c->H) || !linear_shape_ok(2 * c->F, c->H) ||
+        !linear_shape_ok(c->H, c->F) || !linear_shape_ok(c->V, c->H))
         return GHD_ERR_SHAPE;
+    {
+        // every linear layer of the model must fit the work-share plan at this M
+        LinPlan pl;
+        const int G = grid_for_sizing();
+        if (!plan_linear(M, 3 * c->H, c->H, G, &pl) || !plan_linear(M, c->H, c->H, G, &pl) ||
+            !plan_linear(M, 2 * c->F, c->H, G, &pl) || !plan_linear(M, c->H, c->F, G, &pl) ||
+            !plan_linear(M, c->V, c->H, G, &pl))
+            return GHD_ERR_SHAPE;
+    }
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return GHD_ERR_SHAPE;
     if ((int64_t)kv_len + M > (int64_t)c->kv_capacity || (c->kv_capacity % 8) != 0) return GHD_ERR_CAPACITY;
     if ((int64_t)c->kv_capacity * c->d >= (1ll << 31)) return GHD_ERR_SHAPE;   // 32-bit offsets inside a head
@@ -184,8 +207,7 @@ static ghd_status check_layer(const ghd_layer_weights* w, const ghd_kv* kv)
 struct LinearCall {
     const void* Wp;
     int N, K, epi;
-    const half_t* in16;   // fp16 input [M, ldx]
-    int64_t ldx;
+    const half_t* in16;   // fp16 input, packed activation layout
     bool rscale;          // the input is xg16: apply the RMSNorm row factor in the epilogue
     const half_t* gnext;  // EPI_RESID: gain of the norm that follows, or nullptr
     void* out;
@@ -206,9 +228,8 @@ static ghd_status step_linear(const ghd_model_cfg* c, const Ws& w, float* x, int
     a.lin_N = lc.N;
     a.lin_K = lc.K;
     a.lin_epi = lc.epi;
-    a.lin_rs = row_split(M, lc.N, lc.K);
+    if (!fill_plan(a, M, lc.N, lc.K)) return GHD_ERR_SHAPE;
     a.lin_x = lc.in16;
-    a.lin_ldx = lc.ldx;
     a.lin_rscale = lc.rscale;
     a.lin_gnext = lc.gnext;
     a.lin_y = lc.out;
@@ -230,6 +251,7 @@ static ghd_status step_attention(const ghd_model_cfg* c, const Ws& w, const ghd_
     a.att_k = (const half_t*)kv->k;
     a.att_v = (const half_t*)kv->v;
     a.att_out = w.o16;
+    a.att_out_packed = 1;
     a.att_epoch = epoch;
     return timed_fused(a, st);
 }
@@ -243,14 +265,14 @@ static ghd_status run_layer(const ghd_model_cfg* c, const ghd_layer_weights* lw,
 {
     const int H = c->H, F = c->F;
     ghd_status s;
-    LinearCall qkv = {lw->Wqkv, 3 * H, H, EPI_QKV, w.xg16, H, true, nullptr, nullptr, 0, kv, kCntQkv, layer};
+    LinearCall qkv = {lw->Wqkv, 3 * H, H, EPI_QKV, w.xg16, true, nullptr, nullptr, 0, kv, kCntQkv, layer};
     if ((s = step_linear(c, w, x, M, kv_len, qkv, st))) return s;
     if ((s = step_attention(c, w, kv, M, kv_len, layer, st))) return s;
-    LinearCall wo = {lw->Wo, H, H, EPI_RESID, w.o16, H, false, (const half_t*)lw->g_ffn, x, H, nullptr, kCntWo, layer};
+    LinearCall wo = {lw->Wo, H, H, EPI_RESID, w.o16, false, (const half_t*)lw->g_ffn, x, H, nullptr, kCntWo, layer};
     if ((s = step_linear(c, w, x, M, kv_len, wo, st))) return s;
-    LinearCall gu = {lw->Wgu, 2 * F, H, EPI_SWIGLU, w.xg16, H, true, nullptr, w.a16, F, nullptr, kCntGu, layer};
+    LinearCall gu = {lw->Wgu, 2 * F, H, EPI_SWIGLU, w.xg16, true, nullptr, w.a16, F, nullptr, kCntGu, layer};
     if ((s = step_linear(c, w, x, M, kv_len, gu, st))) return s;
-    LinearCall down = {lw->Wdown, H, F, EPI_RESID, w.a16, F, false, next_g, x, H, nullptr, kCntDown, layer};
+    LinearCall down = {lw->Wdown, H, F, EPI_RESID, w.a16, false, next_g, x, H, nullptr, kCntDown, layer};
     return step_linear(c, w, x, M, kv_len, down, st);
 }
 
@@ -322,7 +344,7 @@ ghd_status ghd_pack_weight(void* dst, const void* src, int N, int K, int kind, i
 size_t ghd_linear_workspace_bytes(int M, int N, int K)
 {
     if (M < 1 || M > GHD_MAX_M || N < 1 || K < 1) return 0;
-    return carve(nullptr, 1, M, 0, 0, 0).bytes;
+    return carve(nullptr, 1, M, 0, 0, 0, K).bytes;
 }
 
 ghd_status ghd_linear_skinny(void* y, const void* x, const void* Wp, int M, int N, int K,
@@ -331,20 +353,20 @@ ghd_status ghd_linear_skinny(void* y, const void* x, const void* Wp, int M, int 
 {
     if (!y || !x || !Wp) return GHD_ERR_NULL;
     if (M < 1 || M > GHD_MAX_M || N < 1 || K < 8 || (K % 8) != 0) return GHD_ERR_SHAPE;
-    if (ldx < K || ldy < N || flags > GHD_OUT_F16 || (int64_t)N > 1024 * kGroupRows)
-        return GHD_ERR_SHAPE;
-    // the kernel counts chunks (256 rows x 128 columns) in 32 bits
-    if (((int64_t)N / kGroupRows + 1) * ((int64_t)K / kChunkCols + 1) >= (1ll << 31)) return GHD_ERR_SHAPE;
+    if (ldx < K || ldy < N || flags > GHD_OUT_F16 || !linear_shape_ok(N, K)) return GHD_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(Wp) || !aligned16(y) || (ldx % 8) != 0) return GHD_ERR_ALIGN;
     if (!ws) return GHD_ERR_WORKSPACE;
     if (!aligned16(ws)) return GHD_ERR_ALIGN;
     if (ws_bytes < ghd_linear_workspace_bytes(M, N, K)) return GHD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    Ws w = carve(ws, 1, M, 0, 0, 0);
+    Ws w = carve(ws, 1, M, 0, 0, 0, K);
+    FusedArgs a = {};
+    if (!fill_plan(a, M, N, K)) return GHD_ERR_SHAPE;
     ghd_status s = launch_fused_setup(w.sync, nullptr, M, mpad_of(M), 0, 0, 1.f, nullptr, nullptr,
                                       nullptr, nullptr, 0, nullptr, nullptr, nullptr, st);
     if (s) return s;
-    FusedArgs a = {};
+    // the kernel reads x as MFMA operand blocks
+    if ((s = launch_pack_x(w.xpk, (const half_t*)x, M, mpad_of(M), K, ldx, st))) return s;
     a.mode = MODE_LINEAR;
     a.M = M;
     a.Mpad = mpad_of(M);
@@ -352,15 +374,13 @@ ghd_status ghd_linear_skinny(void* y, const void* x, const void* Wp, int M, int 
     a.sync = w.sync;
     a.part = w.part;
     a.lin_W = (const half8*)Wp;
-    a.lin_x = (const half_t*)x;
+    a.lin_x = w.xpk;
     a.lin_y = y;
     a.lin_N = N;
     a.lin_K = K;
     a.lin_epi = flags == GHD_OUT_F16 ? EPI_STORE_F16 : EPI_STORE_F32;
-    a.lin_rs = row_split(M, N, K);
     a.lin_cnt = kCntLm;
     a.lin_epoch = 0;
-    a.lin_ldx = ldx;
     a.lin_ldy = ldy;
     return timed_fused(a, st);
 }
@@ -512,7 +532,7 @@ ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* l
         if (e != hipSuccess) return hip_fail(e);
     }
     // LM head on the final norm, straight into the caller's logits
-    LinearCall lm = {Wlm, cfg->V, H, EPI_STORE_F32, lw.xg16, H, true, nullptr,
+    LinearCall lm = {Wlm, cfg->V, H, EPI_STORE_F32, lw.xg16, true, nullptr,
                      logits, cfg->V, nullptr, kCntLm, 0};
     return step_linear(cfg, lw, lw.x, M, kv_len, lm, st);
 }
@@ -622,7 +642,7 @@ struct DraftWs {
 static DraftWs carve_draft(void* ws, int H, int K, int V, int R)
 {
     DraftWs d = {};
-    d.lin = carve(ws, 1, 1, 0, 0, 0);
+    d.lin = carve(ws, 1, 1, 0, 0, 0, H);
     Carver cv(ws);
     cv.off = d.lin.bytes;
     d.n16 = cv.take<half_t>((size_t)H);
@@ -635,7 +655,7 @@ static DraftWs carve_draft(void* ws, int H, int K, int V, int R)
 static bool draft_shape_ok(int K, int R, int H, int V)
 {
     return K >= 1 && K <= 16 && R >= 1 && R <= 32 && R <= V && H >= 8 && (H % 8) == 0 && V >= 1 &&
-           (int64_t)K * V <= 1024 * kGroupRows;
+           (int64_t)K * V <= 262144 && linear_shape_ok(K * V, H);
 }
 
 size_t ghd_draft_workspace_bytes(int K, int R, int H, int V)
@@ -667,7 +687,9 @@ ghd_status ghd_draft_tokens(const void* g_final, const void* Wheads, int K, int 
                                       nullptr, nullptr, 0, nullptr, nullptr, nullptr, st);
     if (s) return s;
     if ((s = launch_pick_norm(x_final, res_dev, M, H, g_final, rms_eps, d.n16, st))) return s;
+    if ((s = launch_pack_x(d.lin.xpk, d.n16, 1, mpad_of(1), H, H, st))) return s;
     FusedArgs a = {};
+    if (!fill_plan(a, 1, K * V, H)) return GHD_ERR_SHAPE;
     a.mode = MODE_LINEAR;
     a.M = 1;
     a.Mpad = mpad_of(1);
@@ -675,15 +697,13 @@ ghd_status ghd_draft_tokens(const void* g_final, const void* Wheads, int K, int 
     a.sync = d.lin.sync;
     a.part = d.lin.part;
     a.lin_W = (const half8*)Wheads;
-    a.lin_x = d.n16;
+    a.lin_x = d.lin.xpk;
     a.lin_y = logits;
     a.lin_N = K * V;
     a.lin_K = H;
     a.lin_epi = EPI_STORE_F32;
-    a.lin_rs = row_split(1, K * V, H);
     a.lin_cnt = kCntLm;
     a.lin_epoch = 0;
-    a.lin_ldx = H;
     a.lin_ldy = (int64_t)K * V;
     if ((s = timed_fused(a, st))) return s;
     if ((s = launch_topk(logits, K, V, R, topk, st))) return s;
@@ -764,6 +784,18 @@ ghd_status ghd_spec_step(const ghd_spec_model* m, const int32_t* parent_dev, con
 void ghd_debug_share(int items, int per_item, int j, int G, int item, int* out5)
 {
     share_on_host(items, per_item, j, G, item, out5);
+}
+
+/* out2 = {row tiles a share of a wide matrix handles at once, shares per workgroup} for a
+ * linear layer [N, K] at M rows on G workgroups; returns 0, or -1 if the shape needs more
+ * shares than the library is laid out for. */
+int ghd_debug_plan(int M, int N, int K, int G, int* out2)
+{
+    LinPlan pl;
+    if (!plan_linear(M, N, K, G, &pl)) return -1;
+    out2[0] = pl.slots;
+    out2[1] = pl.passes;
+    return 0;
 }
 
 void ghd_debug_attn_share(int nh, int ntile, int j, int G, int head, int* out6)

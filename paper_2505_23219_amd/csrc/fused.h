@@ -1,34 +1,82 @@
-// Argument block and launchers of the persistent kernels (fused.hip).
+// Argument block, layouts and launchers of the persistent kernels (linear.hip, fused.hip).
 #pragma once
 #include "common.h"
 
 namespace ghd {
 
 constexpr int kFT = 512;        // threads per workgroup (8 wavefronts)
-constexpr int kTG = 16;         // 16-row weight tiles per row group (8 wavefronts x 2)
-constexpr int kCH = 4;          // k-steps (32 columns) per staged chunk of x
-constexpr int kGroupRows = kTG * 16;
-constexpr int kChunkCols = kCH * 32;
 constexpr int kMaxLayers = 48;  // the counter epochs (one per layer) are laid out for this many
 
 enum { EPI_STORE_F32 = 0, EPI_STORE_F16 = 1, EPI_RESID = 2, EPI_SWIGLU = 3, EPI_QKV = 4 };
 enum { MODE_LINEAR = 0, MODE_ATTN = 1 };
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 
-// The sync block (uint32 words), zeroed by the set-up kernel.  Every item counter has a
+// ---- packed weight layout ------------------------------------------------------
+// The unit is the 1 KiB A operand of v_mfma_f32_16x16x32_f16: 16 output features (a
+// "tile") by 32 input features (a "k-step"), 16 bytes per lane in lane order.  Tiles are
+// stored in blocks of `blk` tiles, k-step major inside a block: the tiles a wavefront
+// streams together at one k-step lie side by side.  Work is shared out in row blocks
+// ("items") of rb tiles: wide matrices (many tiles per compute unit) have rb = 1 - a
+// workgroup owns whole tiles and streams several of them over the whole K range - and are
+// stored in blocks of 8 tiles; narrow ones have rb = 4 = blk - a workgroup streams a k range
+// of four tiles at once, so that the x operand it reads is shared by 64 output features.
+constexpr int kRbNarrow = 4;
+constexpr int kWideBlock = 8;
+constexpr int kWideTiles = 640;   // from this many tiles on, rb = 1
+
+struct WLayout {
+    int rb;        // tiles per item
+    int blk;       // tiles per storage block
+    int ntiles;    // 16-row tiles (last one zero padded)
+    int nitems;    // row blocks (last one padded with zero tiles)
+    int nblocks;   // storage blocks (last one padded with zero tiles)
+    int nks;       // 32-column k-steps (last one zero padded)
+};
+
+__host__ __device__ inline WLayout w_layout(int N, int K)
+{
+    WLayout l;
+    l.ntiles = (N + 15) / 16;
+    l.rb = l.ntiles >= kWideTiles ? 1 : kRbNarrow;
+    l.blk = l.rb == 1 ? kWideBlock : kRbNarrow;
+    l.nitems = (l.ntiles + l.rb - 1) / l.rb;
+    l.nblocks = (l.ntiles + l.blk - 1) / l.blk;
+    l.nks = (K + 31) / 32;
+    return l;
+}
+
+// index, in 16-byte pieces, of lane `lane` of the block (tile t, k-step s)
+__host__ __device__ inline size_t w_piece(const WLayout& l, int t, int s, int lane)
+{
+    return ((((size_t)(t / l.blk) * l.nks + s) * l.blk + (t % l.blk)) << 6) + lane;
+}
+__host__ __device__ inline size_t w_pieces(const WLayout& l) { return ((size_t)l.nblocks * l.blk * l.nks) << 6; }
+
+// ---- packed activation layout ----------------------------------------------------
+// Activations that feed a linear layer are kept as MFMA B operands: per k-step (32
+// columns) and row tile (16 rows) one 1 KiB block in lane order; lane (row % 16) +
+// 16 * ((col % 32) / 8) holds 8 consecutive columns of one row.  mtp = row tiles (Mpad/16).
+__host__ __device__ inline size_t xpk_index(int m, int k, int mtp)
+{
+    return ((((size_t)(k >> 5) * mtp + (m >> 4)) << 6) + (((k & 31) >> 3) << 4) + (m & 15)) * 8 + (k & 7);
+}
+__host__ __device__ inline size_t xpk_halves(int K, int mtp) { return (size_t)((K + 31) / 32) * mtp * 512; }
+
+// The sync block (uint32 words), zeroed by the set-up kernel.  Every counter has a
 // 128-byte line of its own (kCntStride words apart): the workgroups of one item poll and
-// bump it without disturbing the others.  A linear layer's shared row slice is counted on
-// the line of the first workgroup that has a part of it (one line per workgroup is enough);
+// bump it without disturbing the others.  A linear layer's shared row block is counted on
+// the line of the first work share that has a part of it (one line per share is enough);
 // each kind of linear layer has an array of its own, reused layer after layer by epoch.
 constexpr int kSyncStatus = 1;    // 0 = ok, else the code of the wait that gave up
 constexpr int kCntStride = 32;
+constexpr int kMaxShares = 2048;  // work shares of one linear launch (workgroups x passes)
 constexpr int kSyncCnt = 32;                          // first counter line
-constexpr int kCntQkv = kSyncCnt;                     // up to 512 workgroups each
-constexpr int kCntWo = kCntQkv + 512 * kCntStride;
-constexpr int kCntGu = kCntWo + 512 * kCntStride;
-constexpr int kCntDown = kCntGu + 512 * kCntStride;
-constexpr int kCntLm = kCntDown + 512 * kCntStride;   // LM head and stand-alone linear calls
-constexpr int kCntAttn = kCntLm + 1024 * kCntStride;  // up to 256 heads
+constexpr int kCntQkv = kSyncCnt;
+constexpr int kCntWo = kCntQkv + kMaxShares * kCntStride;
+constexpr int kCntGu = kCntWo + kMaxShares * kCntStride;
+constexpr int kCntDown = kCntGu + kMaxShares * kCntStride;
+constexpr int kCntLm = kCntDown + kMaxShares * kCntStride;   // LM head and stand-alone linear calls
+constexpr int kCntAttn = kCntLm + kMaxShares * kCntStride;   // up to 256 heads
 constexpr int kSyncWords = kCntAttn + 256 * kCntStride;
 
 struct FusedArgs {
@@ -40,39 +88,49 @@ struct FusedArgs {
     float eps, scale_log2e;
     // scratch (device)
     uint32_t* sync;        // kSyncWords
-    float* part;           // GEMM partial slots: [G][2][up to 16*MT KiB]
+    float* part;           // linear layers: partial sums of shared row blocks, two slots per work share
     float* o_part;         // attention partial states, one per workgroup: [G][Mpad][d]
     float* ml_part;        // [G][Mpad][2]
     float* x;              // residual stream [M, H] fp32
-    half_t* xg16;          // fp16(x * gain of the next RMSNorm / 16) [M, H]: GEMM input
+    half_t* xg16;          // fp16(x * gain of the next RMSNorm / 16), packed activation layout
     float* ss;             // sums of squares per 16-column tile: [H/16][Mpad]
     half_t* q16;           // [M, H]
-    half_t* o16;           // [M, H]
-    half_t* a16;           // [M, F]
+    half_t* o16;           // attention output, packed activation layout
+    half_t* a16;           // SwiGLU output [M, F], packed activation layout
     const float2* rope;    // (cos, sin) [M][d/2]
     const uint64_t* mask;  // ancestor masks [M][2]
     // linear-layer launch
     const half8* lin_W;
-    const half_t* lin_x;
+    const half_t* lin_x;   // input, packed activation layout
     void* lin_y;
     int lin_N, lin_K, lin_epi;
-    int lin_rs;            // row split of the 256-row groups (1, 2 or 4; capped by the LDS at M > 64)
+    int lin_slots;         // wide matrices: row tiles a work share handles at once (template choice)
+    int lin_passes;        // work shares per workgroup
     int lin_rscale;        // the input is xg16: scale output row m by the RMSNorm factor of x[m]
     const half_t* lin_gnext;   // EPI_RESID: gain of the norm that follows (xg16 is rewritten)
     half_t *lin_kc, *lin_vc;   // EPI_QKV: the layer's cache
-    int lin_cnt;           // which group-counter array of the sync block this call uses
+    int lin_cnt;           // which counter array of the sync block this call uses
     uint32_t lin_epoch;    // how often that array was used since it was zeroed
     uint32_t att_epoch;    // same for the attention head counters
-    int64_t lin_ldx, lin_ldy;
+    int64_t lin_ldy;
     // attention launch
     const half_t *att_q, *att_k, *att_v;
     half_t* att_out;
+    int att_out_packed;    // output in the packed activation layout (else row-major [M, nh, d])
 };
 
 ghd_status launch_fused(const FusedArgs& a, hipStream_t st);
+ghd_status launch_linear(const FusedArgs& a, hipStream_t st);
+ghd_status launch_resident_checked(const void* kernel, int key, size_t lds, int* grid);
 int fused_grid_size();
 void share_on_host(int items, int per_item, int j, int G, int item, int* out);
 void attn_share_on_host(int nh, int ntile, int j, int G, int head, int* out);
+
+// How a linear layer is cut for G workgroups and row tiles of M: passes (work shares per
+// workgroup) and, for wide matrices, the most row tiles one share touches.  Host only.
+struct LinPlan { int slots, passes; };
+bool plan_linear(int M, int N, int K, int G, LinPlan* out);
+size_t linear_part_floats(int M, int G);
 
 // setup kernel: zero the sync block, tree tables, and (optionally) the residual stream
 // with its sums of squares and its gain-scaled fp16 image
@@ -80,6 +138,8 @@ ghd_status launch_fused_setup(uint32_t* sync, const int32_t* parent, int M, int 
                               float rope_base, uint64_t* mask, float2* rope, float* x,
                               const half_t* x_in16, int H, float* ss, const half_t* gain,
                               half_t* xg16, hipStream_t st);
+// row-major fp16 [M, ldx] -> packed activation layout (columns K.. of the last k-step zero)
+ghd_status launch_pack_x(half_t* dst, const half_t* src, int M, int Mpad, int K, int64_t ldx, hipStream_t st);
 
 ghd_status launch_pack2(void* dst, const void* src, int N, int K, int kind, int d, hipStream_t st);
 size_t packed_bytes2(int N, int K);

@@ -1,0 +1,513 @@
+// The skinny linear layer: y[M, N] = x[M, K] W[N, K]^T with M <= 128 rows, one launch of one
+// 512-thread workgroup per compute unit.
+//
+// The step re-reads every weight once per decoding step and is bound by that stream
+// (Ghidorah, sections 2.1 and 2.2.2), so the kernel is built around it: the k-steps of the
+// packed matrix (see w_layout) form one sequence, cut into equal contiguous shares whatever
+// the shape.  A share covers a k range of one or more row blocks.  Its eight wavefronts
+// split the k range between them; each wavefront streams its k-steps of ALL the share's
+// row tiles (W is the MFMA A operand, fetched with non-temporal 128-bit loads straight
+// into registers, a few k-steps ahead) together with the matching x fragments (the B
+// operand, read as it lies in the packed activation layout, from the L2), and keeps one
+// fp32 accumulator fragment per (row tile, 16 rows of x).  There is no LDS staging and no
+// barrier inside the stream: the wavefronts run independently until their k ranges end.
+// Then the eight partial fragments of every tile are added up through LDS, in wavefront
+// order, and the reducing wavefront runs the layer's element-wise epilogue (residual add +
+// sums of squares for the next RMSNorm, rotary embedding + KV append, SwiGLU) - or, for a
+// row block whose k range is shared with other shares, stores the partial sum; those
+// blocks are finished cooperatively at the end of the launch, parts added in index order,
+// so results never depend on timing.
+//
+// x traffic: a share that holds R row tiles reads 16 * R weight rows and M rows of x per
+// k-step, all from the L2 except the weights.  Wide matrices (rb = 1) give every share
+// several whole tiles over the whole K range (x is read once per share, almost nothing is
+// exchanged); narrow ones (rb = 4) give it a k range of four tiles.
+#pragma once
+#include "persist.h"
+
+#include <type_traits>
+
+namespace ghd {
+
+struct GemmOp {
+    const half8* W;
+    WLayout lay;
+    int N, K;
+    int epi;
+    const half8* in;     // packed activation layout, Mpad rows
+    bool rscale;         // input is xg16: multiply output row m by 16 * rsqrt(mean x[m]^2 + eps)
+    const half_t* gnext; // RESID: gain of the next RMSNorm (xg16 is rewritten), or nullptr
+    void* out;           // STORE: y;  RESID: x;  SWIGLU: a16
+    int64_t ldo;
+    half_t *kc, *vc;     // QKV: this layer's cache
+    uint32_t* cnt;       // the operation's counters
+    uint32_t epoch;      // how many times these counters were used before (layer index)
+    int passes;          // shares per workgroup
+};
+
+constexpr float kXgScale = 0.0625f;   // xg16 = fp16(x * g * kXgScale)
+
+#ifndef GHD_RING_REGS
+#define GHD_RING_REGS 80     // registers the load ring of a wavefront may take
+#endif
+#ifndef GHD_RING_KIB
+#define GHD_RING_KIB 4       // weight bytes a wavefront keeps in flight, in KiB (more was measured slower)
+#endif
+// k-steps in flight per wavefront: limited by registers (accumulators + the ring) and by
+// what the stream needs (a few KiB per wavefront: loads return in issue order, and a long
+// queue only delays the x fragments behind it)
+__host__ __device__ constexpr int pd_of(int MT, int R)
+{
+    int by_regs = GHD_RING_REGS / ((R + MT) * 4);
+    int by_bytes = (GHD_RING_KIB + R - 1) / R;
+    int pd = by_regs < by_bytes ? by_regs : by_bytes;
+    return pd < 1 ? 1 : (pd > 8 ? 8 : pd);
+}
+
+// ---------------------------------------------------------------------------
+// epilogue of one 16x16 output fragment: lane (c, g4) holds y[m][n0 .. n0+3]
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, floatx4 v, int m, int n0,
+                                         int lane, const float* s_rinv)
+{
+    const bool mok = m < a.M;
+    const int mtp = a.Mpad >> 4;
+    if (op.rscale) v *= s_rinv[m];
+    if (op.epi == EPI_STORE_F32) {
+        if (!mok) return;
+        float* o = (float*)op.out + (size_t)m * op.ldo + n0;
+        if (n0 + 3 < op.N && (op.ldo & 3) == 0) *(floatx4*)o = v;
+        else
+            for (int r = 0; r < 4; ++r)
+                if (n0 + r < op.N) o[r] = v[r];
+    } else if (op.epi == EPI_STORE_F16) {
+        if (!mok) return;
+        half_t* o = (half_t*)op.out + (size_t)m * op.ldo + n0;
+        for (int r = 0; r < 4; ++r)
+            if (n0 + r < op.N) o[r] = (half_t)v[r];
+    } else if (op.epi == EPI_RESID) {
+        // x += y; sums of squares of the new x over this tile's 16 columns, per row
+        float s = 0.f;
+        if (mok && n0 < op.N) {
+            floatx4* xp = (floatx4*)((float*)op.out + (size_t)m * op.ldo + n0);
+            floatx4 xn = *xp + v;
+            *xp = xn;
+            s = xn[0] * xn[0] + xn[1] * xn[1] + xn[2] * xn[2] + xn[3] * xn[3];
+            if (op.gnext) {
+                half4 gv = *(const half4*)(op.gnext + n0), o;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[r] = (half_t)(xn[r] * (float)gv[r] * kXgScale);
+                *(half4*)(a.xg16 + xpk_index(m, n0, mtp)) = o;
+            }
+        }
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if (lane < 16 && n0 < op.N) a.ss[(size_t)(n0 >> 4) * a.Mpad + m] = s;
+    } else if (op.epi == EPI_SWIGLU) {
+        // packed rows: (gate f, gate f+1, up f, up f+1)
+        if (!mok) return;
+        int f = (n0 >> 4) * 8 + ((n0 & 15) >> 2) * 2;
+        if (f >= a.F) return;
+        float a0 = v[0] / (1.0f + expf(-v[0])) * v[2];
+        float a1 = v[1] / (1.0f + expf(-v[1])) * v[3];
+        half2_ h = {(half_t)a0, (half_t)a1};
+        *(half2_*)((half_t*)op.out + xpk_index(m, f, mtp)) = h;
+    } else {   // EPI_QKV: packed rows of a head: (j, j+1, j+d/2, j+1+d/2)
+        if (!mok || n0 >= op.N) return;
+        const int H = a.H, d = a.d, hd = a.d >> 1;
+        int part = n0 / H, hn = n0 - part * H;
+        int head = hn / d, ph = hn - head * d;
+        int jj = (ph >> 2) * 2;
+        float o0 = v[0], o1 = v[1], o2 = v[2], o3 = v[3];
+        if (part < 2) {
+            float2 cs0 = a.rope[(size_t)m * hd + jj], cs1 = a.rope[(size_t)m * hd + jj + 1];
+            o0 = v[0] * cs0.x - v[2] * cs0.y;
+            o2 = v[2] * cs0.x + v[0] * cs0.y;
+            o1 = v[1] * cs1.x - v[3] * cs1.y;
+            o3 = v[3] * cs1.x + v[1] * cs1.y;
+        }
+        if (part == 2) {
+            // V is kept channel-major: row kv_len + m of channels jj, jj+1, jj+d/2, jj+1+d/2
+            half_t* col = op.vc + (size_t)head * a.v_stride_head + (size_t)(a.kv_len + m);
+            col[(size_t)jj * a.v_stride_ch] = (half_t)o0;
+            col[(size_t)(jj + 1) * a.v_stride_ch] = (half_t)o1;
+            col[(size_t)(jj + hd) * a.v_stride_ch] = (half_t)o2;
+            col[(size_t)(jj + 1 + hd) * a.v_stride_ch] = (half_t)o3;
+            return;
+        }
+        half_t* dst = (part == 0)
+                          ? a.q16 + (size_t)m * H + head * d + jj
+                          : op.kc + (size_t)head * a.stride_head + (size_t)(a.kv_len + m) * a.stride_tok + jj;
+        half2_ lo = {(half_t)o0, (half_t)o1}, hi = {(half_t)o2, (half_t)o3};
+        *(half2_*)dst = lo;
+        *(half2_*)(dst + hd) = hi;
+    }
+}
+
+// keeps the compiler from moving memory operations, MFMAs or anything else across this point
+// (a load ring only works if its loads are issued where they are written)
+__device__ __forceinline__ void pin_order()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// MT = 16-row tiles of x (Mpad / 16).  R = weight tiles streamed together.  RB = tiles per
+// row block of the packed matrix: RB == 1, a share's R slots are consecutive tiles, each
+// with its own k range (the first and the last may be shared with neighbouring shares);
+// RB == 4 (== R), the slots are the four tiles of one row block, all with one k range, and a
+// share that touches several blocks streams them one after the other.
+template <int MT, int R, int RB>
+__device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op, Ctx& cx)
+{
+    static_assert(RB == 1 || R == RB, "narrow matrices: the slots are the tiles of one row block");
+    constexpr int NF = R * MT;                     // accumulator fragments per wavefront
+    constexpr int FR = NF < 16 ? NF : 16;          // fragments reduced per round through LDS
+    constexpr int PD = pd_of(MT, R);
+    constexpr int NFI = RB * MT;                   // fragments of one row block
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, g4 = lane >> 4;
+    const size_t lane16 = (size_t)(uint32_t)(lane * 16);   // this lane's 16 bytes of a 1 KiB block
+    floatx4* red = (floatx4*)cx.lds;                       // [8][FR][64]
+    float* s_rinv = (float*)(cx.lds + 8 * FR * 1024);      // 128 floats
+    float* s_tmp = s_rinv + 128;                           // 1024 floats
+    const int nks = op.lay.nks;
+    const int L = cx.G * op.passes;
+    const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    // ---- RMSNorm factor per row from the per-tile sums of squares ss[tile][Mpad]:
+    //      thread (rq, part) adds 4 rows of every P-th tile, lanes of a wavefront that share
+    //      rq are combined by shuffles, the 8 wavefronts through LDS; fixed order throughout.
+    bool rinv_ready = !op.rscale;
+    auto compute_rinv = [&]() {
+        const int n_ss = op.K >> 4;
+        const int RQ = a.Mpad >> 2, P = kFT / RQ;
+        const int rq = tid % RQ, part = tid / RQ;
+        floatx4 s4 = {0.f, 0.f, 0.f, 0.f};
+        for (int t0 = part; t0 < n_ss; t0 += 8 * P) {
+            floatx4 sst[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                sst[q] = *(const floatx4*)(a.ss + (size_t)min(t0 + q * P, n_ss - 1) * a.Mpad + rq * 4);
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (t0 + q * P < n_ss) s4 += sst[q];
+        }
+        for (int off = RQ; off < 64; off <<= 1) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s4[r] += __shfl_xor(s4[r], off);
+        }
+        if (lane < RQ) *(floatx4*)(s_tmp + (wave * RQ + lane) * 4) = s4;
+        __syncthreads();
+        if (tid < a.Mpad) {
+            float tot = 0.f;
+            for (int w = 0; w < 8; ++w) tot += s_tmp[(w * RQ + (tid >> 2)) * 4 + (tid & 3)];
+            s_rinv[tid] = (1.0f / kXgScale) / sqrtf(tot / (float)op.K + a.eps);
+        }
+        __syncthreads();
+        rinv_ready = true;
+    };
+
+    // Slot 0 of a share holds the partial of the row block its range begins in, slot 1 that
+    // of the block it ends in (when that is another one); blocks in between are whole.
+    auto slot_of = [&](const Share& sh, int ls, int item) -> float* {
+        return a.part + ((size_t)ls * 2 + (sh.begins_in(ls, item) ? 0 : 1)) * (size_t)(NFI * 256);
+    };
+    // A shared block is counted on the line of its first part (a share is the first part of
+    // at most one shared block: the one its range ends in).
+    auto counter_of = [&](int first) { return op.cnt + first * kCntStride; };
+
+    // ---- one group of R tile slots streamed together.  RB == 1: the row blocks (= tiles)
+    //      item0 .. item1 of share ls, slot 0 = item0, slot 1 = item1, slots 2.. the tiles
+    //      in between.  RB == 4: the tiles of row block item0 (item1 == item0).
+    auto run_group = [&](const Share& sh, int ls, int item0, int item1) {
+        auto item_of = [&](int t) { return RB == 1 ? (t == 0 ? item0 : (t == 1 ? item1 : item0 + t - 1)) : item0; };
+        auto valid_of = [&](int t) {
+            return RB == 1 ? (t == 0 || (t == 1 ? item1 > item0 : item0 + t - 1 < item1)) : true;
+        };
+        // k range of the slot (empty: the slot is unused, and its loads re-read slot 0's first
+        // block) and index of the 1 KiB block of its k-step 0
+        int s_k0[R], s_k1[R], s_blk[R];
+        int kmin = nks, kmax = 0;
+#pragma unroll
+        for (int t = 0; t < R; ++t) {
+            const int item = item_of(t);
+            const bool valid = valid_of(t);
+            const int ai = valid ? item : item0;
+            const int k0 = max(sh.c0 - ai * nks, 0), k1 = min(sh.c1 - ai * nks, nks);
+            s_k0[t] = k0;
+            s_k1[t] = valid ? k1 : k0;
+            s_blk[t] = RB == 1 ? (ai >> 3) * nks * kWideBlock + (ai & (kWideBlock - 1)) : ai * nks * RB + t;
+            if (valid) {
+                kmin = min(kmin, k0);
+                kmax = max(kmax, k1);
+            }
+        }
+        // this wavefront's k-steps
+        const int n = kmax - kmin;
+        const int ws = kmin + n * wave / 8, we = kmin + n * (wave + 1) / 8;
+        const int s_hi = max(we - 1, kmin);       // loads never go past the wavefront's last k-step
+
+        half8 wr[PD][R], xr[PD][MT];
+        floatx4 acc[R][MT];
+#pragma unroll
+        for (int t = 0; t < R; ++t)
+#pragma unroll
+            for (int b = 0; b < MT; ++b) acc[t][b] = (floatx4){0.f, 0.f, 0.f, 0.f};
+
+        // All loads are unconditional (clamped addresses): the compiler's wait counts then
+        // stay exact and the queue is never drained inside the loop.  Blocks outside a
+        // slot's or the wavefront's range are re-reads of a block that is needed anyway;
+        // they are zeroed before use.
+        auto load = [&](auto slot, int s) {
+            constexpr int p = decltype(slot)::value;
+            const int sl = min(s, s_hi);
+            const char* xq = (const char*)op.in + ((size_t)(sl * MT) << 10);
+#pragma unroll
+            for (int b = 0; b < MT; ++b) xr[p][b] = *(const half8*)(xq + (b << 10) + lane16);
+#pragma unroll
+            for (int t = 0; t < R; ++t) {
+                const int st = min(max(sl, s_k0[t]), max(s_k1[t] - 1, s_k0[t]));
+                const char* wq = (const char*)op.W + ((size_t)(s_blk[t] + st * (RB == 1 ? kWideBlock : RB)) << 10);
+                wr[p][t] = __builtin_nontemporal_load((const half8*)(wq + lane16));
+            }
+        };
+        // MASKED: blocks outside a slot's or the wavefront's k range, and columns past K in the
+        // last k-step, count as zeros.  The unmasked form is for k-steps where every slot is
+        // inside its range.
+        auto compute = [&](auto masked, auto slot, int s) {
+            constexpr int p = decltype(slot)::value;
+            constexpr bool MASKED = decltype(masked)::value;
+            half8 xf[MT];
+            if constexpr (MASKED) {
+                const bool kok = s * 32 + g4 * 8 < op.K;
+#pragma unroll
+                for (int b = 0; b < MT; ++b) xf[b] = kok ? xr[p][b] : zero8;
+            } else {
+#pragma unroll
+                for (int b = 0; b < MT; ++b) xf[b] = xr[p][b];
+            }
+#pragma unroll
+            for (int t = 0; t < R; ++t) {
+                half8 wv = wr[p][t];
+                if constexpr (MASKED) {
+                    const bool act = s >= s_k0[t] && s < s_k1[t] && s < we;
+                    wv = act ? wv : zero8;
+                }
+#pragma unroll
+                for (int b = 0; b < MT; ++b)
+                    acc[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wv, xf[b], acc[t][b], 0, 0, 0);
+            }
+        };
+        auto ring = [&](auto self, auto masked, auto slot, int s) {
+            constexpr int p = decltype(slot)::value;
+            if constexpr (p < PD) {
+                compute(masked, slot, s + p);
+                pin_order();
+                load(slot, s + p + PD);
+                pin_order();
+                self(self, masked, std::integral_constant<int, p + 1>{}, s);
+            }
+        };
+        auto prologue = [&](auto self, auto slot) {
+            constexpr int p = decltype(slot)::value;
+            if constexpr (p < PD) {
+                load(slot, ws + p);
+                pin_order();
+                self(self, std::integral_constant<int, p + 1>{});
+            }
+        };
+        prologue(prologue, std::integral_constant<int, 0>{});
+        // The norm factors are only needed by the epilogues, but their loads are cheapest here:
+        // they arrive together with the first ring, which the wavefront has to wait for anyway.
+        if (!rinv_ready) compute_rinv();
+        {
+            // does every k-step of this wavefront lie inside every used slot's range?  (What an
+            // unused slot accumulates is never looked at.)
+            bool plain = (op.K & 31) == 0 || we < nks;
+#pragma unroll
+            for (int t = 0; t < R; ++t) plain = plain && (s_k1[t] == s_k0[t] || (s_k0[t] <= ws && s_k1[t] >= we));
+            int s = ws;
+            if (plain)
+                for (; s + PD <= we; s += PD) ring(ring, std::false_type{}, std::integral_constant<int, 0>{}, s);
+            for (; s < we; s += PD) ring(ring, std::true_type{}, std::integral_constant<int, 0>{}, s);
+        }
+
+        // ---- the eight k slices are added up through LDS, FR fragments per round; wavefront
+        //      w reduces fragments w, w + 8 of the round (in wavefront order) and finishes them.
+        //      The fragments of row blocks shared with other shares come first (slots 0 and 1 of
+        //      a wide matrix; all of a narrow one): their partial sums are stored and signalled
+        //      as soon as they are complete, so that they are on their way while the rest of the
+        //      share is finished.
+        bool any_shared = false;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int item = k ? item1 : item0;
+            if (k && item1 == item0) break;
+            any_shared = any_shared || sh.first_of(item) != sh.last_of(item);
+        }
+        constexpr int kSignalRound = RB == 1 ? 0 : (NF - 1) / FR;
+        static_assert(RB != 1 || 2 * MT <= FR || NF <= FR, "the shared slots' fragments are in the first round");
+#pragma unroll
+        for (int r0 = 0; r0 < NF; r0 += FR) {
+#pragma unroll
+            for (int ff = 0; ff < FR; ++ff)
+                if (r0 + ff < NF) red[(wave * FR + ff) * 64 + lane] = acc[(r0 + ff) / MT][(r0 + ff) % MT];
+            __syncthreads();
+            for (int ff = wave; ff < FR && r0 + ff < NF; ff += 8) {
+                floatx4 v = red[ff * 64 + lane];
+#pragma unroll
+                for (int w = 1; w < 8; ++w) v += red[(w * FR + ff) * 64 + lane];
+                const int f = r0 + ff, t = f / MT, b = f % MT;
+                if (!valid_of(t)) continue;
+                const int item = item_of(t);
+                const int tile = RB == 1 ? item : item * RB + t;
+                if (sh.first_of(item) == sh.last_of(item))
+                    epilogue(a, op, v, b * 16 + c, tile * 16 + g4 * 4, lane, s_rinv);
+                else
+                    *(floatx4*)(slot_of(sh, ls, item) + ((size_t)((RB == 1 ? 0 : t) * MT + b) * 64 + lane) * 4) = v;
+            }
+            if (any_shared && r0 / FR == kSignalRound) wait_own_stores();   // the partials are in the L2
+            __syncthreads();
+            if (any_shared && r0 / FR == kSignalRound && tid == 0) {
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const int item = k ? item1 : item0;
+                    if (k && item1 == item0) break;
+                    const int first = sh.first_of(item);
+                    if (first != sh.last_of(item)) atomicAdd(counter_of(first), 1u);
+                }
+            }
+        }
+        return any_shared;
+    };
+
+    // ---- the shares of this workgroup, one after the other
+    bool shared_any = false;
+    for (int p = 0; p < op.passes; ++p) {
+        const int ls = cx.j * op.passes + p;
+        const Share sh = make_share(op.lay.nitems, nks, ls, L);
+        if (sh.c0 >= sh.c1) continue;
+        const int it0 = sh.c0 / nks, it1 = (sh.c1 - 1) / nks;
+        if constexpr (RB == 1) {
+            shared_any = run_group(sh, ls, it0, it1) || shared_any;
+        } else {
+            for (int it = it0; it <= it1; ++it) shared_any = run_group(sh, ls, it, it) || shared_any;
+        }
+    }
+    if (!shared_any) return;
+
+    // ---- cooperative finish of the shared row blocks this workgroup has parts of.  All its
+    //      partial sums were stored and signalled before it waits for anybody else's.
+    for (int p = 0; p < op.passes; ++p) {
+        const int ls = cx.j * op.passes + p;
+        const Share sh = make_share(op.lay.nitems, nks, ls, L);
+        if (sh.c0 >= sh.c1) continue;
+        const int it0 = sh.c0 / nks, it1 = (sh.c1 - 1) / nks;
+        for (int k = 0; k < 2; ++k) {
+            const int item = k ? it1 : it0;
+            if (k && it1 == it0) break;
+            const int first = sh.first_of(item), last = sh.last_of(item);
+            if (first == last) continue;
+            const int np = last - first + 1, me = ls - first;
+            if (tid == 0) bounded_wait(a.sync, counter_of(first), (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
+            __syncthreads();
+            const int f0 = NFI * me / np, f1 = NFI * (me + 1) / np;
+            for (int f = f0 + wave; f < f1; f += 8) {
+                // Sum the parts in index order (fixed order: the result does not depend on
+                // timing), eight loads in flight at a time.
+                const size_t foff = ((size_t)f * 64 + lane) * 4;
+                floatx4 v = *(const floatx4*)(slot_of(sh, first, item) + foff);
+                for (int p0 = 1; p0 < np; p0 += 8) {
+                    floatx4 t[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (p0 + q < np) t[q] = *(const floatx4*)(slot_of(sh, first + p0 + q, item) + foff);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (p0 + q < np) v += t[q];
+                }
+                const int tile = RB == 1 ? item : item * RB + f / MT, b = f % MT;
+                epilogue(a, op, v, b * 16 + c, tile * 16 + g4 * 4, lane, s_rinv);
+            }
+        }
+    }
+}
+
+template <int MT, int R, int RB>
+__global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t touched = touch_kernel_arguments();
+    Ctx cx = make_ctx(a, lds);
+    GemmOp op;
+    op.W = a.lin_W;
+    op.N = a.lin_N;
+    op.K = a.lin_K;
+    op.lay = w_layout(a.lin_N, a.lin_K);
+    op.epi = a.lin_epi;
+    op.in = (const half8*)a.lin_x;
+    op.rscale = a.lin_rscale != 0;
+    op.gnext = a.lin_gnext;
+    op.out = a.lin_y;
+    op.ldo = a.lin_ldy;
+    op.kc = a.lin_kc;
+    op.vc = a.lin_vc;
+    op.cnt = a.sync + a.lin_cnt;
+    op.epoch = a.lin_epoch;
+    op.passes = a.lin_passes;
+    gemm_phase<MT, R, RB>(a, op, cx);
+    // (keeps the early reads alive; never true: lin_N is positive)
+    if (touched == 0x9e3779b9u && a.lin_N < 0) a.sync[kSyncStatus] = 4u;
+}
+
+template <int MT, int R>
+constexpr size_t linear_lds_bytes()
+{
+    return 8 * (size_t)(R * MT < 16 ? R * MT : 16) * 1024 + (128 + 1024) * sizeof(float);
+}
+
+template <int MT, int R, int RB>
+static ghd_status launch_linear_t(const FusedArgs& a, hipStream_t st)
+{
+    int G = 0;
+    const size_t lds = linear_lds_bytes<MT, R>();
+    ghd_status s = launch_resident_checked((const void*)k_linear<MT, R, RB>, (MT * 16 + R) * 8 + RB, lds, &G);
+    if (s) return s;
+    hipLaunchKernelGGL((k_linear<MT, R, RB>), dim3(G), dim3(kFT), lds, st, a);
+    return check_launch();
+}
+
+// the instantiations of one M range; slots = row tiles a share handles at once
+template <int MT>
+ghd_status launch_linear_mt(const FusedArgs& a, hipStream_t st)
+{
+    const WLayout lay = w_layout(a.lin_N, a.lin_K);
+    if (lay.rb != 1) return launch_linear_t<MT, kRbNarrow, kRbNarrow>(a, st);
+    constexpr int CAP = MT <= 4 ? 8 : 4;
+    switch (a.lin_slots) {
+    case 1: return launch_linear_t<MT, 1, 1>(a, st);
+    case 2: return launch_linear_t<MT, 2, 1>(a, st);
+    case 3: return launch_linear_t<MT, 3, 1>(a, st);
+    case 4: return launch_linear_t<MT, 4, 1>(a, st);
+    default: break;
+    }
+    if constexpr (CAP >= 8) {
+        switch (a.lin_slots) {
+        case 5: return launch_linear_t<MT, 5, 1>(a, st);
+        case 6: return launch_linear_t<MT, 6, 1>(a, st);
+        case 7: return launch_linear_t<MT, 7, 1>(a, st);
+        case 8: return launch_linear_t<MT, 8, 1>(a, st);
+        default: break;
+        }
+    }
+    return GHD_ERR_SHAPE;
+}
+
+ghd_status launch_linear_mt1(const FusedArgs& a, hipStream_t st);
+ghd_status launch_linear_mt2(const FusedArgs& a, hipStream_t st);
+ghd_status launch_linear_mt4(const FusedArgs& a, hipStream_t st);
+ghd_status launch_linear_mt8(const FusedArgs& a, hipStream_t st);
+
+}  // namespace ghd

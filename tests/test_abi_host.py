@@ -59,8 +59,9 @@ def test_tree_validate(lib):
 
 
 def test_packed_size(lib):
-    assert lib.ghd_packed_weight_bytes(16, 32) == 256 * 128 * 2
-    assert lib.ghd_packed_weight_bytes(257, 129) == 512 * 256 * 2
+    assert lib.ghd_packed_weight_bytes(16, 32) == 64 * 32 * 2          # one row block of four 16-row tiles
+    assert lib.ghd_packed_weight_bytes(257, 129) == 320 * 160 * 2      # 17 tiles -> 5 row blocks, 5 k-steps
+    assert lib.ghd_packed_weight_bytes(10241, 33) == 10368 * 64 * 2    # wide: 641 tiles -> 81 blocks of 8 tiles
     assert lib.ghd_packed_weight_bytes(32000, 4096) == 32000 * 4096 * 2
     assert lib.ghd_packed_weight_bytes(22016, 4096) == 22016 * 4096 * 2
     assert lib.ghd_packed_weight_bytes(12288, 4096) == 12288 * 4096 * 2   # same bytes as row-major

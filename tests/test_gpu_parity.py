@@ -65,7 +65,10 @@ def close(got, ref, atol, rtol):
 def reference_pack(W, kind=0, d=0):
     """The packed layout written out from its definition (include/ghd.h)."""
     N, K = W.shape
-    Np, Kp = (N + 255) // 256 * 256, (K + 127) // 128 * 128
+    ntiles = (N + 15) // 16
+    rb = 8 if ntiles >= 640 else 4              # tiles per storage block
+    nitems = (ntiles + rb - 1) // rb
+    Np, Kp = nitems * rb * 16, (K + 31) // 32 * 32
     src = np.full(Np, -1, dtype=np.int64)
     for p in range(N):
         if kind == 0:
@@ -83,14 +86,16 @@ def reference_pack(W, kind=0, d=0):
     Wp = np.zeros((Np, Kp), dtype=np.uint16)
     rows = src >= 0
     Wp[rows, :K] = W.view(np.uint16)[src[rows]]
-    # [group, tile, row, kstep, kgroup, 8] -> [group, kstep, tile, kgroup, row, 8]
-    out = Wp.reshape(Np // 256, 16, 16, Kp // 32, 4, 8).transpose(0, 3, 1, 4, 2, 5)
+    # [block, tile, row, kstep, kgroup, 8] -> [block, kstep, tile, kgroup, row, 8]
+    out = Wp.reshape(nitems, rb, 16, Kp // 32, 4, 8).transpose(0, 3, 1, 4, 2, 5)
     return np.ascontiguousarray(out).reshape(-1)
 
 
 @pytest.mark.parametrize("N,K,kind,d", [(16, 32, 0, 0), (40, 72, 0, 0), (1000, 256, 0, 0),
                                         (256, 688, 0, 0), (768, 256, 1, 64), (3 * 512, 136, 1, 128),
-                                        (2 * 688, 256, 2, 0), (2 * 1376, 128, 2, 0)])
+                                        (2 * 688, 256, 2, 0), (2 * 1376, 128, 2, 0),
+                                        (10240, 64, 0, 0), (10300, 40, 0, 0), (3 * 3584, 32, 1, 128),
+                                        (2 * 5504, 64, 2, 0)])
 def test_pack_weight_bytes(B, N, K, kind, d):
     say("pack", N, K, kind, d)
     W = wl.activations(N, K, 21, tag="w", std=0.02)

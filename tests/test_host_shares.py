@@ -26,6 +26,10 @@ CASES = [
     (96, 16, 256), (172, 16, 256), (500, 8, 256),                                  # row-split variants
     (3, 2, 256), (1, 1, 256), (7, 5, 256), (300, 1, 256), (9, 1000, 256),
     (5, 3, 16), (40, 7, 24), (13, 9, 8), (11, 4, 7), (2, 50, 5),                   # small grids, also not a multiple of 8
+    # row blocks x k-steps of the packed 7B / 13B matrices (wide ones tile by tile, narrow ones in
+    # blocks of four tiles), one and two shares per workgroup
+    (768, 128, 256), (64, 128, 256), (1376, 128, 256), (64, 344, 256), (2000, 128, 512),
+    (960, 160, 256), (80, 160, 256), (1728, 160, 256), (80, 432, 256), (2000, 160, 512),
 ]
 
 
@@ -76,6 +80,39 @@ def test_share_invariants(items, per_item, G):
             continue
         for item in range(c0 // per_item + 1, (c1 - 1) // per_item):
             assert item * per_item >= c0 and (item + 1) * per_item <= c1
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 12288, 4096), (64, 4096, 4096), (64, 22016, 4096), (64, 4096, 11008),
+                                   (64, 32000, 4096), (1, 32000, 4096), (128, 22016, 4096), (128, 32000, 4096),
+                                   (64, 15360, 5120), (64, 27648, 5120), (16, 160000, 4096), (128, 16384 * 16, 64)])
+def test_linear_plan(M, N, K):
+    """The cut of a linear layer: a wide matrix (640 tiles of 16 rows or more) is cut so that no
+    share touches more row tiles than the kernel keeps accumulators for (8 up to 64 rows of x,
+    4 above), with as few shares per workgroup as that takes; a narrow one always streams one
+    block of four tiles at a time, one share per workgroup."""
+    lib = B.lib()
+    G = 256
+    out = (C.c_int * 2)()
+    rc = lib.ghd_debug_plan(M, N, K, G, out)
+    ntiles, nks = (N + 15) // 16, (K + 31) // 32
+    cap = 8 if M <= 64 else 4
+    if ntiles < 640:
+        assert rc == 0 and list(out) == [4, 1]
+        return
+
+    def most(P):
+        worst = 0
+        for j in range(G * P):
+            c0, c1 = share(lib, ntiles, nks, j, G * P)[:2]
+            if c1 > c0:
+                worst = max(worst, (c1 - 1) // nks - c0 // nks + 1)
+        return worst
+
+    feasible = [P for P in range(1, 9) if most(P) <= cap]
+    if not feasible:
+        assert rc == -1
+        return
+    assert rc == 0 and out[1] == feasible[0] and out[0] == most(feasible[0]) and 1 <= out[0] <= cap
 
 
 def attn_share(lib, nh, ntile, j, G, head):
