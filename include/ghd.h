@@ -236,6 +236,19 @@ ghd_status ghd_accept_greedy(const float *logits, const int32_t *tokens_dev,
                              int32_t *amax_dev, void *ws, size_t ws_bytes, void *stream);
 size_t ghd_accept_workspace_bytes(int M);
 
+/* ghd_accept_greedy for callers that cannot allocate or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments and results, no `ws`: the per-segment maxima go to
+ * an 8 KiB array that is part of the library's device image (one copy per GPU,
+ * held until the process ends), which fits every tree this library accepts;
+ * M > GHD_MAX_M is GHD_ERR_SHAPE as everywhere.  The call allocates nothing
+ * and frees nothing.  All calls on one GPU share that array: calls that
+ * overlap in time on one GPU (two streams, two threads) race; order them on one
+ * stream.  Nothing in the array needs clearing between calls. */
+ghd_status ghd_accept_greedy_static(const float *logits, const int32_t *tokens_dev,
+                                    const int32_t *parent_dev, int M, int V, int32_t *res_dev,
+                                    int32_t *amax_dev, void *stream);
+
 /* ---- commit of the accepted path (section 2.3: of the drafted tree only the
  *      verified tokens join the context) ---------------------------------- */
 

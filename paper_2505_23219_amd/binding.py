@@ -86,6 +86,7 @@ def lib() -> C.CDLL:
             "ghd_workspace_bytes": (sz, [vp, i32, i32]),
             "ghd_accept_greedy": (C.c_int32, [vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]),
             "ghd_accept_workspace_bytes": (sz, [i32]),
+            "ghd_accept_greedy_static": (C.c_int32, [vp, vp, vp, i32, i32, vp, vp, vp]),
             "ghd_commit_path": (C.c_int32, [vp, vp, vp, i32, i32, vp]),
             "ghd_embed": (C.c_int32, [vp, vp, vp, i32, i32, i32, vp]),
             "ghd_tree_build": (C.c_int, [vp, i32, i32, i32, vp, vp, vp]),
@@ -110,7 +111,7 @@ EXPORTS = ["ghd_status_str", "ghd_last_hip_error", "ghd_tree_validate", "ghd_tre
            "ghd_linear_workspace_bytes", "ghd_tree_attention", "ghd_attention_workspace_bytes",
            "ghd_masked_attention",
            "ghd_verify_layer", "ghd_verify_stack", "ghd_workspace_bytes", "ghd_accept_greedy",
-           "ghd_accept_workspace_bytes", "ghd_commit_path", "ghd_embed", "ghd_tree_build",
+           "ghd_accept_workspace_bytes", "ghd_accept_greedy_static", "ghd_commit_path", "ghd_embed", "ghd_tree_build",
            "ghd_choose_width",
            "ghd_draft_tokens", "ghd_draft_workspace_bytes", "ghd_spec_step",
            "ghd_spec_workspace_bytes"]
@@ -310,6 +311,17 @@ def ghd_accept_greedy(logits: torch.Tensor, tokens: torch.Tensor, parent: torch.
                                    _ptr(_dev(parent, torch.int32)), M, V, _ptr(res), _ptr(amax),
                                    _ptr(ws), ws.numel(), _stream()), "ghd_accept_greedy")
     return res, amax
+
+
+def ghd_accept_greedy_static(logits: torch.Tensor, tokens: torch.Tensor, parent: torch.Tensor,
+                             res: torch.Tensor, amax: Optional[torch.Tensor] = None) -> None:
+    """ghd_accept_greedy without a workspace (the library's own static scratch); `res` and
+    `amax` are the caller's: the call itself allocates nothing."""
+    M, V = logits.shape
+    _check(lib().ghd_accept_greedy_static(_ptr(_dev(logits, torch.float32)), _ptr(_dev(tokens, torch.int32)),
+                                          _ptr(_dev(parent, torch.int32)), M, V, _ptr(_dev(res, torch.int32)),
+                                          _ptr(amax) if amax is not None else None, _stream()),
+           "ghd_accept_greedy_static")
 
 
 def ghd_commit_path(stack: Stack, res: torch.Tensor, M: int, kv_len: int) -> None:

@@ -9,6 +9,8 @@
 //                  ties) wins and its root path is written out.
 #include "common.h"
 
+#include <mutex>
+
 namespace ghd {
 
 constexpr int kCommitMaxLayers = 48;
@@ -171,6 +173,48 @@ ghd_status launch_commit_path(void* const* k, void* const* v, int L, int nh, int
 }
 
 size_t accept_workspace_bytes() { return (size_t)GHD_MAX_M * kArgSeg * 8; }
+
+// ---- acceptance without a caller's workspace ------------------------------------
+// The per-segment maxima of ghd_accept_greedy_static live in this array instead of a
+// workspace: GHD_MAX_M rows x kArgSeg segments x (value, index) = 8 KiB, one copy per GPU
+// the library runs on, held until the process ends.  The name is a host-side stand-in; the
+// device address is looked up once per device and only that pointer is handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)GHD_MAX_M * kArgSeg * 8;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kScratchDevices = 64;
+static void* g_scratch_ptr[kScratchDevices] = {};
+static std::mutex g_scratch_mu;
+
+// device address of `scratch` on the current device (looked up on first use)
+static ghd_status static_scratch(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kScratchDevices) return hip_fail(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!p) return hip_fail(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return GHD_OK;
+}
+
+ghd_status launch_accept_static(const float* logits, const int32_t* tokens, const int32_t* parent, int M,
+                                int V, int32_t* res, int32_t* amax_out, hipStream_t st)
+{
+    if ((size_t)M * kArgSeg * 8 > kStaticScratchBytes) return GHD_ERR_SHAPE;
+    void* ws = nullptr;
+    ghd_status s = static_scratch(&ws);
+    if (s) return s;
+    // every entry the second kernel reads (rows < M) is written by the first: nothing to clear
+    return launch_accept(logits, tokens, parent, M, V, res, amax_out, ws, st);
+}
 
 ghd_status launch_accept(const float* logits, const int32_t* tokens, const int32_t* parent, int M,
                          int V, int32_t* res, int32_t* amax_out, void* ws, hipStream_t st)

@@ -568,6 +568,16 @@ ghd_status ghd_accept_greedy(const float* logits, const int32_t* tokens_dev,
                          (hipStream_t)stream);
 }
 
+ghd_status ghd_accept_greedy_static(const float* logits, const int32_t* tokens_dev,
+                                    const int32_t* parent_dev, int M, int V, int32_t* res_dev,
+                                    int32_t* amax_dev, void* stream)
+{
+    if (!logits || !tokens_dev || !parent_dev || !res_dev) return GHD_ERR_NULL;
+    if (M < 1 || M > GHD_MAX_M || V < 1) return GHD_ERR_SHAPE;
+    return launch_accept_static(logits, tokens_dev, parent_dev, M, V, res_dev, amax_dev,
+                                (hipStream_t)stream);
+}
+
 ghd_status ghd_commit_path(const ghd_model_cfg* cfg, const ghd_kv* kv_host, const int32_t* res_dev,
                            int M, int kv_len, void* stream)
 {
