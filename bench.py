@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the tree-verification step on one MI355X.
 
-A "step" is one pass of the whole hot path: ghd_verify_stack (32 decoder layers
-+ LM head over a 64-node tree against a 2048-token KV cache, 7B-shaped) followed
-by ghd_accept_greedy.  Inputs are synthetic (random fp16 weights, random cache),
+A "step" is one pass of the whole hot path: ghd_verify_stack_argmax (32 decoder
+layers + LM head over a 64-node tree against a 2048-token KV cache, 7B-shaped;
+the row argmaxes are reduced in the LM-head finish) followed by ghd_accept_path
+(greedy acceptance of the longest matching root path).  Inputs are synthetic (random fp16 weights, random cache),
 already resident in HBM when the timed region starts.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload stack7b]
@@ -164,9 +165,10 @@ def planted_loop(torch, B, wl, spec, stack, embed, heads, w, stream, steps, K, R
 
 def time_steps(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, res, amax, stream,
                steps, warmup):
+    # the row argmaxes come out of the LM-head finish; no logits are written
     def step():
-        B.ghd_verify_stack(stack, x_in, parent, kv_len, logits=logits, ws=ws)
-        B.ghd_accept_greedy(logits, tokens, parent, res=res, amax=amax, ws=aws)
+        B.ghd_verify_stack_argmax(stack, x_in, parent, kv_len, ws=ws, amax=amax)
+        B.ghd_accept_path(amax, tokens, parent, res=res)
 
     with torch.cuda.stream(stream):
         for _ in range(warmup):
@@ -191,8 +193,8 @@ def step_spread(torch, B, stack, x_in, parent, tokens, kv_len, ws, aws, logits, 
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         ev[0].record(stream)
         for i in range(steps):
-            B.ghd_verify_stack(stack, x_in, parent, kv_len, logits=logits, ws=ws)
-            B.ghd_accept_greedy(logits, tokens, parent, res=res, amax=amax, ws=aws)
+            B.ghd_verify_stack_argmax(stack, x_in, parent, kv_len, ws=ws, amax=amax)
+            B.ghd_accept_path(amax, tokens, parent, res=res)
             ev[i + 1].record(stream)
         torch.cuda.synchronize()
     us = sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(steps))
@@ -253,7 +255,7 @@ def linear_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w
     achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
     att_ms, att_n = timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, 2, steps)
     kv_bytes = 2 * 2 * s.L * s.nh * s.d * (kv_len + w.M)
-    return {"bound": "hbm", "kernel": "k_linear<MT, RS>", "achieved": round(achieved, 1),
+    return {"bound": "hbm", "kernel": "k_linear<MT, R, RB>", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": recorded_traffic(w.name), "launches_per_step": per_step,
             "avg_launch_us": round(avg_ms * 1e3, 2),

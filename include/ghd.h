@@ -210,6 +210,20 @@ ghd_status ghd_verify_stack(const ghd_model_cfg *cfg, const ghd_layer_weights *l
                             float *logits, float *x_out, void *ws, size_t ws_bytes, void *stream);
 size_t ghd_workspace_bytes(const ghd_model_cfg *cfg, int M, int kv_len);
 
+/* ghd_verify_stack for greedy acceptance (section 2.3 keeps the longest root
+ * path the model itself would have produced, which only needs every row's
+ * argmax): the finish of the LM head reduces each row's (largest logit, lowest
+ * vocabulary index) per 16-column tile, one more small launch merges the tiles
+ * into amax_dev int32 [M], and the logits need not be written at all: `logits`
+ * may be NULL (otherwise it is filled as by ghd_verify_stack).  amax_dev[i] is
+ * exactly the argmax (lowest index on ties) of the logits row this call would
+ * write.  Everything else as for ghd_verify_stack, workspace size included. */
+ghd_status ghd_verify_stack_argmax(const ghd_model_cfg *cfg, const ghd_layer_weights *layers_host,
+                                   const ghd_kv *kv_host, const void *g_final, const void *Wlm,
+                                   const void *x_in, const int32_t *parent_dev, int M, int kv_len,
+                                   int32_t *amax_dev, float *logits, float *x_out, void *ws,
+                                   size_t ws_bytes, void *stream);
+
 /* Every linear layer and every attention is one launch of a persistent kernel
  * (one workgroup per compute unit, all resident) whose workgroups hand partial
  * results to each other; every wait is bounded and gives up rather than hang
@@ -235,6 +249,12 @@ ghd_status ghd_accept_greedy(const float *logits, const int32_t *tokens_dev,
                              const int32_t *parent_dev, int M, int V, int32_t *res_dev,
                              int32_t *amax_dev, void *ws, size_t ws_bytes, void *stream);
 size_t ghd_accept_workspace_bytes(int M);
+
+/* The second half of ghd_accept_greedy on its own: the row argmaxes are given
+ * (amax_dev int32 [M], e.g. from ghd_verify_stack_argmax); validity, the deepest
+ * valid node and its root path as above.  One small launch, no workspace. */
+ghd_status ghd_accept_path(const int32_t *amax_dev, const int32_t *tokens_dev,
+                           const int32_t *parent_dev, int M, int32_t *res_dev, void *stream);
 
 /* ghd_accept_greedy for callers that cannot allocate or pass a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid

@@ -84,6 +84,9 @@ def lib() -> C.CDLL:
             "ghd_verify_stack": (C.c_int32, [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, sz,
                                              vp]),
             "ghd_workspace_bytes": (sz, [vp, i32, i32]),
+            "ghd_verify_stack_argmax": (C.c_int32, [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz,
+                                                    vp]),
+            "ghd_accept_path": (C.c_int32, [vp, vp, vp, i32, vp, vp]),
             "ghd_accept_greedy": (C.c_int32, [vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]),
             "ghd_accept_workspace_bytes": (sz, [i32]),
             "ghd_accept_greedy_static": (C.c_int32, [vp, vp, vp, i32, i32, vp, vp, vp]),
@@ -111,7 +114,7 @@ EXPORTS = ["ghd_status_str", "ghd_last_hip_error", "ghd_tree_validate", "ghd_tre
            "ghd_linear_workspace_bytes", "ghd_tree_attention", "ghd_attention_workspace_bytes",
            "ghd_masked_attention",
            "ghd_verify_layer", "ghd_verify_stack", "ghd_workspace_bytes", "ghd_accept_greedy",
-           "ghd_accept_workspace_bytes", "ghd_accept_greedy_static", "ghd_commit_path", "ghd_embed", "ghd_tree_build",
+           "ghd_accept_workspace_bytes", "ghd_accept_greedy_static", "ghd_verify_stack_argmax", "ghd_accept_path", "ghd_commit_path", "ghd_embed", "ghd_tree_build",
            "ghd_choose_width",
            "ghd_draft_tokens", "ghd_draft_workspace_bytes", "ghd_spec_step",
            "ghd_spec_workspace_bytes"]
@@ -288,6 +291,35 @@ def ghd_verify_stack(stack: Stack, x_in: torch.Tensor, parent: torch.Tensor, kv_
                                   _ptr(_dev(parent, torch.int32)), M, kv_len, _ptr(logits),
                                   _ptr(x_out), _ptr(ws), ws.numel(), _stream()), "ghd_verify_stack")
     return logits
+
+
+def ghd_verify_stack_argmax(stack: Stack, x_in: torch.Tensor, parent: torch.Tensor, kv_len: int,
+                            logits: Optional[torch.Tensor] = None, x_out: Optional[torch.Tensor] = None,
+                            ws: Optional[torch.Tensor] = None, amax: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The stack with the row argmaxes from the LM-head finish; returns amax int32 [M].
+    `logits` (optional) is filled as by ghd_verify_stack when given."""
+    cfg = stack.cfg
+    M = x_in.shape[0]
+    if amax is None:
+        amax = torch.empty(M, dtype=torch.int32, device=x_in.device)
+    if ws is None:
+        ws = workspace(lib().ghd_workspace_bytes(C.byref(cfg), M, kv_len), x_in.device)
+    _check(lib().ghd_verify_stack_argmax(C.byref(cfg), stack.lw, stack.kv, _ptr(stack.g_final),
+                                         _ptr(stack.Wlm), _ptr(_dev(x_in, torch.float16)),
+                                         _ptr(_dev(parent, torch.int32)), M, kv_len, _ptr(amax), _ptr(logits),
+                                         _ptr(x_out), _ptr(ws), ws.numel(), _stream()), "ghd_verify_stack_argmax")
+    return amax
+
+
+def ghd_accept_path(amax: torch.Tensor, tokens: torch.Tensor, parent: torch.Tensor,
+                    res: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The tree walk of greedy acceptance from given row argmaxes; returns res int32 [2+M]."""
+    M = amax.shape[0]
+    if res is None:
+        res = torch.zeros(2 + M, dtype=torch.int32, device=amax.device)
+    _check(lib().ghd_accept_path(_ptr(_dev(amax, torch.int32)), _ptr(_dev(tokens, torch.int32)),
+                                 _ptr(_dev(parent, torch.int32)), M, _ptr(res), _stream()), "ghd_accept_path")
+    return res
 
 
 def ghd_workspace_bytes(cfg: ModelCfg, M: int, kv_len: int) -> int:

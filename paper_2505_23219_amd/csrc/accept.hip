@@ -63,8 +63,44 @@ __global__ __launch_bounds__(256) void k_row_argmax(const float* __restrict__ lo
     }
 }
 
+// Row argmax from the per-tile candidates the LM-head finish leaves: one workgroup per row
+// merges `ntiles` (value, column) pairs, lowest column on ties.
+__global__ __launch_bounds__(256) void k_amax_merge(const float2* __restrict__ tbl, int ntiles, int Mpad,
+                                                    int32_t* __restrict__ amax)
+{
+    __shared__ float s_v[4];
+    __shared__ int s_i[4];
+    const int row = blockIdx.x, tid = threadIdx.x;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int t0 = tid; t0 < ntiles; t0 += 1024) {
+        float2 c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) c[u] = tbl[(size_t)min(t0 + 256 * u, ntiles - 1) * Mpad + row];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (t0 + 256 * u < ntiles) argmax_merge(bv, bi, c[u].x, __float_as_int(c[u].y));
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        float ov = __shfl_xor(bv, off);
+        int oi = __shfl_xor(bi, off);
+        argmax_merge(bv, bi, ov, oi);
+    }
+    if ((tid & 63) == 0) {
+        s_v[tid >> 6] = bv;
+        s_i[tid >> 6] = bi;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w) argmax_merge(bv, bi, s_v[w], s_i[w]);
+        amax[row] = bi;
+    }
+}
+
+// amax_in != nullptr: the row argmaxes are given (seg_v, seg_i unused)
 __global__ __launch_bounds__(128) void k_accept(const float* __restrict__ seg_v,
                                                 const int32_t* __restrict__ seg_i,
+                                                const int32_t* __restrict__ amax_in,
                                                 const int32_t* __restrict__ tokens,
                                                 const int32_t* __restrict__ parent, int M,
                                                 int32_t* __restrict__ res,
@@ -78,7 +114,9 @@ __global__ __launch_bounds__(128) void k_accept(const float* __restrict__ seg_v,
         s_tok[i] = tokens[i];
         float bv = -INFINITY;
         int bi = 0x7fffffff;
-        for (int sg = 0; sg < kArgSeg; ++sg) argmax_merge(bv, bi, seg_v[i * kArgSeg + sg], seg_i[i * kArgSeg + sg]);
+        if (amax_in) bi = amax_in[i];
+        else
+            for (int sg = 0; sg < kArgSeg; ++sg) argmax_merge(bv, bi, seg_v[i * kArgSeg + sg], seg_i[i * kArgSeg + sg]);
         s_amax[i] = bi;
         if (amax_out) amax_out[i] = s_amax[i];
     }
@@ -224,7 +262,21 @@ ghd_status launch_accept(const float* logits, const int32_t* tokens, const int32
     int32_t* seg_i = (int32_t*)(seg_v + GHD_MAX_M * kArgSeg);
     hipLaunchKernelGGL(k_row_argmax, dim3(M * kArgSeg), dim3(256), 0, st, logits, V, seg_v, seg_i);
     hipLaunchKernelGGL(k_accept, dim3(1), dim3(128), 0, st, (const float*)seg_v,
-                       (const int32_t*)seg_i, tokens, parent, M, res, amax_out);
+                       (const int32_t*)seg_i, (const int32_t*)nullptr, tokens, parent, M, res, amax_out);
+    return check_launch();
+}
+
+ghd_status launch_amax_merge(const void* tbl, int ntiles, int Mpad, int M, int32_t* amax, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_amax_merge, dim3(M), dim3(256), 0, st, (const float2*)tbl, ntiles, Mpad, amax);
+    return check_launch();
+}
+
+ghd_status launch_accept_path(const int32_t* amax, const int32_t* tokens, const int32_t* parent, int M,
+                              int32_t* res, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(128), 0, st, (const float*)nullptr, (const int32_t*)nullptr,
+                       amax, tokens, parent, M, res, (int32_t*)nullptr);
     return check_launch();
 }
 

@@ -97,13 +97,14 @@ struct Ws {
     float *part, *o_part, *ml_part, *x, *ss;
     half_t *q16, *o16, *a16, *xg16, *xpk;
     float2* rope;
+    float2* amax_tbl;   // per (16-column tile of the LM head, row): largest logit and its column
     uint64_t* mask;
     size_t bytes;
 };
 
 // what: 0 = whole model (layer / stack), 1 = linear only (K = its input features),
 // 2 = attention only
-static Ws carve(void* ws, int what, int M, int H, int F, int d, int K = 0)
+static Ws carve(void* ws, int what, int M, int H, int F, int d, int K = 0, int V = 0)
 {
     Carver cv(ws);
     Ws w = {};
@@ -125,6 +126,7 @@ static Ws carve(void* ws, int what, int M, int H, int F, int d, int K = 0)
         w.o16 = cv.take<half_t>(xpk_halves(H, mtp));
         w.a16 = cv.take<half_t>(xpk_halves(F, mtp));
         w.xg16 = cv.take<half_t>(xpk_halves(H, mtp));
+        w.amax_tbl = cv.take<float2>((size_t)((V + 15) / 16) * Mpad);
     }
     w.bytes = cv.off;
     return w;
@@ -215,6 +217,7 @@ struct LinearCall {
     const ghd_kv* kv;     // EPI_QKV
     int cnt;
     uint32_t epoch;
+    float2* amax_tbl;     // EPI_STORE_F32: per-tile row maxima (optional)
 };
 
 static ghd_status step_linear(const ghd_model_cfg* c, const Ws& w, float* x, int M, int kv_len,
@@ -238,6 +241,7 @@ static ghd_status step_linear(const ghd_model_cfg* c, const Ws& w, float* x, int
     a.lin_vc = lc.kv ? (half_t*)lc.kv->v : nullptr;
     a.lin_cnt = lc.cnt;
     a.lin_epoch = lc.epoch;
+    a.lin_amax = lc.amax_tbl;
     return timed_fused(a, st);
 }
 
@@ -265,14 +269,14 @@ static ghd_status run_layer(const ghd_model_cfg* c, const ghd_layer_weights* lw,
 {
     const int H = c->H, F = c->F;
     ghd_status s;
-    LinearCall qkv = {lw->Wqkv, 3 * H, H, EPI_QKV, w.xg16, true, nullptr, nullptr, 0, kv, kCntQkv, layer};
+    LinearCall qkv = {lw->Wqkv, 3 * H, H, EPI_QKV, w.xg16, true, nullptr, nullptr, 0, kv, kCntQkv, layer, nullptr};
     if ((s = step_linear(c, w, x, M, kv_len, qkv, st))) return s;
     if ((s = step_attention(c, w, kv, M, kv_len, layer, st))) return s;
-    LinearCall wo = {lw->Wo, H, H, EPI_RESID, w.o16, false, (const half_t*)lw->g_ffn, x, H, nullptr, kCntWo, layer};
+    LinearCall wo = {lw->Wo, H, H, EPI_RESID, w.o16, false, (const half_t*)lw->g_ffn, x, H, nullptr, kCntWo, layer, nullptr};
     if ((s = step_linear(c, w, x, M, kv_len, wo, st))) return s;
-    LinearCall gu = {lw->Wgu, 2 * F, H, EPI_SWIGLU, w.xg16, true, nullptr, w.a16, F, nullptr, kCntGu, layer};
+    LinearCall gu = {lw->Wgu, 2 * F, H, EPI_SWIGLU, w.xg16, true, nullptr, w.a16, F, nullptr, kCntGu, layer, nullptr};
     if ((s = step_linear(c, w, x, M, kv_len, gu, st))) return s;
-    LinearCall down = {lw->Wdown, H, F, EPI_RESID, w.a16, false, next_g, x, H, nullptr, kCntDown, layer};
+    LinearCall down = {lw->Wdown, H, F, EPI_RESID, w.a16, false, next_g, x, H, nullptr, kCntDown, layer, nullptr};
     return step_linear(c, w, x, M, kv_len, down, st);
 }
 
@@ -470,7 +474,7 @@ ghd_status ghd_masked_attention(void* out, const void* q, const void* k_cache, c
 size_t ghd_workspace_bytes(const ghd_model_cfg* cfg, int M, int kv_len)
 {
     if (check_cfg(cfg, M, kv_len) != GHD_OK) return 0;
-    return carve(nullptr, 0, M, cfg->H, cfg->F, cfg->d).bytes;
+    return carve(nullptr, 0, M, cfg->H, cfg->F, cfg->d, 0, cfg->V).bytes;
 }
 
 ghd_status ghd_verify_layer(const ghd_model_cfg* cfg, const ghd_layer_weights* w, const ghd_kv* kv,
@@ -486,7 +490,7 @@ ghd_status ghd_verify_layer(const ghd_model_cfg* cfg, const ghd_layer_weights* w
     if (!aligned16(ws)) return GHD_ERR_ALIGN;
     if (ws_bytes < ghd_workspace_bytes(cfg, M, kv_len)) return GHD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    Ws lw = carve(ws, 0, M, cfg->H, cfg->F, cfg->d);
+    Ws lw = carve(ws, 0, M, cfg->H, cfg->F, cfg->d, 0, cfg->V);
     // the caller's x is the residual stream itself; the set-up leaves its sums of squares
     if ((s = launch_fused_setup(lw.sync, parent_dev, M, mpad_of(M), kv_len, cfg->d, cfg->rope_base,
                                 lw.mask, lw.rope, x, nullptr, cfg->H, lw.ss, (const half_t*)w->g_attn,
@@ -495,25 +499,26 @@ ghd_status ghd_verify_layer(const ghd_model_cfg* cfg, const ghd_layer_weights* w
     return run_layer(cfg, w, kv, x, M, kv_len, lw, nullptr, 0, st);
 }
 
-ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* layers_host,
-                            const ghd_kv* kv_host, const void* g_final, const void* Wlm,
-                            const void* x_in, const int32_t* parent_dev, int M, int kv_len,
-                            float* logits, float* x_out, void* ws, size_t ws_bytes, void* stream)
+static ghd_status verify_stack_impl(const ghd_model_cfg* cfg, const ghd_layer_weights* layers_host,
+                                    const ghd_kv* kv_host, const void* g_final, const void* Wlm,
+                                    const void* x_in, const int32_t* parent_dev, int M, int kv_len,
+                                    float* logits, int32_t* amax_dev, float* x_out, void* ws,
+                                    size_t ws_bytes, void* stream)
 {
-    if (!cfg || !layers_host || !kv_host || !g_final || !Wlm || !x_in || !parent_dev || !logits)
+    if (!cfg || !layers_host || !kv_host || !g_final || !Wlm || !x_in || !parent_dev || (!logits && !amax_dev))
         return GHD_ERR_NULL;
     ghd_status s = check_cfg(cfg, M, kv_len);
     if (s) return s;
     for (int l = 0; l < cfg->L; ++l)
         if ((s = check_layer(layers_host + l, kv_host + l))) return s;
-    if (!aligned16(x_in) || !aligned16(Wlm) || !aligned16(g_final) || !aligned16(logits) ||
-        (x_out && !aligned16(x_out)))
+    if (!aligned16(x_in) || !aligned16(Wlm) || !aligned16(g_final) || (logits && !aligned16(logits)) ||
+        (x_out && !aligned16(x_out)) || ((uintptr_t)amax_dev & 3) != 0)
         return GHD_ERR_ALIGN;
     if (!ws) return GHD_ERR_WORKSPACE;
     if (!aligned16(ws)) return GHD_ERR_ALIGN;
     if (ws_bytes < ghd_workspace_bytes(cfg, M, kv_len)) return GHD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    Ws lw = carve(ws, 0, M, cfg->H, cfg->F, cfg->d);
+    Ws lw = carve(ws, 0, M, cfg->H, cfg->F, cfg->d, 0, cfg->V);
     const int H = cfg->H;
     // x = widen(x_in) with its sums of squares
     if ((s = launch_fused_setup(lw.sync, parent_dev, M, mpad_of(M), kv_len, cfg->d, cfg->rope_base,
@@ -531,10 +536,34 @@ ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* l
                                       hipMemcpyDeviceToDevice, st);
         if (e != hipSuccess) return hip_fail(e);
     }
-    // LM head on the final norm, straight into the caller's logits
+    // LM head on the final norm, straight into the caller's logits and / or into one
+    // (largest logit, lowest column) candidate per 16-column tile and row
     LinearCall lm = {Wlm, cfg->V, H, EPI_STORE_F32, lw.xg16, true, nullptr,
-                     logits, cfg->V, nullptr, kCntLm, 0};
-    return step_linear(cfg, lw, lw.x, M, kv_len, lm, st);
+                     logits, cfg->V, nullptr, kCntLm, 0, amax_dev ? lw.amax_tbl : nullptr};
+    if ((s = step_linear(cfg, lw, lw.x, M, kv_len, lm, st))) return s;
+    if (amax_dev) return launch_amax_merge(lw.amax_tbl, (cfg->V + 15) / 16, mpad_of(M), M, amax_dev, st);
+    return GHD_OK;
+}
+
+ghd_status ghd_verify_stack(const ghd_model_cfg* cfg, const ghd_layer_weights* layers_host,
+                            const ghd_kv* kv_host, const void* g_final, const void* Wlm,
+                            const void* x_in, const int32_t* parent_dev, int M, int kv_len,
+                            float* logits, float* x_out, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!logits) return GHD_ERR_NULL;
+    return verify_stack_impl(cfg, layers_host, kv_host, g_final, Wlm, x_in, parent_dev, M, kv_len, logits,
+                             nullptr, x_out, ws, ws_bytes, stream);
+}
+
+ghd_status ghd_verify_stack_argmax(const ghd_model_cfg* cfg, const ghd_layer_weights* layers_host,
+                                   const ghd_kv* kv_host, const void* g_final, const void* Wlm,
+                                   const void* x_in, const int32_t* parent_dev, int M, int kv_len,
+                                   int32_t* amax_dev, float* logits, float* x_out, void* ws,
+                                   size_t ws_bytes, void* stream)
+{
+    if (!amax_dev) return GHD_ERR_NULL;
+    return verify_stack_impl(cfg, layers_host, kv_host, g_final, Wlm, x_in, parent_dev, M, kv_len, logits,
+                             amax_dev, x_out, ws, ws_bytes, stream);
 }
 
 ghd_status ghd_step_status(const void* ws, int32_t* status_host, void* stream)
@@ -566,6 +595,14 @@ ghd_status ghd_accept_greedy(const float* logits, const int32_t* tokens_dev,
     if (ws_bytes < ghd_accept_workspace_bytes(M)) return GHD_ERR_WORKSPACE;
     return launch_accept(logits, tokens_dev, parent_dev, M, V, res_dev, amax_dev, ws,
                          (hipStream_t)stream);
+}
+
+ghd_status ghd_accept_path(const int32_t* amax_dev, const int32_t* tokens_dev, const int32_t* parent_dev,
+                           int M, int32_t* res_dev, void* stream)
+{
+    if (!amax_dev || !tokens_dev || !parent_dev || !res_dev) return GHD_ERR_NULL;
+    if (M < 1 || M > GHD_MAX_M) return GHD_ERR_SHAPE;
+    return launch_accept_path(amax_dev, tokens_dev, parent_dev, M, res_dev, (hipStream_t)stream);
 }
 
 ghd_status ghd_accept_greedy_static(const float* logits, const int32_t* tokens_dev,
@@ -674,11 +711,14 @@ size_t ghd_draft_workspace_bytes(int K, int R, int H, int V)
     return carve_draft(nullptr, H, K, V, R).bytes;
 }
 
-ghd_status ghd_draft_tokens(const void* g_final, const void* Wheads, int K, int R, int H, int V,
-                            float rms_eps, const float* x_final, const int32_t* res_dev,
-                            const int32_t* parent_dev, const int32_t* rank_dev, int M,
-                            int32_t* tokens_dev, int32_t* topk_dev, float* head_logits, void* ws,
-                            size_t ws_bytes, void* stream)
+// step_sync: the sync block of the verification pass this call belongs to (its status word
+// then covers the drafting launch too, and is not cleared again), or nullptr for a call of
+// its own, which uses and clears the sync block of its own workspace.
+static ghd_status draft_tokens_impl(const void* g_final, const void* Wheads, int K, int R, int H, int V,
+                                    float rms_eps, const float* x_final, const int32_t* res_dev,
+                                    const int32_t* parent_dev, const int32_t* rank_dev, int M,
+                                    int32_t* tokens_dev, int32_t* topk_dev, float* head_logits, void* ws,
+                                    size_t ws_bytes, void* stream, uint32_t* step_sync)
 {
     if (!g_final || !Wheads || !x_final || !res_dev || !parent_dev || !rank_dev || !tokens_dev)
         return GHD_ERR_NULL;
@@ -693,9 +733,11 @@ ghd_status ghd_draft_tokens(const void* g_final, const void* Wheads, int K, int 
     DraftWs d = carve_draft(ws, H, K, V, R);
     float* logits = head_logits ? head_logits : d.logits;
     int32_t* topk = topk_dev ? topk_dev : d.topk;
-    ghd_status s = launch_fused_setup(d.lin.sync, nullptr, 1, mpad_of(1), 0, 0, 1.f, nullptr, nullptr,
-                                      nullptr, nullptr, 0, nullptr, nullptr, nullptr, st);
-    if (s) return s;
+    ghd_status s = GHD_OK;
+    if (!step_sync &&
+        (s = launch_fused_setup(d.lin.sync, nullptr, 1, mpad_of(1), 0, 0, 1.f, nullptr, nullptr, nullptr,
+                                nullptr, 0, nullptr, nullptr, nullptr, st)))
+        return s;
     if ((s = launch_pick_norm(x_final, res_dev, M, H, g_final, rms_eps, d.n16, st))) return s;
     if ((s = launch_pack_x(d.lin.xpk, d.n16, 1, mpad_of(1), H, H, st))) return s;
     FusedArgs a = {};
@@ -704,7 +746,7 @@ ghd_status ghd_draft_tokens(const void* g_final, const void* Wheads, int K, int 
     a.M = 1;
     a.Mpad = mpad_of(1);
     a.d = 128;
-    a.sync = d.lin.sync;
+    a.sync = step_sync ? step_sync : d.lin.sync;
     a.part = d.lin.part;
     a.lin_W = (const half8*)Wheads;
     a.lin_x = d.lin.xpk;
@@ -712,7 +754,7 @@ ghd_status ghd_draft_tokens(const void* g_final, const void* Wheads, int K, int 
     a.lin_N = K * V;
     a.lin_K = H;
     a.lin_epi = EPI_STORE_F32;
-    a.lin_cnt = kCntLm;
+    a.lin_cnt = step_sync ? kCntDraft : kCntLm;
     a.lin_epoch = 0;
     a.lin_ldy = (int64_t)K * V;
     if ((s = timed_fused(a, st))) return s;
@@ -720,14 +762,23 @@ ghd_status ghd_draft_tokens(const void* g_final, const void* Wheads, int K, int 
     return launch_tree_tokens(tokens_dev, parent_dev, rank_dev, M, topk, K, R, res_dev, V, st);
 }
 
+ghd_status ghd_draft_tokens(const void* g_final, const void* Wheads, int K, int R, int H, int V,
+                            float rms_eps, const float* x_final, const int32_t* res_dev,
+                            const int32_t* parent_dev, const int32_t* rank_dev, int M,
+                            int32_t* tokens_dev, int32_t* topk_dev, float* head_logits, void* ws,
+                            size_t ws_bytes, void* stream)
+{
+    return draft_tokens_impl(g_final, Wheads, K, R, H, V, rms_eps, x_final, res_dev, parent_dev, rank_dev, M,
+                             tokens_dev, topk_dev, head_logits, ws, ws_bytes, stream, nullptr);
+}
+
 struct SpecWs {
-    void* verify;
-    void* accept;
+    void* verify;     // first, so that ghd_step_status on the step's workspace reads its status word
     void* draft;
     half_t* x16;
-    float* logits;
+    int32_t* amax;
     float* x_out;
-    size_t verify_bytes, accept_bytes, draft_bytes, bytes;
+    size_t verify_bytes, draft_bytes, bytes;
 };
 
 static SpecWs carve_spec(void* ws, const ghd_spec_model* m, int M, int kv_len)
@@ -735,14 +786,12 @@ static SpecWs carve_spec(void* ws, const ghd_spec_model* m, int M, int kv_len)
     SpecWs w = {};
     const ghd_model_cfg* c = m->cfg;
     w.verify_bytes = ghd_workspace_bytes(c, M, kv_len);
-    w.accept_bytes = ghd_accept_workspace_bytes(M);
     w.draft_bytes = ghd_draft_workspace_bytes(m->K, m->R, c->H, c->V);
     Carver cv(ws);
     w.verify = cv.take<char>(w.verify_bytes);
-    w.accept = cv.take<char>(w.accept_bytes);
     w.draft = cv.take<char>(w.draft_bytes);
     w.x16 = cv.take<half_t>((size_t)M * c->H);
-    w.logits = cv.take<float>((size_t)M * c->V);
+    w.amax = cv.take<int32_t>((size_t)GHD_MAX_M);
     w.x_out = cv.take<float>((size_t)M * c->H);
     w.bytes = cv.off;
     return w;
@@ -770,16 +819,15 @@ ghd_status ghd_spec_step(const ghd_spec_model* m, const int32_t* parent_dev, con
     const ghd_model_cfg* c = m->cfg;
     SpecWs w = carve_spec(ws, m, M, kv_len);
     if ((s = ghd_embed(w.x16, m->embed, tokens_dev, M, c->H, c->V, stream))) return s;
-    if ((s = ghd_verify_stack(c, m->layers_host, m->kv_host, m->g_final, m->Wlm, w.x16, parent_dev, M,
-                              kv_len, w.logits, w.x_out, w.verify, w.verify_bytes, stream)))
+    // the LM-head finish leaves the row argmaxes: no logits are written in a decoding step
+    if ((s = ghd_verify_stack_argmax(c, m->layers_host, m->kv_host, m->g_final, m->Wlm, w.x16, parent_dev, M,
+                                     kv_len, w.amax, nullptr, w.x_out, w.verify, w.verify_bytes, stream)))
         return s;
-    if ((s = ghd_accept_greedy(w.logits, tokens_dev, parent_dev, M, c->V, res_dev, nullptr, w.accept,
-                               w.accept_bytes, stream)))
-        return s;
+    if ((s = ghd_accept_path(w.amax, tokens_dev, parent_dev, M, res_dev, stream))) return s;
     if ((s = ghd_commit_path(c, m->kv_host, res_dev, M, kv_len, stream))) return s;
-    return ghd_draft_tokens(m->g_final, m->Wheads, m->K, m->R, c->H, c->V, c->rms_eps, w.x_out, res_dev,
-                            parent_dev, rank_dev, M, tokens_dev, nullptr, nullptr, w.draft,
-                            w.draft_bytes, stream);
+    return draft_tokens_impl(m->g_final, m->Wheads, m->K, m->R, c->H, c->V, c->rms_eps, w.x_out, res_dev,
+                             parent_dev, rank_dev, M, tokens_dev, nullptr, nullptr, w.draft, w.draft_bytes,
+                             stream, (uint32_t*)w.verify);
 }
 
 /* Benchmark support (not part of the documented ABI): time the launches of one kind

@@ -24,6 +24,9 @@ ghd_status check_launch();
 ghd_status launch_accept(const float* logits, const int32_t* tokens, const int32_t* parent, int M,
                          int V, int32_t* res, int32_t* amax_out, void* ws, hipStream_t st);
 size_t accept_workspace_bytes();
+ghd_status launch_amax_merge(const void* tbl, int ntiles, int Mpad, int M, int32_t* amax, hipStream_t st);
+ghd_status launch_accept_path(const int32_t* amax, const int32_t* tokens, const int32_t* parent, int M,
+                              int32_t* res, hipStream_t st);
 ghd_status launch_accept_static(const float* logits, const int32_t* tokens, const int32_t* parent, int M,
                                 int V, int32_t* res, int32_t* amax_out, hipStream_t st);
 ghd_status launch_commit_path(void* const* k, void* const* v, int L, int nh, int d, int cap,

@@ -76,7 +76,8 @@ constexpr int kCntWo = kCntQkv + kMaxShares * kCntStride;
 constexpr int kCntGu = kCntWo + kMaxShares * kCntStride;
 constexpr int kCntDown = kCntGu + kMaxShares * kCntStride;
 constexpr int kCntLm = kCntDown + kMaxShares * kCntStride;   // LM head and stand-alone linear calls
-constexpr int kCntAttn = kCntLm + kMaxShares * kCntStride;   // up to 256 heads
+constexpr int kCntDraft = kCntLm + kMaxShares * kCntStride;  // drafting heads inside a whole decoding step
+constexpr int kCntAttn = kCntDraft + kMaxShares * kCntStride;   // up to 256 heads
 constexpr int kSyncWords = kCntAttn + 256 * kCntStride;
 
 struct FusedArgs {
@@ -113,6 +114,8 @@ struct FusedArgs {
     uint32_t lin_epoch;    // how often that array was used since it was zeroed
     uint32_t att_epoch;    // same for the attention head counters
     int64_t lin_ldy;
+    float2* lin_amax;      // EPI_STORE_F32, optional: per (16-column tile, row) the largest output and,
+                           // as int bits in .y, its lowest column: [tiles][Mpad]
     // attention launch
     const half_t *att_q, *att_k, *att_v;
     half_t* att_out;

@@ -74,7 +74,30 @@ __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, f
     const int mtp = a.Mpad >> 4;
     if (op.rscale) v *= s_rinv[m];
     if (op.epi == EPI_STORE_F32) {
-        if (!mok) return;
+        if (a.lin_amax) {
+            // the row's best output among this tile's 16 columns: (largest value, lowest column).
+            // Greedy acceptance (section 2.3) only needs the row argmax, so the finish of the
+            // LM head leaves one candidate per tile and row instead of (or besides) the logits.
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (n0 + r < op.N && v[r] > bv) {
+                    bv = v[r];
+                    bi = n0 + r;
+                }
+#pragma unroll
+            for (int off = 16; off < 64; off <<= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int oi = __shfl_xor(bi, off);
+                if (ov > bv || (ov == bv && oi < bi)) {
+                    bv = ov;
+                    bi = oi;
+                }
+            }
+            if (lane < 16 && mok) a.lin_amax[(size_t)(n0 >> 4) * a.Mpad + m] = make_float2(bv, __int_as_float(bi));
+        }
+        if (!mok || !op.out) return;
         float* o = (float*)op.out + (size_t)m * op.ldo + n0;
         if (n0 + 3 < op.N && (op.ldo & 3) == 0) *(floatx4*)o = v;
         else

@@ -167,6 +167,18 @@ def test_layer_and_stack_reject_bad_arguments(lib):
     assert stack(x_in=FAKE + 2) == B.GHD_ERR_ALIGN
     assert stack(ws_bytes=100) == B.GHD_ERR_WORKSPACE
 
+    def stack_argmax(amax=FAKE, logits=None, g=FAKE, M=8, ws=FAKE, ws_bytes=1 << 30):
+        return lib.ghd_verify_stack_argmax(C.byref(cfg), lws, kvs, g, FAKE, FAKE, FAKE, M, 128, amax, logits,
+                                           None, ws, ws_bytes, None)
+
+    assert stack_argmax(amax=None) == B.GHD_ERR_NULL              # the argmaxes are what the call is for
+    assert stack_argmax(g=None) == B.GHD_ERR_NULL
+    assert stack_argmax(amax=FAKE + 2) == B.GHD_ERR_ALIGN
+    assert stack_argmax(logits=FAKE + 4) == B.GHD_ERR_ALIGN
+    assert stack_argmax(M=0) == B.GHD_ERR_SHAPE
+    assert stack_argmax(ws=None) == B.GHD_ERR_WORKSPACE
+    assert stack_argmax(ws_bytes=need - 1) == B.GHD_ERR_WORKSPACE
+
 
 def test_pack_and_mask_reject_bad_arguments(lib):
     f = lib.ghd_pack_weight
@@ -185,6 +197,20 @@ def test_pack_and_mask_reject_bad_arguments(lib):
     assert g(FAKE, 4, FAKE, None, need, None) == B.GHD_ERR_WORKSPACE
     assert g(FAKE, 4, FAKE, FAKE, 8, None) == B.GHD_ERR_WORKSPACE
     assert lib.ghd_step_status(None, None, None) == B.GHD_ERR_NULL
+
+
+def test_accept_path_and_static_reject_bad_arguments(lib):
+    p = lib.ghd_accept_path
+    assert p(None, FAKE, FAKE, 4, FAKE, None) == B.GHD_ERR_NULL
+    assert p(FAKE, None, FAKE, 4, FAKE, None) == B.GHD_ERR_NULL
+    assert p(FAKE, FAKE, FAKE, 4, None, None) == B.GHD_ERR_NULL
+    assert p(FAKE, FAKE, FAKE, 0, FAKE, None) == B.GHD_ERR_SHAPE
+    assert p(FAKE, FAKE, FAKE, 129, FAKE, None) == B.GHD_ERR_SHAPE
+    q = lib.ghd_accept_greedy_static
+    assert q(None, FAKE, FAKE, 4, 10, FAKE, None, None) == B.GHD_ERR_NULL
+    assert q(FAKE, FAKE, FAKE, 4, 10, None, None, None) == B.GHD_ERR_NULL
+    assert q(FAKE, FAKE, FAKE, 129, 10, FAKE, None, None) == B.GHD_ERR_SHAPE
+    assert q(FAKE, FAKE, FAKE, 4, 0, FAKE, None, None) == B.GHD_ERR_SHAPE
 
 
 def test_accept_rejects_bad_arguments(lib):

@@ -343,6 +343,57 @@ def test_verify_stack_small_multilayer(B, model, orc32):
     check_accept(B, orc32, logits, ref_logits, parent, pd, shape.V, 9)
 
 
+@pytest.mark.parametrize("M,V,L", [(48, 3000, 2), (1, 1000, 1), (64, 10300, 1), (100, 300, 1)])
+def test_verify_stack_argmax_in_the_lm_head_finish(B, model, orc32, M, V, L):
+    """The row argmaxes reduced in the LM-head finish (per 16-column tile, then merged) are
+    exactly the argmax of the logits the same call writes, lowest index on ties (the
+    vocabulary holds duplicated rows, so maxima are tied), with and without the logits
+    written; the walk from them is the oracle's acceptance."""
+    shape = wl.ModelShape("amax%d" % V, H=256, nh=2, d=128, F=688, V=V, L=L)
+    say("stack argmax", M, V, L)
+    parent = wl.tree_random(M, 5, M + V)
+    kv_len = 70
+    cap = ((kv_len + M + 63) // 64) * 64
+    layers = [wl.layer_weights(shape, 5, l) for l in range(L)]
+    head = wl.head_weights(shape, 5)
+    half = V // 2
+    head["Wlm"][half:2 * half] = head["Wlm"][:half]          # logits of v and v + half are equal
+    caches = [wl.kv_cache(shape, cap, kv_len, 5, l) for l in range(L)]
+    stack = model.build_stack(shape, cap, [model.upload_layer(w, shape.d) for w in layers],
+                              [model.upload_cache(k, v) for k, v in caches], model.upload_head(head))
+    x16 = wl.activations(M, shape.H, 5).cuda()
+    pd = torch.from_numpy(parent).cuda()
+    ws = B.workspace(B.ghd_workspace_bytes(stack.cfg, M, kv_len))
+    logits = torch.empty((M, V), dtype=torch.float32, device="cuda")
+    amax = B.ghd_verify_stack_argmax(stack, x16, pd, kv_len, logits=logits, ws=ws)
+    assert B.ghd_step_status(ws) == 0
+    plain = B.ghd_verify_stack(stack, x16, pd, kv_len, ws=ws)
+    assert torch.equal(plain, logits)
+    lg = logits.cpu().numpy()
+    first = np.array([int(np.flatnonzero(row == row.max())[0]) for row in lg], dtype=np.int32)
+    # (a duplicated row is bit-equal to its twin only where both tiles are cut the same way
+    # between workgroups, so not every row's maximum is tied - but some are)
+    tied = sum(int((row == row.max()).sum() > 1) for row in lg)
+    assert M < 8 or tied > 0
+    assert np.array_equal(amax.cpu().numpy(), first)
+    only = B.ghd_verify_stack_argmax(stack, x16, pd, kv_len, ws=ws)     # no logits written at all
+    assert np.array_equal(only.cpu().numpy(), first)
+    # the walk from the argmaxes
+    tokens = wl.draft_tokens(M, V, 5)
+    depth = orc32.tree_depth(parent)
+    j = int(np.argmax(depth))
+    while parent[j] >= 0:
+        tokens[j] = first[parent[j]]
+        j = int(parent[j])
+    td = torch.from_numpy(tokens).cuda()
+    res = B.ghd_accept_path(only, td, pd).cpu().numpy()
+    n, nxt, path, ref_amax = orc32.accept_greedy(lg, tokens, parent)
+    assert np.array_equal(ref_amax, first)
+    assert res[0] == n == depth.max() + 1 and res[1] == nxt and np.array_equal(res[2:2 + n], path)
+    res2, _ = B.ghd_accept_greedy(logits, td, pd)
+    assert np.array_equal(res2.cpu().numpy()[:2 + n], res[:2 + n])
+
+
 def test_stack_is_deterministic(B, model, orc32):
     shape = wl.ModelShape("small2", H=512, nh=4, d=128, F=1376, V=3000, L=2)
     parent = wl.tree_random(33, 4, 10)
