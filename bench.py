@@ -303,6 +303,50 @@ def sweep(torch, B, model, wl, stream, sets=4, iters=40):
     return rows
 
 
+def tree_part_comparison(torch, B, model, wl, stream, iters=200):
+    """The drafted tokens' own attention block two ways (the paper's Figure 8b on this chip):
+    from the nonzeros of the tree mask (one dot product per (token, ancestor) pair,
+    ghd_tree_part_attention_coo) and as the masked MFMA tile of the attention kernel
+    (ghd_tree_attention on a cache that holds the tree rows only), 32 heads x 128, for a
+    chain, a bushy tree (depth <= 5) and a wide depth-2 tree at 64 and 128 nodes.  Each
+    figure is the time of one call (set-up launch + kernel) by events on the stream."""
+    dev = "cuda"
+    nh, d = 32, 128
+    shape = wl.ModelShape("tp", H=nh * d, nh=nh, d=d, F=8, V=8, L=1)
+    rows = []
+    for M in (64, 128):
+        kc, vc = wl.kv_cache(shape, 128, 128, 5, 0, device=dev)
+        kd, vd = model.upload_cache(kc, vc, device=dev)
+        q = wl.activations(M, nh * d, 5, tag="q").reshape(M, nh, d).to(dev)
+        ws = B.workspace(B.lib().ghd_attention_workspace_bytes(M, 0, nh, d))
+        out = torch.empty_like(q)
+        for kind, parent in (("chain", wl.tree_chain(M)), ("bushy", wl.tree_random(M, 5, 3)),
+                             ("depth2", wl.tree_wide_shallow(M, 32, 4))):
+            pd = torch.from_numpy(parent).to(dev)
+            depth = [0] * M
+            for i in range(1, M):
+                depth[i] = depth[parent[i]] + 1
+            res = {"M": M, "tree": kind, "mask_nonzeros": int(sum(depth) + M)}
+            for name, call in (("coo_us", lambda: B.ghd_tree_part_attention_coo(q, kd, vd, pd, 0, ws=ws, out=out)),
+                               ("masked_mfma_us", lambda: B.ghd_tree_attention(q, kd, vd, pd, 0, ws=ws))):
+                with torch.cuda.stream(stream):
+                    for _ in range(10):
+                        call()
+                    torch.cuda.synchronize()
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    for _ in range(iters):
+                        call()
+                    e1.record(stream)
+                    torch.cuda.synchronize()
+                res[name] = round(e0.elapsed_time(e1) / iters * 1e3, 2)
+            rows.append(res)
+            log("  tree part M=%3d %-6s nnz %4d: coo %6.2f us, masked MFMA tile %6.2f us"
+                % (M, kind, res["mask_nonzeros"], res["coo_us"], res["masked_mfma_us"]))
+    return rows
+
+
 def cpu_model_name():
     try:
         for line in open("/proc/cpuinfo"):
@@ -374,6 +418,9 @@ def main():
                     help="skip the tree-size sweep (one 7B-shaped layer at tree sizes 1..128, the \"sweep\" list)")
     ap.add_argument("--loop", type=int, default=0,
                     help="also run this many whole predict-then-verify steps (adds \"decode_loop\")")
+    ap.add_argument("--tree-part", action="store_true",
+                    help="also time the drafted tokens' own attention block from the mask nonzeros and as a "
+                         "masked MFMA tile (adds \"tree_part\")")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also launch one plain 1 GiB copy kernel (for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -473,6 +520,8 @@ def main():
         out["width_choice"] = {"widths": widths, "chosen": widths[i],
                                "expected_tokens_per_layer_ms": [round(x * 1e3, 3) for x in rate]}
         log("width choice:", out["width_choice"])
+    if args.tree_part:
+        out["tree_part"] = tree_part_comparison(torch, B, model, wl, stream)
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on %s layers ..." % (args.cpu_sample_layers or "all"))
         out["cpu_baseline"] = cpu_baseline(wl, w, args.cpu_sample_layers)

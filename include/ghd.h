@@ -190,6 +190,23 @@ ghd_status ghd_masked_attention(void *out, const void *q, const void *k_cache, c
                                 int64_t v_stride_ch, float scale, void *ws, size_t ws_bytes,
                                 void *stream);
 
+/* The drafted tokens' own block of the attention alone, computed from the
+ * nonzeros of the tree mask (section 3.2.2 splits the attention into the dense
+ * part over the committed cache and this sparse part; section 3.2.3 computes the
+ * sparse part from a coordinate list of the mask's nonzeros, one dot product per
+ * (token, ancestor) pair): out[i] = softmax over j in ancestors-or-self(i) of
+ * q_i . k_j * scale, applied to v_j, where k_j, v_j are cache rows kv_len + j.
+ * The committed rows [0, kv_len) are NOT attended: the result equals
+ * ghd_tree_attention on a cache that holds the tree rows only.  The verification
+ * step does not use this call (its attention kernel covers the block with one
+ * masked MFMA tile); it is the paper's sparse kernel on this chip, for
+ * comparison.  Arguments, layouts and workspace size as for ghd_tree_attention. */
+ghd_status ghd_tree_part_attention_coo(void *out, const void *q, const void *k_cache, const void *v_cache,
+                                       const int32_t *parent_dev, int M, int kv_len, int nh, int d,
+                                       int64_t k_stride_head, int64_t k_stride_tok,
+                                       int64_t v_stride_head, int64_t v_stride_ch, float scale,
+                                       void *ws, size_t ws_bytes, void *stream);
+
 /* ---- decoder layer and stack (section 2.2.2; model details as in the
  *      LLaMA architecture of section 4.1: RMSNorm, rotary positions at
  *      kv_len + depth, SwiGLU, no biases) -------------------------------- */

@@ -78,6 +78,8 @@ def lib() -> C.CDLL:
             "ghd_tree_attention": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, i64, i64, f32,
                                                vp, sz, vp]),
             "ghd_attention_workspace_bytes": (sz, [i32, i32, i32, i32]),
+            "ghd_tree_part_attention_coo": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, i64, i64,
+                                                        f32, vp, sz, vp]),
             "ghd_masked_attention": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, i64, i64, f32,
                                                  vp, sz, vp]),
             "ghd_verify_layer": (C.c_int32, [vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]),
@@ -112,7 +114,7 @@ EXPORTS = ["ghd_status_str", "ghd_last_hip_error", "ghd_tree_validate", "ghd_tre
            "ghd_tree_mask_workspace_bytes", "ghd_step_status",
            "ghd_packed_weight_bytes", "ghd_pack_weight", "ghd_linear_skinny",
            "ghd_linear_workspace_bytes", "ghd_tree_attention", "ghd_attention_workspace_bytes",
-           "ghd_masked_attention",
+           "ghd_masked_attention", "ghd_tree_part_attention_coo",
            "ghd_verify_layer", "ghd_verify_stack", "ghd_workspace_bytes", "ghd_accept_greedy",
            "ghd_accept_workspace_bytes", "ghd_accept_greedy_static", "ghd_verify_stack_argmax", "ghd_accept_path", "ghd_commit_path", "ghd_embed", "ghd_tree_build",
            "ghd_choose_width",
@@ -219,6 +221,29 @@ def ghd_tree_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Te
                                     k_cache.stride(0), k_cache.stride(1), v_cache.stride(0),
                                     v_cache.stride(1), scale, _ptr(ws), ws.numel(),
                                     _stream()), "ghd_tree_attention")
+    return out
+
+
+def ghd_tree_part_attention_coo(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                                parent: torch.Tensor, kv_len: int, scale: Optional[float] = None,
+                                ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The drafted tokens' own attention block from the nonzeros of the tree mask: token i
+    over its ancestors-or-self only (cache rows kv_len + j); the committed rows are not
+    attended.  Layouts as for ghd_tree_attention."""
+    M, nh, d = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    if scale is None:
+        scale = 1.0 / (d ** 0.5)
+    if ws is None:
+        ws = workspace(lib().ghd_attention_workspace_bytes(M, kv_len, nh, d), q.device)
+    _check(lib().ghd_tree_part_attention_coo(_ptr(out), _ptr(_dev(q, torch.float16)),
+                                             _ptr(_dev(k_cache, torch.float16)),
+                                             _ptr(_dev(v_cache, torch.float16)),
+                                             _ptr(_dev(parent, torch.int32)), M, kv_len, nh, d,
+                                             k_cache.stride(0), k_cache.stride(1), v_cache.stride(0),
+                                             v_cache.stride(1), scale, _ptr(ws), ws.numel(),
+                                             _stream()), "ghd_tree_part_attention_coo")
     return out
 
 

@@ -471,6 +471,34 @@ ghd_status ghd_masked_attention(void* out, const void* q, const void* k_cache, c
                           k_stride_tok, v_stride_head, v_stride_ch, scale, ws, ws_bytes, stream);
 }
 
+ghd_status ghd_tree_part_attention_coo(void* out, const void* q, const void* k_cache, const void* v_cache,
+                                       const int32_t* parent_dev, int M, int kv_len, int nh, int d,
+                                       int64_t k_stride_head, int64_t k_stride_tok, int64_t v_stride_head,
+                                       int64_t v_stride_ch, float scale, void* ws, size_t ws_bytes,
+                                       void* stream)
+{
+    if (!out || !q || !k_cache || !v_cache || !parent_dev) return GHD_ERR_NULL;
+    if (M < 1 || M > GHD_MAX_M || kv_len < 0 || nh < 1 || nh > 256 || (d != 64 && d != 128))
+        return GHD_ERR_SHAPE;
+    if (k_stride_tok < d || k_stride_head < 0 || v_stride_head < 0) return GHD_ERR_SHAPE;
+    if (v_stride_ch < (int64_t)kv_len + M) return GHD_ERR_CAPACITY;
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) ||
+        (k_stride_tok % 8) != 0 || (k_stride_head % 8) != 0 || (v_stride_ch % 8) != 0 ||
+        (v_stride_head % 8) != 0)
+        return GHD_ERR_ALIGN;
+    if (!ws) return GHD_ERR_WORKSPACE;
+    if (!aligned16(ws)) return GHD_ERR_ALIGN;
+    if (ws_bytes < ghd_attention_workspace_bytes(M, kv_len, nh, d)) return GHD_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    Ws w = carve(ws, 2, M, 0, 0, d);
+    // the coordinate list is read off the ancestor masks the set-up kernel builds from parent[]
+    ghd_status s = launch_fused_setup(w.sync, parent_dev, M, mpad_of(M), kv_len, d, 1.f, w.mask, nullptr,
+                                      nullptr, nullptr, 0, nullptr, nullptr, nullptr, st);
+    if (s) return s;
+    return launch_tree_part_coo(out, q, k_cache, v_cache, w.mask, M, kv_len, nh, d, k_stride_head, k_stride_tok,
+                                v_stride_head, v_stride_ch, scale, st);
+}
+
 size_t ghd_workspace_bytes(const ghd_model_cfg* cfg, int M, int kv_len)
 {
     if (check_cfg(cfg, M, kv_len) != GHD_OK) return 0;

@@ -144,6 +144,11 @@ ghd_status launch_fused_setup(uint32_t* sync, const int32_t* parent, int M, int 
 // row-major fp16 [M, ldx] -> packed activation layout (columns K.. of the last k-step zero)
 ghd_status launch_pack_x(half_t* dst, const half_t* src, int M, int Mpad, int K, int64_t ldx, hipStream_t st);
 
+// the drafted tokens' own attention block from the nonzeros of the mask only (coo.hip)
+ghd_status launch_tree_part_coo(void* out, const void* q, const void* kc, const void* vc, const uint64_t* mask,
+                                int M, int kv_len, int nh, int d, int64_t stride_head, int64_t stride_tok,
+                                int64_t v_stride_head, int64_t v_stride_ch, float scale, hipStream_t st);
+
 ghd_status launch_pack2(void* dst, const void* src, int N, int K, int kind, int d, hipStream_t st);
 size_t packed_bytes2(int N, int K);
 

@@ -193,6 +193,34 @@ def test_tree_attention(B, model, orc32, M, nh, d, kv_len, tree):
     assert ok, (ma, mr)
 
 
+@pytest.mark.parametrize("M,nh,d,kv_len,tree", [(8, 4, 64, 128, "rand3"), (64, 4, 128, 200, "rand5"),
+                                                (64, 2, 128, 0, "chain"), (128, 2, 64, 77, "chain"),
+                                                (128, 3, 128, 333, "rand5"), (64, 2, 128, 2048, "wide"),
+                                                (1, 2, 128, 9, "chain"), (100, 2, 64, 40, "star")])
+def test_tree_part_attention_from_the_mask_nonzeros(B, model, orc32, M, nh, d, kv_len, tree):
+    """The sparse component alone (one dot product per (token, ancestor) pair): equals the
+    oracle's tree attention on a cache that holds the tree rows only, and the attention
+    kernel's masked tile on that cache."""
+    say("tree part coo", M, nh, d, kv_len, tree)
+    parent = make_tree(tree, M)
+    q, kc, vc = attention_case(M, nh, d, kv_len, parent, 43)
+    rows_k = kc[:, kv_len:kv_len + M].contiguous()
+    rows_v = vc[:, kv_len:kv_len + M].contiguous()
+    ref = orc32.tree_attention(q.numpy().astype(np.float32), rows_k.numpy(), rows_v.numpy(), parent, 0)
+    kd, vd = model.upload_cache(kc, vc)
+    pd = torch.from_numpy(parent).cuda()
+    got = B.ghd_tree_part_attention_coo(q.cuda(), kd, vd, pd, kv_len).cpu().numpy()
+    ok, ma, mr = close(got, ref, 5e-3, 5e-3)
+    assert ok, (ma, mr)
+    cap = ((M + 63) // 64) * 64
+    pk = torch.zeros((nh, cap, d), dtype=torch.float16)
+    pv = torch.zeros((nh, cap, d), dtype=torch.float16)
+    pk[:, :M], pv[:, :M] = rows_k, rows_v
+    dense = B.ghd_tree_attention(q.cuda(), *model.upload_cache(pk, pv), pd, 0).cpu().numpy()
+    ok, ma, mr = close(got, dense, 5e-3, 5e-3)
+    assert ok, (ma, mr)
+
+
 @pytest.mark.parametrize("M,kv_len,cap", [(6, 64, 72), (1, 7, 8), (10, 118, 128), (9, 190, 200)])
 def test_tree_attention_tight_capacity(B, model, orc32, M, kv_len, cap):
     """Capacity not a multiple of the 64-key tile: the last tile's V pieces past the
