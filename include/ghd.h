@@ -212,7 +212,11 @@ ghd_status ghd_tree_part_attention_coo(void *out, const void *q, const void *k_c
  *      kv_len + depth, SwiGLU, no biases) -------------------------------- */
 
 /* x [M, H] float: residual stream, updated in place.  Writes node i's rotated
- * key and its value to cache row kv_len + i, then attends. */
+ * key and its value to cache row kv_len + i, then attends.
+ * Magnitudes: the input of every normalised linear layer is kept as
+ * fp16(x * gain) (the row factor of the RMSNorm is applied after the
+ * contraction), so |x * gain| must stay below 65504 and keeps full fp16
+ * precision down to 6e-5; smaller entries lose relative precision gradually. */
 ghd_status ghd_verify_layer(const ghd_model_cfg *cfg, const ghd_layer_weights *w, const ghd_kv *kv,
                             float *x, const int32_t *parent_dev, int M, int kv_len, void *ws,
                             size_t ws_bytes, void *stream);

@@ -144,6 +144,13 @@ def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
     return t
 
 
+def _devs(t: torch.Tensor, dtype) -> torch.Tensor:
+    """A device tensor that may be a strided view (its last axis contiguous): the entry
+    points that take explicit strides."""
+    assert t.is_cuda and t.dtype == dtype and t.stride(-1) == 1, (t.device, t.dtype, t.stride())
+    return t
+
+
 def make_cfg(shape, kv_capacity: int) -> ModelCfg:
     return ModelCfg(shape.H, shape.nh, shape.d, shape.F, shape.V, shape.L, kv_capacity,
                     shape.rope_base, shape.rms_eps)
@@ -196,7 +203,8 @@ def ghd_linear_skinny(x: torch.Tensor, Wp: torch.Tensor, N: int, out_dtype=torch
     if ws is None:
         ws = workspace(lib().ghd_linear_workspace_bytes(M, N, K), x.device)
     flags = GHD_OUT_F16 if y.dtype == torch.float16 else GHD_OUT_F32
-    _check(lib().ghd_linear_skinny(_ptr(y), _ptr(_dev(x, torch.float16)), _ptr(Wp), M, N, K,
+    assert y.stride(-1) == 1
+    _check(lib().ghd_linear_skinny(_ptr(y), _ptr(_devs(x, torch.float16)), _ptr(Wp), M, N, K,
                                    x.stride(0), y.stride(0), flags, _ptr(ws), ws.numel(), _stream()),
            "ghd_linear_skinny")
     return y
@@ -215,8 +223,8 @@ def ghd_tree_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Te
     if ws is None:
         ws = workspace(lib().ghd_attention_workspace_bytes(M, kv_len, nh, d), q.device)
     _check(lib().ghd_tree_attention(_ptr(out), _ptr(_dev(q, torch.float16)),
-                                    _ptr(_dev(k_cache, torch.float16)),
-                                    _ptr(_dev(v_cache, torch.float16)),
+                                    _ptr(_devs(k_cache, torch.float16)),
+                                    _ptr(_devs(v_cache, torch.float16)),
                                     _ptr(_dev(parent, torch.int32)), M, kv_len, nh, d,
                                     k_cache.stride(0), k_cache.stride(1), v_cache.stride(0),
                                     v_cache.stride(1), scale, _ptr(ws), ws.numel(),

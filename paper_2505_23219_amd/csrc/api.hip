@@ -261,7 +261,7 @@ static ghd_status step_attention(const ghd_model_cfg* c, const Ws& w, const ghd_
 }
 
 // One decoder layer on the residual stream x.  On entry (and again on return) w.ss holds
-// x's per-tile sums of squares and w.xg16 = fp16(x * g / 16) for the gain of the norm that
+// x's per-tile sums of squares and w.xg16 = fp16(x * g) for the gain of the norm that
 // comes next: g_attn of this layer on entry, next_g on return (skipped if next_g is null).
 static ghd_status run_layer(const ghd_model_cfg* c, const ghd_layer_weights* lw, const ghd_kv* kv,
                             float* x, int M, int kv_len, const Ws& w, const half_t* next_g,

@@ -80,6 +80,14 @@ constexpr int kCntDraft = kCntLm + kMaxShares * kCntStride;  // drafting heads i
 constexpr int kCntAttn = kCntDraft + kMaxShares * kCntStride;   // up to 256 heads
 constexpr int kSyncWords = kCntAttn + 256 * kCntStride;
 
+// RMSNorm is split around the linear layer that consumes it: the producer of the residual
+// stream x also leaves xg16 = fp16(x * g * kXgScale) (g = gain of the next norm), which is
+// streamed like any fp16 input, and the per-row factor rsqrt(mean x^2 + eps) / kXgScale - a
+// scalar per row, so it commutes with the contraction - is applied to the fp32 sums in the
+// consumer's epilogue.  x * g itself must fit fp16: magnitudes up to 65504 (LLaMA-style
+// residual outliers of a few thousand do), full relative precision down to 6e-5.
+constexpr float kXgScale = 1.0f;
+
 struct FusedArgs {
     int mode;
     int M, Mpad, kv_len;
@@ -93,7 +101,7 @@ struct FusedArgs {
     float* o_part;         // attention partial states, one per workgroup: [G][Mpad][d]
     float* ml_part;        // [G][Mpad][2]
     float* x;              // residual stream [M, H] fp32
-    half_t* xg16;          // fp16(x * gain of the next RMSNorm / 16), packed activation layout
+    half_t* xg16;          // fp16(x * gain of the next RMSNorm), packed activation layout
     float* ss;             // sums of squares per 16-column tile: [H/16][Mpad]
     half_t* q16;           // [M, H]
     half_t* o16;           // attention output, packed activation layout

@@ -15,7 +15,6 @@
 
 namespace ghd {
 
-constexpr float kXgScale = 0.0625f;   // xg16 = fp16(x * g * kXgScale), as the linear layers expect it
 
 // ---------------------------------------------------------------------------
 // tree attention

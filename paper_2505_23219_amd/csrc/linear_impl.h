@@ -35,7 +35,7 @@ struct GemmOp {
     int N, K;
     int epi;
     const half8* in;     // packed activation layout, Mpad rows
-    bool rscale;         // input is xg16: multiply output row m by 16 * rsqrt(mean x[m]^2 + eps)
+    bool rscale;         // input is xg16: multiply output row m by rsqrt(mean x[m]^2 + eps) / kXgScale
     const half_t* gnext; // RESID: gain of the next RMSNorm (xg16 is rewritten), or nullptr
     void* out;           // STORE: y;  RESID: x;  SWIGLU: a16
     int64_t ldo;
@@ -45,7 +45,6 @@ struct GemmOp {
     int passes;          // shares per workgroup
 };
 
-constexpr float kXgScale = 0.0625f;   // xg16 = fp16(x * g * kXgScale)
 
 #ifndef GHD_RING_REGS
 #define GHD_RING_REGS 80     // registers the load ring of a wavefront may take

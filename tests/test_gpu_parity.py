@@ -144,6 +144,28 @@ def test_linear_skinny(B, orc32, M, N, K):
     assert ok, (ma, mr)
 
 
+@pytest.mark.parametrize("M,N,K,padx,pady", [(5, 130, 688, 24, 6), (64, 4096, 1024, 8, 64), (33, 10300, 264, 40, 4)])
+def test_linear_skinny_with_padded_leading_dimensions(B, orc32, M, N, K, padx, pady):
+    """x and y given as views of wider arrays (ldx > K, ldy > N): the columns beside them
+    are neither read into the result nor written."""
+    say("linear padded", M, N, K, padx, pady)
+    x = wl.activations(M, K, 33)
+    W = wl.activations(N, K, 34, tag="w", std=0.02)
+    ref = orc32.linear(x.numpy().astype(np.float32), W.numpy())
+    bigx = torch.full((M, K + padx), float("nan"), dtype=torch.float16)
+    bigx[:, :K] = x
+    bigx = bigx.cuda()
+    for dt, tol in ((torch.float32, 2e-4), (torch.float16, 1e-3)):
+        bigy = torch.full((M, N + pady), -77.0, dtype=dt, device="cuda")
+        ws = B.workspace(B.lib().ghd_linear_workspace_bytes(M, N, K))
+        B.ghd_linear_skinny(bigx[:, :K], B.ghd_pack_weight(W.cuda()), N, ws=ws, y=bigy[:, :N])
+        assert B.ghd_step_status(ws) == 0
+        got = bigy.cpu().float().numpy()
+        ok, ma, mr = close(got[:, :N], ref, tol, tol)
+        assert ok, (ma, mr)
+        assert (got[:, N:] == -77.0).all()
+
+
 def attention_case(M, nh, d, kv_len, parent, seed, cap=None):
     shape = wl.ModelShape("t", H=nh * d, nh=nh, d=d, F=8, V=8, L=1)
     cap = cap or ((kv_len + M + 63) // 64) * 64
@@ -190,6 +212,41 @@ def test_tree_attention(B, model, orc32, M, nh, d, kv_len, tree):
     assert B.ghd_step_status(ws) == 0
     got = got.cpu().numpy()
     ok, ma, mr = close(got, ref, 5e-3, 5e-3)
+    assert ok, (ma, mr)
+
+
+@pytest.mark.parametrize("M,nh,d,kv_len,tree", [(8, 4, 64, 128, "rand3"), (40, 3, 128, 333, "rand5"),
+                                                (64, 8, 128, 1000, "chain")])
+def test_tree_attention_token_major_keys(B, model, orc32, M, nh, d, kv_len, tree):
+    """K cache kept [capacity][nh][d] (k_stride_tok = nh * d, k_stride_head = d), the layout
+    the strides of the call exist for."""
+    say("attention, token-major K", M, nh, d, kv_len, tree)
+    parent = make_tree(tree, M)
+    q, kc, vc = attention_case(M, nh, d, kv_len, parent, 45)
+    ref = orc32.tree_attention(q.numpy().astype(np.float32), kc.numpy(), vc.numpy(), parent, kv_len)
+    kd, vd = model.upload_cache(kc, vc)
+    k_tok = kd.permute(1, 0, 2).contiguous()          # [cap, nh, d] in memory
+    view = k_tok.permute(1, 0, 2)                     # indexed [nh, cap, d] with strides (d, nh * d, 1)
+    assert view.stride() == (d, nh * d, 1)
+    ws = B.workspace(B.lib().ghd_attention_workspace_bytes(M, kv_len, nh, d))
+    got = B.ghd_tree_attention(q.cuda(), view, vd, torch.from_numpy(parent).cuda(), kv_len, ws=ws)
+    assert B.ghd_step_status(ws) == 0
+    ok, ma, mr = close(got.cpu().numpy(), ref, 5e-3, 5e-3)
+    assert ok, (ma, mr)
+
+
+def test_tree_attention_with_256_heads(B, model, orc32):
+    """More heads than workgroups per XCD: every workgroup takes whole heads."""
+    M, nh, d, kv_len = 8, 256, 64, 130
+    say("attention, 256 heads")
+    parent = make_tree("rand3", M)
+    q, kc, vc = attention_case(M, nh, d, kv_len, parent, 46)
+    ref = orc32.tree_attention(q.numpy().astype(np.float32), kc.numpy(), vc.numpy(), parent, kv_len)
+    ws = B.workspace(B.lib().ghd_attention_workspace_bytes(M, kv_len, nh, d))
+    got = B.ghd_tree_attention(q.cuda(), *model.upload_cache(kc, vc), torch.from_numpy(parent).cuda(),
+                               kv_len, ws=ws)
+    assert B.ghd_step_status(ws) == 0
+    ok, ma, mr = close(got.cpu().numpy(), ref, 5e-3, 5e-3)
     assert ok, (ma, mr)
 
 
@@ -284,6 +341,42 @@ def run_layer_case(B, model, orc32, shape, M, kv_len, parent, seed):
         ok, ma, mr = close(got[:, kv_len:kv_len + M], want[:, kv_len:kv_len + M], 2e-3, 2e-3)
         assert ok, (name, ma, mr)
     return ma
+
+
+@pytest.mark.parametrize("x_std,gain", [(1e-2, 0.03), (1e3, 1.0), (30.0, 4.0)])
+def test_verify_layer_small_and_large_magnitudes(B, model, orc32, x_std, gain):
+    """The normalised linear layers stream fp16(x * gain) and apply the row factor after the
+    contraction: a small residual stream with small gains (first-layer embeddings) and a
+    large one must come out as precisely as the usual N(0, 1) one.  The tolerance of the
+    other layer tests, taken relative to the size of the layer's own update."""
+    shape = wl.ModelShape("mag", H=512, nh=4, d=128, F=1376, V=100, L=1)
+    M, kv_len, seed = 40, 64, 12
+    say("layer magnitudes", x_std, gain)
+    parent = make_tree("rand5", M)
+    cap = ((kv_len + M + 63) // 64) * 64
+    w = wl.layer_weights(shape, seed, 0)
+    for g in ("g_attn", "g_ffn"):
+        w[g] = (w[g].float() * gain).to(torch.float16)
+    kc, vc = wl.kv_cache(shape, cap, kv_len, seed, 0)
+    x32 = (wl.activations(M, shape.H, seed).float() * x_std).contiguous()
+    kc_o, vc_o = kc.numpy().copy(), vc.numpy().copy()
+    ref = orc32.verify_layer(shape, {k: v.numpy() for k, v in w.items()}, kc_o, vc_o, x32.numpy().copy(),
+                             parent, kv_len, round16=True)
+    wd = model.upload_layer(w, shape.d)
+    kc_d, vc_d = model.upload_cache(kc, vc)
+    x = x32.cuda()
+    cfg = B.make_cfg(shape, cap)
+    ws = B.workspace(B.ghd_workspace_bytes(cfg, M, kv_len))
+    B.ghd_verify_layer(cfg, wd, kc_d, vc_d, x, torch.from_numpy(parent).cuda(), kv_len, ws=ws)
+    assert B.ghd_step_status(ws) == 0
+    update = ref - x32.numpy()
+    unit = float(np.sqrt((update.astype(np.float64) ** 2).mean()))
+    err = np.abs(x.cpu().numpy() - ref)
+    # fp32 spacing of the residual stream itself is part of what can be had at x ~ 1e3
+    bound = 2e-2 * unit + 1e-2 * np.abs(update) + 4 * np.spacing(np.abs(ref).astype(np.float32))
+    assert (err <= bound).all(), (float(err.max()), unit)
+    ok, ma, mr = close(kc_d.cpu().numpy()[:, kv_len:kv_len + M], kc_o[:, kv_len:kv_len + M], 2e-3 * max(gain, 1e-3), 2e-3)
+    assert ok, ("k", ma, mr)
 
 
 def test_verify_layer_tiny(B, model, orc32):
