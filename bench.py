@@ -241,29 +241,43 @@ def timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, wh
 
 
 def linear_roofline(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, w, steps):
-    """Dominant kernel: the persistent skinny-GEMM kernel (4 launches per layer + the LM
-    head; it streams every weight byte of the step).  Its launches are bracketed by HIP
-    events inside the library, on the launch stream.  achieved = algorithmic bytes per
-    launch (all weight bytes of the step / launches per step: every launch reads its
-    matrix exactly once) / average launch duration."""
+    """Dominant kernel: the persistent skinny-GEMM kernel (it streams every weight byte of
+    the step).  Its launches are bracketed by HIP events inside the library, on the launch
+    stream.  Where the QKV layer shares its launch with the attention, that launch is timed
+    and reported on its own ("qkv_attention": QKV weights + the layer's cache), and the
+    linear figure covers the launches that are linear layers only (output, gate|up and down
+    projections and the LM head): achieved = their weight bytes / launches / average
+    duration (every launch reads its matrix exactly once)."""
     s = w.shape
+    qkv_bytes = 2 * s.L * 3 * s.H * s.H
     weight_bytes = 2 * (s.L * (3 * s.H * s.H + s.H * s.H + 2 * s.F * s.H + s.H * s.F) + s.V * s.H)
+    kv_bytes = 2 * 2 * s.L * s.nh * s.d * (kv_len + w.M)
     tot_ms, launches = timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, 1, steps)
     per_step = launches // steps
-    per_launch_bytes = weight_bytes / per_step
+    fused_ms, fused_n = timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, 3, steps)
+    fused = fused_n > 0
+    lin_bytes = weight_bytes - (qkv_bytes if fused else 0)
+    per_launch_bytes = lin_bytes / per_step
     avg_ms = tot_ms / launches
     achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
-    att_ms, att_n = timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, 2, steps)
-    kv_bytes = 2 * 2 * s.L * s.nh * s.d * (kv_len + w.M)
-    return {"bound": "hbm", "kernel": "k_linear<MT, R, RB>", "achieved": round(achieved, 1),
-            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": recorded_traffic(w.name), "launches_per_step": per_step,
-            "avg_launch_us": round(avg_ms * 1e3, 2),
-            "algorithmic_bytes_per_launch": int(per_launch_bytes),
-            "attention": {"kernel": "k_attention<MT, D>", "launches_per_step": att_n // steps,
-                          "avg_launch_us": round(att_ms / att_n * 1e3, 2),
-                          "algorithmic_bytes_per_launch": int(kv_bytes / (att_n // steps)),
-                          "achieved": round(kv_bytes / (att_n // steps) / (att_ms / att_n * 1e-3) / 1e9, 1)}}
+    out = {"bound": "hbm", "kernel": "k_linear<MT, R, RB>", "achieved": round(achieved, 1),
+           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+           "traffic": recorded_traffic(w.name), "launches_per_step": per_step,
+           "avg_launch_us": round(avg_ms * 1e3, 2),
+           "algorithmic_bytes_per_launch": int(per_launch_bytes)}
+    if fused:
+        b = (qkv_bytes + kv_bytes) / (fused_n // steps)
+        out["qkv_attention"] = {"kernel": "k_qkv_attn<MT, R, D>", "launches_per_step": fused_n // steps,
+                                "avg_launch_us": round(fused_ms / fused_n * 1e3, 2),
+                                "algorithmic_bytes_per_launch": int(b),
+                                "achieved": round(b / (fused_ms / fused_n * 1e-3) / 1e9, 1)}
+    else:
+        att_ms, att_n = timed_launches(torch, B, stack, x_in, parent, kv_len, ws, logits, stream, 2, steps)
+        out["attention"] = {"kernel": "k_attention<MT, D>", "launches_per_step": att_n // steps,
+                            "avg_launch_us": round(att_ms / att_n * 1e3, 2),
+                            "algorithmic_bytes_per_launch": int(kv_bytes / (att_n // steps)),
+                            "achieved": round(kv_bytes / (att_n // steps) / (att_ms / att_n * 1e-3) / 1e9, 1)}
+    return out
 
 
 def sweep(torch, B, model, wl, stream, sets=4, iters=40):

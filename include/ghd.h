@@ -253,9 +253,15 @@ ghd_status ghd_verify_stack_argmax(const ghd_model_cfg *cfg, const ghd_layer_wei
  * last ghd_linear_skinny / ghd_tree_attention / ghd_verify_layer /
  * ghd_verify_stack call left in its workspace `ws`: 0 = completed, otherwise
  * the code of the wait that gave up (3: a workgroup did not run on the expected
- * XCD) and the outputs are invalid.  Blocking; for tests and error handling,
- * not the hot path. */
+ * XCD) and the outputs are invalid (a workgroup whose wait gave up writes no
+ * results for the item it waited for).  The word is sticky: every call's set-up
+ * clears the status for the launches that follow but keeps the first non-zero
+ * status it finds, so a caller who asks only every so often still learns that
+ * some call since ghd_step_status_reset (or since the first use of the
+ * workspace) gave up.  Blocking; for tests and error handling, not the hot path. */
 ghd_status ghd_step_status(const void *ws, int32_t *status_host, void *stream);
+/* Clears the status, the kept one included (enqueued on `stream`). */
+ghd_status ghd_step_status_reset(void *ws, void *stream);
 
 /* ---- greedy acceptance (section 2.3: of the drafted tree, the longest root
  *      path the model itself would have produced is kept) ------------------- */

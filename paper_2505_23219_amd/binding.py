@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
             "ghd_tree_mask": (C.c_int32, [vp, i32, vp, vp, sz, vp]),
             "ghd_tree_mask_workspace_bytes": (sz, []),
             "ghd_step_status": (C.c_int32, [vp, vp, vp]),
+            "ghd_step_status_reset": (C.c_int32, [vp, vp]),
             "ghd_packed_weight_bytes": (sz, [i32, i32]),
             "ghd_pack_weight": (C.c_int32, [vp, vp, i32, i32, i32, i32, vp]),
             "ghd_linear_skinny": (C.c_int32, [vp, vp, vp, i32, i32, i32, i64, i64, u32, vp, sz, vp]),
@@ -111,7 +112,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["ghd_status_str", "ghd_last_hip_error", "ghd_tree_validate", "ghd_tree_mask",
-           "ghd_tree_mask_workspace_bytes", "ghd_step_status",
+           "ghd_tree_mask_workspace_bytes", "ghd_step_status", "ghd_step_status_reset",
            "ghd_packed_weight_bytes", "ghd_pack_weight", "ghd_linear_skinny",
            "ghd_linear_workspace_bytes", "ghd_tree_attention", "ghd_attention_workspace_bytes",
            "ghd_masked_attention", "ghd_tree_part_attention_coo",

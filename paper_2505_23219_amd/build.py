@@ -11,7 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libghd.so")
 SOURCES = ["api.hip", "fused.hip", "linear.hip", "linear_mt1.hip", "linear_mt2.hip", "linear_mt4.hip",
-           "linear_mt8.hip", "accept.hip", "draft.hip", "coo.hip"]
+           "linear_mt8.hip", "qkv_attn_mt1.hip", "qkv_attn_mt2.hip", "qkv_attn_mt4.hip", "qkv_attn_mt8.hip",
+           "accept.hip", "draft.hip", "coo.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -42,6 +42,9 @@ static ghd_status timed_fused(const FusedArgs& a, hipStream_t st)
     return s;
 }
 
+// benchmark support: run the QKV layer and the attention as two launches even where one would do
+static bool g_split_qkv_attn = false;
+
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 // Number of workgroups of the persistent kernel; 256 (the MI355X's compute units) when
@@ -220,10 +223,9 @@ struct LinearCall {
     float2* amax_tbl;     // EPI_STORE_F32: per-tile row maxima (optional)
 };
 
-static ghd_status step_linear(const ghd_model_cfg* c, const Ws& w, float* x, int M, int kv_len,
-                              const LinearCall& lc, hipStream_t st)
+static ghd_status fill_linear(FusedArgs& a, const ghd_model_cfg* c, const Ws& w, float* x, int M, int kv_len,
+                              const LinearCall& lc)
 {
-    FusedArgs a = {};
     fill_common(a, c, w, M, kv_len);
     a.x = x;
     a.mode = MODE_LINEAR;
@@ -242,6 +244,25 @@ static ghd_status step_linear(const ghd_model_cfg* c, const Ws& w, float* x, int
     a.lin_cnt = lc.cnt;
     a.lin_epoch = lc.epoch;
     a.lin_amax = lc.amax_tbl;
+    return GHD_OK;
+}
+
+static void fill_attention(FusedArgs& a, const Ws& w, const ghd_kv* kv, uint32_t epoch)
+{
+    a.att_q = w.q16;
+    a.att_k = (const half_t*)kv->k;
+    a.att_v = (const half_t*)kv->v;
+    a.att_out = w.o16;
+    a.att_out_packed = 1;
+    a.att_epoch = epoch;
+}
+
+static ghd_status step_linear(const ghd_model_cfg* c, const Ws& w, float* x, int M, int kv_len,
+                              const LinearCall& lc, hipStream_t st)
+{
+    FusedArgs a = {};
+    ghd_status s = fill_linear(a, c, w, x, M, kv_len, lc);
+    if (s) return s;
     return timed_fused(a, st);
 }
 
@@ -251,13 +272,25 @@ static ghd_status step_attention(const ghd_model_cfg* c, const Ws& w, const ghd_
     FusedArgs a = {};
     fill_common(a, c, w, M, kv_len);
     a.mode = MODE_ATTN;
-    a.att_q = w.q16;
-    a.att_k = (const half_t*)kv->k;
-    a.att_v = (const half_t*)kv->v;
-    a.att_out = w.o16;
-    a.att_out_packed = 1;
-    a.att_epoch = epoch;
+    fill_attention(a, w, kv, epoch);
     return timed_fused(a, st);
+}
+
+// The QKV layer and the attention of a layer: one launch where the shape allows it (see
+// qkv_attn_available), else two.
+static ghd_status step_qkv_attention(const ghd_model_cfg* c, const Ws& w, const ghd_kv* kv, float* x, int M,
+                                     int kv_len, const LinearCall& qkv, uint32_t layer, hipStream_t st)
+{
+    FusedArgs a = {};
+    ghd_status s = fill_linear(a, c, w, x, M, kv_len, qkv);
+    if (s) return s;
+    if (!g_split_qkv_attn && qkv_attn_available(M, a.lin_slots, a.lin_passes, c->d, c->nh)) {
+        a.mode = MODE_QKV_ATTN;
+        fill_attention(a, w, kv, layer);
+        return timed_fused(a, st);
+    }
+    if ((s = timed_fused(a, st))) return s;
+    return step_attention(c, w, kv, M, kv_len, layer, st);
 }
 
 // One decoder layer on the residual stream x.  On entry (and again on return) w.ss holds
@@ -270,8 +303,7 @@ static ghd_status run_layer(const ghd_model_cfg* c, const ghd_layer_weights* lw,
     const int H = c->H, F = c->F;
     ghd_status s;
     LinearCall qkv = {lw->Wqkv, 3 * H, H, EPI_QKV, w.xg16, true, nullptr, nullptr, 0, kv, kCntQkv, layer, nullptr};
-    if ((s = step_linear(c, w, x, M, kv_len, qkv, st))) return s;
-    if ((s = step_attention(c, w, kv, M, kv_len, layer, st))) return s;
+    if ((s = step_qkv_attention(c, w, kv, x, M, kv_len, qkv, layer, st))) return s;
     LinearCall wo = {lw->Wo, H, H, EPI_RESID, w.o16, false, (const half_t*)lw->g_ffn, x, H, nullptr, kCntWo, layer, nullptr};
     if ((s = step_linear(c, w, x, M, kv_len, wo, st))) return s;
     LinearCall gu = {lw->Wgu, 2 * F, H, EPI_SWIGLU, w.xg16, true, nullptr, w.a16, F, nullptr, kCntGu, layer, nullptr};
@@ -338,7 +370,7 @@ ghd_status ghd_pack_weight(void* dst, const void* src, int N, int K, int kind, i
 {
     if (!dst || !src) return GHD_ERR_NULL;
     if (N < 1 || K < 1 || kind < GHD_PACK_PLAIN || kind > GHD_PACK_GATE_UP) return GHD_ERR_SHAPE;
-    if (kind == GHD_PACK_QKV && ((head_dim != 64 && head_dim != 128) || N % head_dim != 0))
+    if (kind == GHD_PACK_QKV && ((head_dim != 64 && head_dim != 128) || N % (3 * head_dim) != 0))
         return GHD_ERR_SHAPE;
     if (kind == GHD_PACK_GATE_UP && (N % 16) != 0) return GHD_ERR_SHAPE;
     if (!aligned16(dst)) return GHD_ERR_ALIGN;
@@ -597,13 +629,23 @@ ghd_status ghd_verify_stack_argmax(const ghd_model_cfg* cfg, const ghd_layer_wei
 ghd_status ghd_step_status(const void* ws, int32_t* status_host, void* stream)
 {
     if (!ws || !status_host) return GHD_ERR_NULL;
-    uint32_t v = 0;
-    hipError_t e = hipMemcpyAsync(&v, (const uint32_t*)ws + kSyncStatus, sizeof(v),
-                                  hipMemcpyDeviceToHost, (hipStream_t)stream);
+    uint32_t v[4] = {0, 0, 0, 0};
+    hipError_t e = hipMemcpyAsync(v, (const uint32_t*)ws, sizeof(v), hipMemcpyDeviceToHost,
+                                  (hipStream_t)stream);
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
-    *status_host = (int32_t)v;
+    // the calls since the last set-up, else what an earlier set-up found and kept
+    uint32_t st = v[kSyncStatus];
+    if (st == 0 && v[kSyncMagic] == kSyncMagicValue) st = v[kSyncSticky];
+    *status_host = (int32_t)st;
     return GHD_OK;
+}
+
+ghd_status ghd_step_status_reset(void* ws, void* stream)
+{
+    if (!ws) return GHD_ERR_NULL;
+    hipError_t e = hipMemsetAsync((uint32_t*)ws + kSyncStatus, 0, 2 * sizeof(uint32_t), (hipStream_t)stream);
+    return e == hipSuccess ? GHD_OK : hip_fail(e);
 }
 
 size_t ghd_accept_workspace_bytes(int M)
@@ -861,7 +903,8 @@ ghd_status ghd_spec_step(const ghd_spec_model* m, const int32_t* parent_dev, con
 /* Benchmark support (not part of the documented ABI): time the launches of one kind
  * of the persistent kernel with HIP events on the launch stream.
  * ghd_debug_profile(1) starts a fresh measurement of the linear-layer launches,
- * ghd_debug_profile(2) of the attention launches, ghd_debug_profile(0) stops it; after
+ * ghd_debug_profile(2) of the attention launches, ghd_debug_profile(3) of the launches that
+ * hold a QKV layer and its attention, ghd_debug_profile(0) stops it; after
  * synchronising the stream, ghd_debug_profile_read returns the number of launches and
  * their summed duration in milliseconds.  ghd_debug_copy is a plain copy kernel of known
  * traffic (bytes read + bytes written) used to calibrate the profiler's byte counters. */
@@ -889,9 +932,11 @@ void ghd_debug_attn_share(int nh, int ntile, int j, int G, int head, int* out6)
     attn_share_on_host(nh, ntile, j, G, head, out6);
 }
 
+void ghd_debug_split_qkv_attn(int on) { g_split_qkv_attn = on != 0; }
+
 void ghd_debug_profile(int what)
 {
-    g_prof_mode = what == 1 ? MODE_LINEAR : what == 2 ? MODE_ATTN : -1;
+    g_prof_mode = what == 1 ? MODE_LINEAR : what == 2 ? MODE_ATTN : what == 3 ? MODE_QKV_ATTN : -1;
     if (what) g_prof_used = 0;
 }
 

@@ -8,7 +8,7 @@ constexpr int kFT = 512;        // threads per workgroup (8 wavefronts)
 constexpr int kMaxLayers = 48;  // the counter epochs (one per layer) are laid out for this many
 
 enum { EPI_STORE_F32 = 0, EPI_STORE_F16 = 1, EPI_RESID = 2, EPI_SWIGLU = 3, EPI_QKV = 4 };
-enum { MODE_LINEAR = 0, MODE_ATTN = 1 };
+enum { MODE_LINEAR = 0, MODE_ATTN = 1, MODE_QKV_ATTN = 2 };
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 
 // ---- packed weight layout ------------------------------------------------------
@@ -52,6 +52,48 @@ __host__ __device__ inline size_t w_piece(const WLayout& l, int t, int s, int la
 }
 __host__ __device__ inline size_t w_pieces(const WLayout& l) { return ((size_t)l.nblocks * l.blk * l.nks) << 6; }
 
+// ---- row order of the packed QKV matrix ------------------------------------------------
+// Packed rows come in quads (j, j+1, j+d/2, j+1+d/2) of one head's channels, so that both
+// members of two rotary pairs sit in one lane of the GEMM output.  With a head count that
+// is a multiple of 8, the rows are grouped by XCD first: XCD x gets the q rows, then the k
+// rows, then the v rows of its nh/8 heads, which are exactly the heads whose attention its
+// workgroups run - the QKV layer and the attention can then share a launch, with nothing
+// crossing an XCD in between.  Otherwise the order is q rows, k rows, v rows of all heads.
+struct QkvRow {
+    int part;    // 0 q, 1 k, 2 v
+    int head;
+    int ph;      // position inside the head's packed rows
+};
+
+__host__ __device__ inline bool qkv_grouped(int nh) { return nh % 8 == 0; }
+
+__host__ __device__ inline QkvRow qkv_row(int p, int nh, int d)
+{
+    QkvRow r;
+    const int H = nh * d;
+    if (qkv_grouped(nh)) {
+        const int hpx = nh / 8, rx = 3 * hpx * d;
+        const int x = p / rx, q = p - x * rx;
+        r.part = q / (hpx * d);
+        const int hn = q - r.part * (hpx * d);
+        r.head = x * hpx + hn / d;
+        r.ph = hn % d;
+    } else {
+        r.part = p / H;
+        const int hn = p - r.part * H;
+        r.head = hn / d;
+        r.ph = hn % d;
+    }
+    return r;
+}
+
+// channel of packed position ph inside a head
+__host__ __device__ inline int qkv_channel(int ph, int d)
+{
+    const int r = ph & 3;
+    return (ph >> 2) * 2 + (r & 1) + ((r >= 2) ? d / 2 : 0);
+}
+
 // ---- packed activation layout ----------------------------------------------------
 // Activations that feed a linear layer are kept as MFMA B operands: per k-step (32
 // columns) and row tile (16 rows) one 1 KiB block in lane order; lane (row % 16) +
@@ -67,7 +109,10 @@ __host__ __device__ inline size_t xpk_halves(int K, int mtp) { return (size_t)((
 // bump it without disturbing the others.  A linear layer's shared row block is counted on
 // the line of the first work share that has a part of it (one line per share is enough);
 // each kind of linear layer has an array of its own, reused layer after layer by epoch.
-constexpr int kSyncStatus = 1;    // 0 = ok, else the code of the wait that gave up
+constexpr int kSyncStatus = 1;    // 0 = ok, else the code of the wait that gave up (this set-up's calls)
+constexpr int kSyncSticky = 2;    // the first non-zero status an earlier set-up found in kSyncStatus
+constexpr int kSyncMagic = 3;     // kSyncMagicValue once a set-up kernel has run on this workspace
+constexpr uint32_t kSyncMagicValue = 0x67686453u;
 constexpr int kCntStride = 32;
 constexpr int kMaxShares = 2048;  // work shares of one linear launch (workgroups x passes)
 constexpr int kSyncCnt = 32;                          // first counter line
@@ -78,7 +123,8 @@ constexpr int kCntDown = kCntGu + kMaxShares * kCntStride;
 constexpr int kCntLm = kCntDown + kMaxShares * kCntStride;   // LM head and stand-alone linear calls
 constexpr int kCntDraft = kCntLm + kMaxShares * kCntStride;  // drafting heads inside a whole decoding step
 constexpr int kCntAttn = kCntDraft + kMaxShares * kCntStride;   // up to 256 heads
-constexpr int kSyncWords = kCntAttn + 256 * kCntStride;
+constexpr int kCntXcd = kCntAttn + 256 * kCntStride;            // one line per XCD: QKV done, attention may start
+constexpr int kSyncWords = kCntXcd + 8 * kCntStride;
 
 // RMSNorm is split around the linear layer that consumes it: the producer of the residual
 // stream x also leaves xg16 = fp16(x * g * kXgScale) (g = gain of the next norm), which is
@@ -132,6 +178,8 @@ struct FusedArgs {
 
 ghd_status launch_fused(const FusedArgs& a, hipStream_t st);
 ghd_status launch_linear(const FusedArgs& a, hipStream_t st);
+ghd_status launch_qkv_attn(const FusedArgs& a, hipStream_t st);
+bool qkv_attn_available(int M, int slots, int passes, int d, int nh);
 ghd_status launch_resident_checked(const void* kernel, int key, size_t lds, int* grid);
 int fused_grid_size();
 void share_on_host(int items, int per_item, int j, int G, int item, int* out);

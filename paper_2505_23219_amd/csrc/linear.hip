@@ -1,6 +1,7 @@
 // Host side of the skinny linear layers (how an operation is cut into work shares, kernel
 // selection) and the two packing kernels (weights, activations).
 #include "linear_impl.h"
+#include "qkv_attn_impl.h"
 
 #include <mutex>
 #include <vector>
@@ -106,6 +107,26 @@ ghd_status launch_linear(const FusedArgs& a, hipStream_t st)
     return launch_linear_mt8(a, st);
 }
 
+// The QKV layer and the attention share a launch when the packed QKV rows are grouped by
+// XCD, the matrix is a wide one that needs one share per workgroup, and a kernel was built
+// for the shape.
+bool qkv_attn_available(int M, int slots, int passes, int d, int nh)
+{
+    const int mt = (M + 15) / 16;
+    if (!qkv_grouped(nh) || d != 128 || passes != 1) return false;
+    if (w_layout(3 * nh * d, nh * d).rb != 1) return false;
+    return slots >= 3 && slots <= (mt <= 4 ? 6 : 4);
+}
+
+ghd_status launch_qkv_attn(const FusedArgs& a, hipStream_t st)
+{
+    const int mt = (a.M + 15) / 16;
+    if (mt <= 1) return launch_qkv_attn_mt1(a, st);
+    if (mt <= 2) return launch_qkv_attn_mt2(a, st);
+    if (mt <= 4) return launch_qkv_attn_mt4(a, st);
+    return launch_qkv_attn_mt8(a, st);
+}
+
 // The work-share arithmetic evaluated on the host (for tests of its invariants): the unit
 // range of share j, and for `item` its first and last part and whether j's range begins
 // in it.  out[0..4] = c0, c1, first_of(item), last_of(item), begins_in(j, item).
@@ -128,7 +149,8 @@ void share_on_host(int items, int per_item, int j, int G, int item, int* out)
 // to a source row through the permutation of its kind:
 //   PLAIN    p
 //   QKV      inside every head the rows are ordered (j, j+1, j+d/2, j+1+d/2), j even,
-//            so the two rotary pairs of a quad sit in one lane of the GEMM output
+//            so the two rotary pairs of a quad sit in one lane of the GEMM output; heads
+//            grouped by XCD when their number is a multiple of 8 (see qkv_row)
 //   GATE_UP  (gate f, gate f+1, up f, up f+1): source holds gate rows [0,F) then up rows
 __global__ void k_pack2(half8* __restrict__ dst, const half_t* __restrict__ src, int N, int K,
                         int kind, int d, WLayout lay)
@@ -149,10 +171,9 @@ __global__ void k_pack2(half8* __restrict__ dst, const half_t* __restrict__ src,
         if (p < N) srow = p;
     } else if (kind == PACK_QKV) {
         if (p < N) {
-            int head = p / d, ph = p % d;
-            int r = ph & 3;
-            int ch = (ph >> 2) * 2 + (r & 1) + ((r >= 2) ? d / 2 : 0);
-            srow = head * d + ch;
+            const int H = N / 3;
+            const QkvRow qr = qkv_row(p, H / d, d);
+            srow = qr.part * H + qr.head * d + qkv_channel(qr.ph, d);
         }
     } else {
         int F = N / 2;

@@ -137,8 +137,8 @@ __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, f
     } else {   // EPI_QKV: packed rows of a head: (j, j+1, j+d/2, j+1+d/2)
         if (!mok || n0 >= op.N) return;
         const int H = a.H, d = a.d, hd = a.d >> 1;
-        int part = n0 / H, hn = n0 - part * H;
-        int head = hn / d, ph = hn - head * d;
+        const QkvRow qr = qkv_row(n0, a.nh, d);
+        const int part = qr.part, head = qr.head, ph = qr.ph;
         int jj = (ph >> 2) * 2;
         float o0 = v[0], o1 = v[1], o2 = v[2], o3 = v[3];
         if (part < 2) {
@@ -179,8 +179,9 @@ __device__ __forceinline__ void pin_order()
 // with its own k range (the first and the last may be shared with neighbouring shares);
 // RB == 4 (== R), the slots are the four tiles of one row block, all with one k range, and a
 // share that touches several blocks streams them one after the other.
+// Returns false if a wait for another share's partial sums gave up.
 template <int MT, int R, int RB>
-__device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op, Ctx& cx)
+__device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op, Ctx& cx)
 {
     static_assert(RB == 1 || R == RB, "narrow matrices: the slots are the tiles of one row block");
     constexpr int NF = R * MT;                     // accumulator fragments per wavefront
@@ -194,6 +195,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
     floatx4* red = (floatx4*)cx.lds;                       // [8][FR][64]
     float* s_rinv = (float*)(cx.lds + 8 * FR * 1024);      // 128 floats
     float* s_tmp = s_rinv + 128;                           // 1024 floats
+    int* s_wait_ok = (int*)(s_tmp + 1024);                 // thread 0's verdict on a bounded wait
     const int nks = op.lay.nks;
     const int L = cx.G * op.passes;
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -418,7 +420,7 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
             for (int it = it0; it <= it1; ++it) shared_any = run_group(sh, ls, it, it) || shared_any;
         }
     }
-    if (!shared_any) return;
+    if (!shared_any) return true;
 
     // ---- cooperative finish of the shared row blocks this workgroup has parts of.  All its
     //      partial sums were stored and signalled before it waits for anybody else's.
@@ -433,8 +435,10 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
             const int first = sh.first_of(item), last = sh.last_of(item);
             if (first == last) continue;
             const int np = last - first + 1, me = ls - first;
-            if (tid == 0) bounded_wait(a.sync, counter_of(first), (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
+            if (tid == 0)
+                *s_wait_ok = bounded_wait(a.sync, counter_of(first), (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
             __syncthreads();
+            if (!*s_wait_ok) return false;    // the other parts never arrived: nothing sensible to write
             const int f0 = NFI * me / np, f1 = NFI * (me + 1) / np;
             for (int f = f0 + wave; f < f1; f += 8) {
                 // Sum the parts in index order (fixed order: the result does not depend on
@@ -455,14 +459,11 @@ __device__ __forceinline__ void gemm_phase(const FusedArgs& a, const GemmOp& op,
             }
         }
     }
+    return true;
 }
 
-template <int MT, int R, int RB>
-__global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
+__device__ __forceinline__ GemmOp linear_op_of(const FusedArgs& a)
 {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-    const uint32_t touched = touch_kernel_arguments();
-    Ctx cx = make_ctx(a, lds);
     GemmOp op;
     op.W = a.lin_W;
     op.N = a.lin_N;
@@ -479,6 +480,16 @@ __global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
     op.cnt = a.sync + a.lin_cnt;
     op.epoch = a.lin_epoch;
     op.passes = a.lin_passes;
+    return op;
+}
+
+template <int MT, int R, int RB>
+__global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t touched = touch_kernel_arguments();
+    Ctx cx = make_ctx(a, lds);
+    const GemmOp op = linear_op_of(a);
     gemm_phase<MT, R, RB>(a, op, cx);
     // (keeps the early reads alive; never true: lin_N is positive)
     if (touched == 0x9e3779b9u && a.lin_N < 0) a.sync[kSyncStatus] = 4u;
@@ -487,7 +498,7 @@ __global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
 template <int MT, int R>
 constexpr size_t linear_lds_bytes()
 {
-    return 8 * (size_t)(R * MT < 16 ? R * MT : 16) * 1024 + (128 + 1024) * sizeof(float);
+    return 8 * (size_t)(R * MT < 16 ? R * MT : 16) * 1024 + (128 + 1024 + 4) * sizeof(float);
 }
 
 template <int MT, int R, int RB>

@@ -73,6 +73,10 @@ __host__ __device__ __forceinline__ Share make_share(int items, int per_item, in
 // workgroup, not their stores still on the way to the L2.)  s_waitcnt vmcnt(0).
 __device__ __forceinline__ void wait_own_stores() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+// Invalidates this compute unit's vector L1 (workgroup-scope buffer_inv): loads that follow
+// are served by the L2.
+__device__ __forceinline__ void invalidate_l1() { asm volatile("buffer_inv sc0" ::: "memory"); }
+
 __device__ __forceinline__ uint32_t poll(uint32_t* p)
 {
     // a read-modify-write that changes nothing: it is served where the counting atomics
@@ -83,18 +87,20 @@ __device__ __forceinline__ uint32_t poll(uint32_t* p)
 // Waits until *p >= target.  Gives up (and raises the status word to `code`) after
 // kWaitTicks of wall-clock time, or as soon as another workgroup has given up, so that a
 // launch that is not fully resident ends with an error instead of hanging.  One thread calls.
-__device__ __forceinline__ void bounded_wait(uint32_t* sync, uint32_t* p, uint32_t target,
+// Returns false if it gave up: what was waited for is then not there.
+__device__ __forceinline__ bool bounded_wait(uint32_t* sync, uint32_t* p, uint32_t target,
                                              uint32_t code)
 {
-    if (poll(p) >= target) return;
+    if (poll(p) >= target) return true;
     const long long t0 = wall_clock64();
     while (poll(p) < target) {
         if (wall_clock64() - t0 > kWaitTicks || ld_relaxed(sync + kSyncStatus) != 0) {
             atomicCAS(sync + kSyncStatus, 0u, code);
-            break;
+            return false;
         }
         __builtin_amdgcn_s_sleep(8);
     }
+    return true;
 }
 
 // The argument block is a few 64-byte lines of kernel-argument memory, which the compiler
