@@ -9,11 +9,9 @@ template <int MT, int D>
 __global__ __launch_bounds__(kFT) void k_attention(const FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const uint32_t touched = touch_kernel_arguments();
+    touch_kernel_arguments();
     Ctx cx = make_ctx(a, lds);
     attn_phase<MT, D>(a, cx, a.att_q, a.att_k, a.att_v, a.att_out, a.att_epoch);
-    // (keeps the early reads alive; never true: nh is positive)
-    if (touched == 0x9e3779b9u && a.nh < 0) a.sync[kSyncStatus] = 4u;
 }
 
 // ---------------------------------------------------------------------------

@@ -200,36 +200,47 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     const int L = cx.G * op.passes;
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-    // ---- RMSNorm factor per row from the per-tile sums of squares ss[tile][Mpad]:
-    //      thread (rq, part) adds 4 rows of every P-th tile, lanes of a wavefront that share
-    //      rq are combined by shuffles, the 8 wavefronts through LDS; fixed order throughout.
-    bool rinv_ready = !op.rscale;
-    auto compute_rinv = [&]() {
-        const int n_ss = op.K >> 4;
-        const int RQ = a.Mpad >> 2, P = kFT / RQ;
-        const int rq = tid % RQ, part = tid / RQ;
-        floatx4 s4 = {0.f, 0.f, 0.f, 0.f};
+    // ---- RMSNorm factor per row from the per-tile sums of squares ss[tile][Mpad], in two
+    //      steps.  Early, behind the stream's first loads (it has to wait for those anyway):
+    //      thread (rq, part) adds 4 rows of every P-th tile and the lanes of a wavefront that
+    //      share rq are combined by shuffles - no barrier, so that no wavefront waits for
+    //      another before it starts streaming.
+    //      Late, when the stream is over and the workgroup meets anyway: the 8 wavefronts'
+    //      sums are added through LDS.  Fixed order throughout.
+    bool rinv_loaded = !op.rscale, rinv_ready = !op.rscale;
+    floatx4 rs4 = {0.f, 0.f, 0.f, 0.f}, sst[8];
+    const int RQ = a.Mpad >> 2, n_ss = op.K >> 4;
+    const int P = kFT / RQ, rq = tid % RQ, part = tid / RQ;
+    auto rinv_request = [&](int t0) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            sst[q] = *(const floatx4*)(a.ss + (size_t)min(t0 + q * P, n_ss - 1) * a.Mpad + rq * 4);
+    };
+    auto rinv_add = [&](int t0) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (t0 + q * P < n_ss) rs4 += sst[q];
+    };
+    auto rinv_sum = [&]() {
         for (int t0 = part; t0 < n_ss; t0 += 8 * P) {
-            floatx4 sst[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                sst[q] = *(const floatx4*)(a.ss + (size_t)min(t0 + q * P, n_ss - 1) * a.Mpad + rq * 4);
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                if (t0 + q * P < n_ss) s4 += sst[q];
+            rinv_request(t0);
+            rinv_add(t0);
         }
         for (int off = RQ; off < 64; off <<= 1) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) s4[r] += __shfl_xor(s4[r], off);
+            for (int r = 0; r < 4; ++r) rs4[r] += __shfl_xor(rs4[r], off);
         }
-        if (lane < RQ) *(floatx4*)(s_tmp + (wave * RQ + lane) * 4) = s4;
+        rinv_loaded = true;
+    };
+    // (the barrier that makes s_rinv visible is the first one of the reduction that follows)
+    auto rinv_finish = [&]() {
+        if (lane < RQ) *(floatx4*)(s_tmp + (wave * RQ + lane) * 4) = rs4;
         __syncthreads();
         if (tid < a.Mpad) {
             float tot = 0.f;
             for (int w = 0; w < 8; ++w) tot += s_tmp[(w * RQ + (tid >> 2)) * 4 + (tid & 3)];
             s_rinv[tid] = (1.0f / kXgScale) / sqrtf(tot / (float)op.K + a.eps);
         }
-        __syncthreads();
         rinv_ready = true;
     };
 
@@ -342,10 +353,9 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
                 self(self, std::integral_constant<int, p + 1>{});
             }
         };
+        // The norm factors are only needed by the epilogues, but their loads are cheapest here.
         prologue(prologue, std::integral_constant<int, 0>{});
-        // The norm factors are only needed by the epilogues, but their loads are cheapest here:
-        // they arrive together with the first ring, which the wavefront has to wait for anyway.
-        if (!rinv_ready) compute_rinv();
+        if (!rinv_loaded) rinv_sum();
         {
             // does every k-step of this wavefront lie inside every used slot's range?  (What an
             // unused slot accumulates is never looked at.)
@@ -364,6 +374,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         //      a wide matrix; all of a narrow one): their partial sums are stored and signalled
         //      as soon as they are complete, so that they are on their way while the rest of the
         //      share is finished.
+        if (!rinv_ready) rinv_finish();
         bool any_shared = false;
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
@@ -487,12 +498,10 @@ template <int MT, int R, int RB>
 __global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const uint32_t touched = touch_kernel_arguments();
+    touch_kernel_arguments();
     Ctx cx = make_ctx(a, lds);
     const GemmOp op = linear_op_of(a);
     gemm_phase<MT, R, RB>(a, op, cx);
-    // (keeps the early reads alive; never true: lin_N is positive)
-    if (touched == 0x9e3779b9u && a.lin_N < 0) a.sync[kSyncStatus] = 4u;
 }
 
 template <int MT, int R>

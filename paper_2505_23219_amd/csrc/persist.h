@@ -106,15 +106,25 @@ __device__ __forceinline__ bool bounded_wait(uint32_t* sync, uint32_t* p, uint32
 // The argument block is a few 64-byte lines of kernel-argument memory, which the compiler
 // reads field by field as the code needs them, one memory round trip after the other.  One
 // word of every line is requested here, back to back at the start of the kernel, so that
-// the lines arrive together and the later reads find them in the scalar cache.
-__device__ __forceinline__ uint32_t touch_kernel_arguments()
+// the lines arrive together and the later reads find them in the scalar cache.  (Written as
+// one block of scalar loads with its own wait: left to the compiler, the five results are
+// parked one by one, with a wait after each load.)
+__device__ __forceinline__ void touch_kernel_arguments()
 {
+    static_assert(sizeof(FusedArgs) > 256 && sizeof(FusedArgs) <= 320, "five 64-byte lines");
     typedef const __attribute__((address_space(4))) uint32_t* kernarg_words;
     kernarg_words kp = (kernarg_words)__builtin_amdgcn_kernarg_segment_ptr();
-    uint32_t t = 0;
-#pragma unroll
-    for (int i = 0; i < (int)((sizeof(FusedArgs) + 63) / 64); ++i) t ^= kp[i * 16];
-    return t;
+    uint32_t t0, t1, t2, t3, t4;
+    asm volatile(
+        "s_load_dword %0, %5, 0x0\n\t"
+        "s_load_dword %1, %5, 0x40\n\t"
+        "s_load_dword %2, %5, 0x80\n\t"
+        "s_load_dword %3, %5, 0xc0\n\t"
+        "s_load_dword %4, %5, 0x100\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4)
+        : "s"(kp)
+        : "memory");
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs; neighbours in the work sequence (which

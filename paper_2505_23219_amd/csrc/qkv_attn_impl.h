@@ -17,7 +17,7 @@ template <int MT, int R, int D>
 __global__ __launch_bounds__(kFT) void k_qkv_attn(const FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const uint32_t touched = touch_kernel_arguments();
+    touch_kernel_arguments();
     Ctx cx = make_ctx(a, lds);
     const GemmOp op = linear_op_of(a);
     const bool ok = gemm_phase<MT, R, 1>(a, op, cx);
@@ -45,8 +45,6 @@ __global__ __launch_bounds__(kFT) void k_qkv_attn(const FusedArgs a)
         return true;
     };
     attn_phase<MT, D, true>(a, cx, a.att_q, a.att_k, a.att_v, a.att_out, a.att_epoch, gate);
-    // (keeps the early reads alive; never true: lin_N is positive)
-    if (touched == 0x9e3779b9u && a.lin_N < 0) a.sync[kSyncStatus] = 4u;
 }
 
 template <int MT, int R, int D>
