@@ -435,12 +435,22 @@ def main():
     ap.add_argument("--tree-part", action="store_true",
                     help="also time the drafted tokens' own attention block from the mask nonzeros and as a "
                          "masked MFMA tile (adds \"tree_part\")")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="only run the stream probe (the bare weight stream with matrix-core, dot-product and "
+                         "no multiply; a program of its own built next to the library) and print its table")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also launch one plain 1 GiB copy kernel (for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the verification step runs on a single MI355X and "
                  "there is no multi-GPU path (--gpus %d refused)" % args.gpus)
+
+    if args.stream_probe:
+        import subprocess
+        probe = os.path.join(ROOT, "paper_2505_23219_amd", "ghd_stream_probe")
+        if not os.path.exists(probe):
+            sys.exit("%s is not built: run python -m paper_2505_23219_amd.build" % probe)
+        sys.exit(subprocess.run([probe]).returncode)
 
     import torch
     from paper_2505_23219_amd import binding as B, model, workloads as wl

@@ -1,4 +1,4 @@
-"""Builds libghd.so (gfx950) in-tree with hipcc.  Run as a module or call build()."""
+"""Builds libghd.so and the stream probe (gfx950) in-tree with hipcc.  Run as a module or call build()."""
 from __future__ import annotations
 
 import concurrent.futures
@@ -10,6 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libghd.so")
+PROBE = os.path.join(HERE, "ghd_stream_probe")       # measurement tool (bench.py --stream-probe), its own program
+PROBE_SOURCE = "stream_probe.hip"
 SOURCES = ["api.hip", "fused.hip", "linear.hip", "linear_mt1.hip", "linear_mt2.hip", "linear_mt4.hip",
            "linear_mt8.hip", "qkv_attn_mt1.hip", "qkv_attn_mt2.hip", "qkv_attn_mt4.hip", "qkv_attn_mt8.hip",
            "accept.hip", "draft.hip", "coo.hip"]
@@ -45,8 +47,13 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    cmd = [_hipcc()] + [f for f in FLAGS if f != "-fPIC"] + ["-o", PROBE, os.path.join(CSRC, PROBE_SOURCE)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for %s:\n%s" % (PROBE_SOURCE, r.stderr))
     if verbose:
         print("built", LIB)
+        print("built", PROBE)
     return LIB
 
 

@@ -22,7 +22,8 @@ import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CALIBRATION_BYTES = 1 << 30          # bench.py --pmc-calibrate copies 1 GiB
-LINEAR_KERNEL = re.compile(r"k_linear<4, 1>")
+LINEAR_KERNEL = re.compile(r"k_linear<4, \d+, \d+>")        # linear-only launches of the M = 64 step
+FUSED_KERNEL = re.compile(r"k_qkv_attn<4, \d+, \d+>")      # QKV layer + attention in one launch
 COPY_KERNEL = re.compile(r"k_debug_copy")
 
 
@@ -50,8 +51,9 @@ def stats(path: str, out: str, command: str) -> None:
         f.write("# rocprofv3 kernel statistics: verification step, workload stack7b\n\n")
         f.write("Command (on an MI355X, from the repository root):\n\n    %s\n\n" % command)
         f.write("Kernels of this library only (model set-up and PyTorch fill kernels left out); "
-                "the run holds tree steps (M=64: `k_linear<4, 1>`, `k_attention<4, 128>`) and 1-token "
-                "decode steps (`k_linear<1, 2>`, `k_attention<1, 128>`).\n\n")
+                "the run holds tree steps (M=64: `k_linear<4, R, RB>`, `k_qkv_attn<4, R, 128>`) and 1-token "
+                "decode steps (`k_linear<1, R, RB>`, `k_qkv_attn<1, R, 128>`); R = row tiles streamed together, "
+                "RB = tiles per row block (4: narrow matrices, split along K).\n\n")
         f.write("| kernel | calls | avg us | min us | max us | total ms | share |\n|---|---|---|---|---|---|---|\n")
         for r in sorted(rows, key=lambda r: -int(r["TotalDurationNs"])):
             f.write("| `%s` | %s | %.2f | %.2f | %.2f | %.3f | %.1f%% |\n" % (
@@ -61,7 +63,7 @@ def stats(path: str, out: str, command: str) -> None:
 
 
 def _counter(path: str, name: str):
-    copy, lin = [], []
+    copy, lin, fused = [], [], []
     for r in csv.DictReader(open(path)):
         if r["Counter_Name"] != name:
             continue
@@ -70,29 +72,40 @@ def _counter(path: str, name: str):
             copy.append(v)
         elif LINEAR_KERNEL.search(r["Kernel_Name"]):
             lin.append(v)
+        elif FUSED_KERNEL.search(r["Kernel_Name"]):
+            fused.append(v)
     if not copy or not lin:
         sys.exit("%s: calibration copy or linear-layer dispatches missing" % path)
-    return sum(copy) / len(copy), sum(lin) / len(lin), len(lin)
+    avg = lambda v: sum(v) / len(v) if v else 0.0
+    return avg(copy), avg(lin), len(lin), avg(fused), len(fused)
 
 
 def traffic(fetch_csv: str, write_csv: str, out: str, command: str) -> None:
-    f_copy, f_lin, n = _counter(fetch_csv, "FETCH_SIZE")
-    w_copy, w_lin, _ = _counter(write_csv, "WRITE_SIZE")
+    f_copy, f_lin, n, f_fus, nf = _counter(fetch_csv, "FETCH_SIZE")
+    w_copy, w_lin, _, w_fus, _ = _counter(write_csv, "WRITE_SIZE")
     f_scale = CALIBRATION_BYTES / f_copy       # bytes per counter unit
     w_scale = CALIBRATION_BYTES / w_copy
     fetched, written = f_lin * f_scale, w_lin * w_scale
     with open(out, "w") as f:
-        f.write("# HBM traffic of the linear-layer kernel `k_linear<4, 1>`, workload stack7b\n\n")
+        f.write("# HBM traffic of the linear-layer kernel `k_linear<4, R, RB>`, workload stack7b\n\n")
         f.write("Commands (on an MI355X, from the repository root; one counter per run):\n\n")
         f.write("    %s\n\n" % command.replace("COUNTER", "FETCH_SIZE"))
         f.write("    %s\n\n" % command.replace("COUNTER", "WRITE_SIZE"))
         f.write("Calibration: the 1 GiB copy kernel of the same run (reads 1 GiB, writes 1 GiB) "
                 "reads FETCH_SIZE = %.1f and WRITE_SIZE = %.1f, i.e. %.1f and %.1f bytes per "
                 "counter unit.\n\n" % (f_copy, w_copy, f_scale, w_scale))
-        f.write("Average over %d dispatches (4 per layer + LM head, M = 64):\n\n" % n)
-        f.write("| | counter avg | bytes per launch |\n|---|---|---|\n")
-        f.write("| fetched | %.1f | %d |\n| written | %.1f | %d |\n\n" % (f_lin, fetched, w_lin, written))
-        f.write("traffic_bytes_per_launch: %d\n" % int(fetched + written))
+        f.write("Average over %d dispatches of the linear-only launches (output, gate|up and down "
+                "projection of every layer + LM head, M = 64)" % n)
+        if nf:
+            f.write(" and over %d dispatches of `k_qkv_attn<4, R, 128>` (QKV layer + tree attention)" % nf)
+        f.write(":\n\n| kernel | | counter avg | bytes per launch |\n|---|---|---|---|\n")
+        f.write("| k_linear | fetched | %.1f | %d |\n| k_linear | written | %.1f | %d |\n" % (f_lin, fetched, w_lin, written))
+        if nf:
+            f.write("| k_qkv_attn | fetched | %.1f | %d |\n| k_qkv_attn | written | %.1f | %d |\n"
+                    % (f_fus, f_fus * f_scale, w_fus, w_fus * w_scale))
+        f.write("\ntraffic_bytes_per_launch: %d\n" % int(fetched + written))
+        if nf:
+            f.write("qkv_attention_traffic_bytes_per_launch: %d\n" % int(f_fus * f_scale + w_fus * w_scale))
         f.write("source_sha256: %s\n" % source_digest())
 
 
