@@ -78,6 +78,7 @@ static bool fill_plan(FusedArgs& a, int M, int N, int K)
     if (!plan_linear(M, N, K, grid_for_sizing(), &pl)) return false;
     a.lin_slots = pl.slots;
     a.lin_passes = pl.passes;
+    a.lin_whole = pl.whole;
     return true;
 }
 
@@ -915,15 +916,16 @@ void ghd_debug_share(int items, int per_item, int j, int G, int item, int* out5)
     share_on_host(items, per_item, j, G, item, out5);
 }
 
-/* out2 = {row tiles a share of a wide matrix handles at once, shares per workgroup} for a
- * linear layer [N, K] at M rows on G workgroups; returns 0, or -1 if the shape needs more
- * shares than the library is laid out for. */
-int ghd_debug_plan(int M, int N, int K, int G, int* out2)
+/* out3 = {row tiles a share handles at once, shares per workgroup, whole tiles (1) or k ranges of
+ * four-tile row blocks (0)} for a linear layer [N, K] at M rows on G workgroups; returns 0, or -1
+ * if the shape needs more shares than the library is laid out for. */
+int ghd_debug_plan(int M, int N, int K, int G, int* out3)
 {
     LinPlan pl;
     if (!plan_linear(M, N, K, G, &pl)) return -1;
-    out2[0] = pl.slots;
-    out2[1] = pl.passes;
+    out3[0] = pl.slots;
+    out3[1] = pl.passes;
+    out3[2] = pl.whole;
     return 0;
 }
 

@@ -161,6 +161,7 @@ struct FusedArgs {
     int lin_N, lin_K, lin_epi;
     int lin_slots;         // wide matrices: row tiles a work share handles at once (template choice)
     int lin_passes;        // work shares per workgroup
+    int lin_whole;         // wide matrices: deal whole tiles (no tile is shared between shares)
     int lin_rscale;        // the input is xg16: scale output row m by the RMSNorm factor of x[m]
     const half_t* lin_gnext;   // EPI_RESID: gain of the norm that follows (xg16 is rewritten)
     half_t *lin_kc, *lin_vc;   // EPI_QKV: the layer's cache
@@ -187,7 +188,7 @@ void attn_share_on_host(int nh, int ntile, int j, int G, int head, int* out);
 
 // How a linear layer is cut for G workgroups and row tiles of M: passes (work shares per
 // workgroup) and, for wide matrices, the most row tiles one share touches.  Host only.
-struct LinPlan { int slots, passes; };
+struct LinPlan { int slots, passes, whole; };
 bool plan_linear(int M, int N, int K, int G, LinPlan* out);
 size_t linear_part_floats(int M, int G);
 

@@ -43,6 +43,7 @@ struct GemmOp {
     uint32_t* cnt;       // the operation's counters
     uint32_t epoch;      // how many times these counters were used before (layer index)
     int passes;          // shares per workgroup
+    bool whole;          // wide matrices: shares are whole tiles
 };
 
 
@@ -175,10 +176,11 @@ __device__ __forceinline__ void pin_order()
 }
 
 // MT = 16-row tiles of x (Mpad / 16).  R = weight tiles streamed together.  RB = tiles per
-// row block of the packed matrix: RB == 1, a share's R slots are consecutive tiles, each
-// with its own k range (the first and the last may be shared with neighbouring shares);
-// RB == 4 (== R), the slots are the four tiles of one row block, all with one k range, and a
-// share that touches several blocks streams them one after the other.
+// item of the work shares: RB == 1, a share's R slots are consecutive tiles, each with its
+// own k range (whole tiles: the full range; else the first and the last may be shared with
+// neighbouring shares), in either storage layout; RB == 4 (== R), the slots are the four
+// tiles of one row block of a narrow matrix, all with one k range, and a share that touches
+// several blocks streams them one after the other.
 // Returns false if a wait for another share's partial sums gave up.
 template <int MT, int R, int RB>
 __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op, Ctx& cx)
@@ -197,6 +199,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     float* s_tmp = s_rinv + 128;                           // 1024 floats
     int* s_wait_ok = (int*)(s_tmp + 1024);                 // thread 0's verdict on a bounded wait
     const int nks = op.lay.nks;
+    const int blk_sh = op.lay.blk == kWideBlock ? 3 : 2;   // tiles per storage block: 8 or 4
+    static_assert(kWideBlock == 8 && kRbNarrow == 4, "storage blocks of 8 or 4 tiles");
     const int L = cx.G * op.passes;
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
@@ -244,6 +248,17 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         rinv_ready = true;
     };
 
+    // Share ls of the launch.  With whole tiles, the tiles (not their k-steps) are dealt out and
+    // every share covers the whole k range of its tiles: nothing is shared between shares.
+    auto share_of = [&](int ls) {
+        if (!op.whole) return make_share(op.lay.nitems, nks, ls, L);
+        Share sh = make_share(op.lay.ntiles, 1, ls, L);
+        sh.c0 *= nks;
+        sh.c1 *= nks;
+        return sh;
+    };
+    auto is_shared = [&](const Share& sh, int item) { return !op.whole && sh.first_of(item) != sh.last_of(item); };
+
     // Slot 0 of a share holds the partial of the row block its range begins in, slot 1 that
     // of the block it ends in (when that is another one); blocks in between are whole.
     auto slot_of = [&](const Share& sh, int ls, int item) -> float* {
@@ -273,7 +288,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             const int k0 = max(sh.c0 - ai * nks, 0), k1 = min(sh.c1 - ai * nks, nks);
             s_k0[t] = k0;
             s_k1[t] = valid ? k1 : k0;
-            s_blk[t] = RB == 1 ? (ai >> 3) * nks * kWideBlock + (ai & (kWideBlock - 1)) : ai * nks * RB + t;
+            s_blk[t] = RB == 1 ? (ai >> blk_sh) * (nks << blk_sh) + (ai & ((1 << blk_sh) - 1)) : ai * nks * RB + t;
             if (valid) {
                 kmin = min(kmin, k0);
                 kmax = max(kmax, k1);
@@ -304,7 +319,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
 #pragma unroll
             for (int t = 0; t < R; ++t) {
                 const int st = min(max(sl, s_k0[t]), max(s_k1[t] - 1, s_k0[t]));
-                const char* wq = (const char*)op.W + ((size_t)(s_blk[t] + st * (RB == 1 ? kWideBlock : RB)) << 10);
+                const char* wq = (const char*)op.W + ((size_t)(s_blk[t] + (RB == 1 ? st << blk_sh : st * RB)) << 10);
                 wr[p][t] = __builtin_nontemporal_load((const half8*)(wq + lane16));
             }
         };
@@ -380,7 +395,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         for (int k = 0; k < 2; ++k) {
             const int item = k ? item1 : item0;
             if (k && item1 == item0) break;
-            any_shared = any_shared || sh.first_of(item) != sh.last_of(item);
+            any_shared = any_shared || is_shared(sh, item);
         }
         constexpr int kSignalRound = RB == 1 ? 0 : (NF - 1) / FR;
         static_assert(RB != 1 || 2 * MT <= FR || NF <= FR, "the shared slots' fragments are in the first round");
@@ -398,7 +413,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
                 if (!valid_of(t)) continue;
                 const int item = item_of(t);
                 const int tile = RB == 1 ? item : item * RB + t;
-                if (sh.first_of(item) == sh.last_of(item))
+                if (!is_shared(sh, item))
                     epilogue(a, op, v, b * 16 + c, tile * 16 + g4 * 4, lane, s_rinv);
                 else
                     *(floatx4*)(slot_of(sh, ls, item) + ((size_t)((RB == 1 ? 0 : t) * MT + b) * 64 + lane) * 4) = v;
@@ -410,8 +425,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
                 for (int k = 0; k < 2; ++k) {
                     const int item = k ? item1 : item0;
                     if (k && item1 == item0) break;
-                    const int first = sh.first_of(item);
-                    if (first != sh.last_of(item)) atomicAdd(counter_of(first), 1u);
+                    if (is_shared(sh, item)) atomicAdd(counter_of(sh.first_of(item)), 1u);
                 }
             }
         }
@@ -422,7 +436,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     bool shared_any = false;
     for (int p = 0; p < op.passes; ++p) {
         const int ls = cx.j * op.passes + p;
-        const Share sh = make_share(op.lay.nitems, nks, ls, L);
+        const Share sh = share_of(ls);
         if (sh.c0 >= sh.c1) continue;
         const int it0 = sh.c0 / nks, it1 = (sh.c1 - 1) / nks;
         if constexpr (RB == 1) {
@@ -437,14 +451,14 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     //      partial sums were stored and signalled before it waits for anybody else's.
     for (int p = 0; p < op.passes; ++p) {
         const int ls = cx.j * op.passes + p;
-        const Share sh = make_share(op.lay.nitems, nks, ls, L);
+        const Share sh = share_of(ls);
         if (sh.c0 >= sh.c1) continue;
         const int it0 = sh.c0 / nks, it1 = (sh.c1 - 1) / nks;
         for (int k = 0; k < 2; ++k) {
             const int item = k ? it1 : it0;
             if (k && it1 == it0) break;
+            if (!is_shared(sh, item)) continue;
             const int first = sh.first_of(item), last = sh.last_of(item);
-            if (first == last) continue;
             const int np = last - first + 1, me = ls - first;
             if (tid == 0)
                 *s_wait_ok = bounded_wait(a.sync, counter_of(first), (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
@@ -491,6 +505,7 @@ __device__ __forceinline__ GemmOp linear_op_of(const FusedArgs& a)
     op.cnt = a.sync + a.lin_cnt;
     op.epoch = a.lin_epoch;
     op.passes = a.lin_passes;
+    op.whole = a.lin_whole != 0;
     return op;
 }
 
@@ -526,7 +541,7 @@ template <int MT>
 ghd_status launch_linear_mt(const FusedArgs& a, hipStream_t st)
 {
     const WLayout lay = w_layout(a.lin_N, a.lin_K);
-    if (lay.rb != 1) return launch_linear_t<MT, kRbNarrow, kRbNarrow>(a, st);
+    if (lay.rb != 1 && !a.lin_whole) return launch_linear_t<MT, kRbNarrow, kRbNarrow>(a, st);
     constexpr int CAP = MT <= 4 ? 8 : 4;
     switch (a.lin_slots) {
     case 1: return launch_linear_t<MT, 1, 1>(a, st);

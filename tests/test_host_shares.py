@@ -84,35 +84,36 @@ def test_share_invariants(items, per_item, G):
 
 @pytest.mark.parametrize("M,N,K", [(64, 12288, 4096), (64, 4096, 4096), (64, 22016, 4096), (64, 4096, 11008),
                                    (64, 32000, 4096), (1, 32000, 4096), (128, 22016, 4096), (128, 32000, 4096),
-                                   (64, 15360, 5120), (64, 27648, 5120), (16, 160000, 4096), (128, 16384 * 16, 64)])
+                                   (64, 15360, 5120), (64, 27648, 5120), (16, 160000, 4096), (128, 16384 * 16, 64),
+                                   (1, 4096, 4096), (16, 4096, 11008), (17, 4096, 11008), (8, 5120, 13824), (3, 130, 688)])
 def test_linear_plan(M, N, K):
-    """The cut of a linear layer: a wide matrix (640 tiles of 16 rows or more) is cut so that no
-    share touches more row tiles than the kernel keeps accumulators for (8 up to 64 rows of x,
-    4 above), with as few shares per workgroup as that takes; a narrow one always streams one
-    block of four tiles at a time, one share per workgroup."""
+    """The cut of a linear layer.  A wide matrix (640 tiles of 16 rows or more), and a narrow one
+    at up to 16 rows of x, is dealt out in whole tiles, so that no share has more tiles than the
+    kernel keeps accumulators for (8 up to 64 rows of x, 4 above), with as few shares per
+    workgroup as that takes; a narrow one at more rows always streams a k range of one block of
+    four tiles at a time, one share per workgroup."""
     lib = B.lib()
     G = 256
-    out = (C.c_int * 2)()
+    out = (C.c_int * 3)()
     rc = lib.ghd_debug_plan(M, N, K, G, out)
-    ntiles, nks = (N + 15) // 16, (K + 31) // 32
+    ntiles = (N + 15) // 16
     cap = 8 if M <= 64 else 4
-    if ntiles < 640:
-        assert rc == 0 and list(out) == [4, 1]
+    if ntiles < 640 and M > 16:
+        assert rc == 0 and list(out) == [4, 1, 0]
         return
 
     def most(P):
         worst = 0
         for j in range(G * P):
-            c0, c1 = share(lib, ntiles, nks, j, G * P)[:2]
-            if c1 > c0:
-                worst = max(worst, (c1 - 1) // nks - c0 // nks + 1)
+            c0, c1 = share(lib, ntiles, 1, j, G * P)[:2]
+            worst = max(worst, c1 - c0)
         return worst
 
     feasible = [P for P in range(1, 9) if most(P) <= cap]
     if not feasible:
         assert rc == -1
         return
-    assert rc == 0 and out[1] == feasible[0] and out[0] == most(feasible[0]) and 1 <= out[0] <= cap
+    assert rc == 0 and out[2] == 1 and out[1] == feasible[0] and out[0] == most(feasible[0]) and 1 <= out[0] <= cap
 
 
 def attn_share(lib, nh, ntile, j, G, head):
