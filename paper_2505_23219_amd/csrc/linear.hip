@@ -64,45 +64,48 @@ ghd_status launch_resident_checked(const void* kernel, int key, size_t lds, int*
 // shares that differ by one tile and of x being read once per share.  That is how wide
 // matrices are cut at every M (measured against equal shares of k-steps with the boundary
 // tiles finished jointly: 5.7% of a 64-row step, 4.8% of a 1-row step), and narrow ones up to
-// 16 rows of x, where x is small.  Narrow matrices at more rows are cut into k ranges of
-// four-tile row blocks: a share then reads a fraction of x, and the blocks' partial sums are
-// exchanged.  Every share streams all the row tiles it touches at once, so their number is
-// bounded by the accumulator registers (8 tiles up to 64 rows of x, 4 above); more shares
-// per workgroup (passes) make the shares smaller until that holds.
-static int env_int(const char* name, int dflt)
+// 16 rows of x (where x is small) unless the one-tile difference between shares costs more
+// stream time than the exchange it saves (about 3 us a launch).  Otherwise narrow matrices
+// are cut into k ranges of four-tile row blocks: a share then reads a fraction of x, and the
+// blocks' partial sums are exchanged.  Every share streams all the row tiles it touches at
+// once, so their number is bounded by the accumulator registers (8 tiles up to 64 rows of x,
+// 4 above); more shares per workgroup (passes) make the shares smaller until that holds.
+constexpr double kStreamBytesPerUs = 6.4e6;    // what a launch streams at best (measured)
+constexpr double kExchangeUs = 3.0;            // what finishing shared row blocks jointly costs a launch
+
+static bool plan_whole(const WLayout& lay, int mt, int G, LinPlan* out)
 {
-    const char* e = getenv(name);
-    return (e && *e) ? atoi(e) : dflt;
+    const int cap = mt <= 4 ? 8 : 4;
+    for (int P = 1; P <= kMaxShares / (G > 0 ? G : 1) && P <= 8; ++P) {
+        int most = 1;
+        for (int ls = 0; ls < G * P; ++ls) {
+            const Share sh = make_share(lay.ntiles, 1, ls, G * P);
+            most = sh.c1 - sh.c0 > most ? sh.c1 - sh.c0 : most;
+        }
+        if (most <= cap) {
+            out->slots = most;
+            out->passes = P;
+            out->whole = 1;
+            return true;
+        }
+    }
+    return false;
 }
 
 bool plan_linear(int M, int N, int K, int G, LinPlan* out)
 {
     const WLayout lay = w_layout(N, K);
     const int mt = (M + 15) / 16;
-    const bool whole = lay.rb == 1 ? env_int("GHD_WHOLE_TILES", 1) != 0 : mt <= env_int("GHD_NARROW_WHOLE_MT", 1);
-    if (lay.rb != 1 && !whole) {
-        out->slots = kRbNarrow;
-        out->passes = 1;
-        out->whole = 0;
-        return true;
+    if (lay.rb == 1) return plan_whole(lay, mt, G, out);
+    if (mt <= 1 && plan_whole(lay, mt, G, out)) {
+        // stream time lost to the shares with one tile more than the average
+        const double excess = (double)out->slots * out->passes * G / lay.ntiles - 1.0;
+        if (excess * (2.0 * N * K / kStreamBytesPerUs) < kExchangeUs) return true;
     }
-    const int cap = mt <= 4 ? 8 : 4;
-    for (int P = 1; P <= kMaxShares / (G > 0 ? G : 1) && P <= 8; ++P) {
-        int most = 1;
-        for (int ls = 0; ls < G * P; ++ls) {
-            const Share sh = whole ? make_share(lay.ntiles, 1, ls, G * P) : make_share(lay.nitems, lay.nks, ls, G * P);
-            if (sh.c0 >= sh.c1) continue;
-            const int n = whole ? sh.c1 - sh.c0 : (sh.c1 - 1) / lay.nks - sh.c0 / lay.nks + 1;
-            most = n > most ? n : most;
-        }
-        if (most <= cap) {
-            out->slots = most;
-            out->passes = P;
-            out->whole = whole;
-            return true;
-        }
-    }
-    return false;
+    out->slots = kRbNarrow;
+    out->passes = 1;
+    out->whole = 0;
+    return true;
 }
 
 // partial-sum slots: two per share, each one row block of fragments; sized for the most

@@ -87,20 +87,17 @@ def test_share_invariants(items, per_item, G):
                                    (64, 15360, 5120), (64, 27648, 5120), (16, 160000, 4096), (128, 16384 * 16, 64),
                                    (1, 4096, 4096), (16, 4096, 11008), (17, 4096, 11008), (8, 5120, 13824), (3, 130, 688)])
 def test_linear_plan(M, N, K):
-    """The cut of a linear layer.  A wide matrix (640 tiles of 16 rows or more), and a narrow one
-    at up to 16 rows of x, is dealt out in whole tiles, so that no share has more tiles than the
-    kernel keeps accumulators for (8 up to 64 rows of x, 4 above), with as few shares per
-    workgroup as that takes; a narrow one at more rows always streams a k range of one block of
-    four tiles at a time, one share per workgroup."""
+    """The cut of a linear layer.  A wide matrix (640 tiles of 16 rows or more) is dealt out in
+    whole tiles, so that no share has more tiles than the kernel keeps accumulators for (8 up to
+    64 rows of x, 4 above), with as few shares per workgroup as that takes.  So is a narrow one at
+    up to 16 rows of x if its tiles spread evenly enough over the workgroups; otherwise a narrow
+    one streams a k range of one block of four tiles at a time, one share per workgroup."""
     lib = B.lib()
     G = 256
     out = (C.c_int * 3)()
     rc = lib.ghd_debug_plan(M, N, K, G, out)
     ntiles = (N + 15) // 16
     cap = 8 if M <= 64 else 4
-    if ntiles < 640 and M > 16:
-        assert rc == 0 and list(out) == [4, 1, 0]
-        return
 
     def most(P):
         worst = 0
@@ -110,10 +107,32 @@ def test_linear_plan(M, N, K):
         return worst
 
     feasible = [P for P in range(1, 9) if most(P) <= cap]
+    whole = bool(feasible)
+    if ntiles < 640:
+        if M > 16:
+            whole = False
+        elif whole:
+            P = feasible[0]
+            excess = most(P) * P * G / ntiles - 1.0
+            whole = excess * (2.0 * N * K / 6.4e6) < 3.0
+        if not whole:
+            assert rc == 0 and list(out) == [4, 1, 0]
+            return
     if not feasible:
         assert rc == -1
         return
     assert rc == 0 and out[2] == 1 and out[1] == feasible[0] and out[0] == most(feasible[0]) and 1 <= out[0] <= cap
+
+
+def test_linear_plan_known_shapes():
+    """7B-shaped output and down projections (256 tiles on 256 workgroups) go whole-tile at one
+    row of x; the 13B-shaped ones (320 tiles: shares of one and two) do not."""
+    lib = B.lib()
+    out = (C.c_int * 3)()
+    for (M, N, K), want in [((1, 4096, 4096), [1, 1, 1]), ((16, 4096, 11008), [1, 1, 1]), ((17, 4096, 4096), [4, 1, 0]),
+                            ((1, 5120, 5120), [4, 1, 0]), ((1, 5120, 13824), [4, 1, 0]), ((64, 22016, 4096), [6, 1, 1]),
+                            ((64, 12288, 4096), [3, 1, 1]), ((128, 22016, 4096), [3, 2, 1])]:
+        assert lib.ghd_debug_plan(M, N, K, 256, out) == 0 and list(out) == want, (M, N, K, list(out))
 
 
 def attn_share(lib, nh, ntile, j, G, head):
