@@ -161,7 +161,7 @@ struct FusedArgs {
     int lin_N, lin_K, lin_epi;
     int lin_slots;         // wide matrices: row tiles a work share handles at once (template choice)
     int lin_passes;        // work shares per workgroup
-    int lin_whole;         // wide matrices: deal whole tiles (no tile is shared between shares)
+    int lin_whole;         // whole tiles are dealt out (always for wide matrices), else k ranges of row blocks
     int lin_rscale;        // the input is xg16: scale output row m by the RMSNorm factor of x[m]
     const half_t* lin_gnext;   // EPI_RESID: gain of the norm that follows (xg16 is rewritten)
     half_t *lin_kc, *lin_vc;   // EPI_QKV: the layer's cache

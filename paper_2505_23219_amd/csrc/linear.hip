@@ -108,14 +108,12 @@ bool plan_linear(int M, int N, int K, int G, LinPlan* out)
     return true;
 }
 
-// partial-sum slots: two per share, each one row block of fragments; sized for the most
-// shares a launch can have
+// partial-sum slots of the row-block cut (one share per workgroup): two per share, each one
+// row block of fragments
 size_t linear_part_floats(int M, int G)
 {
     const size_t mt = (size_t)((M + 15) / 16 <= 1 ? 1 : (M + 15) / 16 <= 2 ? 2 : (M + 15) / 16 <= 4 ? 4 : 8);
-    const size_t wide = (size_t)kMaxShares * 2 * mt * 256;             // rb = 1, up to kMaxShares shares
-    const size_t narrow = (size_t)G * 2 * kRbNarrow * mt * 256;        // rb = 4, one share per workgroup
-    return wide > narrow ? wide : narrow;
+    return (size_t)G * 2 * kRbNarrow * mt * 256;
 }
 
 ghd_status launch_linear(const FusedArgs& a, hipStream_t st)

@@ -43,7 +43,6 @@ struct GemmOp {
     uint32_t* cnt;       // the operation's counters
     uint32_t epoch;      // how many times these counters were used before (layer index)
     int passes;          // shares per workgroup
-    bool whole;          // wide matrices: shares are whole tiles
 };
 
 
@@ -175,12 +174,11 @@ __device__ __forceinline__ void pin_order()
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// MT = 16-row tiles of x (Mpad / 16).  R = weight tiles streamed together.  RB = tiles per
-// item of the work shares: RB == 1, a share's R slots are consecutive tiles, each with its
-// own k range (whole tiles: the full range; else the first and the last may be shared with
-// neighbouring shares), in either storage layout; RB == 4 (== R), the slots are the four
-// tiles of one row block of a narrow matrix, all with one k range, and a share that touches
-// several blocks streams them one after the other.
+// MT = 16-row tiles of x (Mpad / 16).  R = weight tiles streamed together.  RB = how the
+// matrix is dealt out.  RB == 1: whole tiles - a share is up to R consecutive tiles over the
+// whole k range, in either storage layout, and finishes them alone.  RB == 4 (== R): k ranges
+// of the four-tile row blocks of a narrow matrix - a share streams the blocks its range touches
+// one after the other, and a block whose k range is cut between shares is finished jointly.
 // Returns false if a wait for another share's partial sums gave up.
 template <int MT, int R, int RB>
 __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op, Ctx& cx)
@@ -248,56 +246,38 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         rinv_ready = true;
     };
 
-    // Share ls of the launch.  With whole tiles, the tiles (not their k-steps) are dealt out and
-    // every share covers the whole k range of its tiles: nothing is shared between shares.
+    // Share ls of the launch.  RB == 1: the tiles are dealt out, c0 .. c1 are tile indices and
+    // every share covers the whole k range of its tiles - nothing is shared between shares.
+    // RB == 4: the k-steps of the four-tile row blocks are dealt out, c0 .. c1 are indices into
+    // the sequence [block][k-step]; a block whose k range is cut is finished jointly.
     auto share_of = [&](int ls) {
-        if (!op.whole) return make_share(op.lay.nitems, nks, ls, L);
-        Share sh = make_share(op.lay.ntiles, 1, ls, L);
-        sh.c0 *= nks;
-        sh.c1 *= nks;
-        return sh;
+        return RB == 1 ? make_share(op.lay.ntiles, 1, ls, L) : make_share(op.lay.nitems, nks, ls, L);
     };
-    auto is_shared = [&](const Share& sh, int item) { return !op.whole && sh.first_of(item) != sh.last_of(item); };
-
-    // Slot 0 of a share holds the partial of the row block its range begins in, slot 1 that
-    // of the block it ends in (when that is another one); blocks in between are whole.
-    auto slot_of = [&](const Share& sh, int ls, int item) -> float* {
-        return a.part + ((size_t)ls * 2 + (sh.begins_in(ls, item) ? 0 : 1)) * (size_t)(NFI * 256);
+    auto is_shared = [&](const Share& sh, int block) { return RB != 1 && sh.first_of(block) != sh.last_of(block); };
+    // Slot 0 of a share holds the partial sums of the row block its range begins in, slot 1
+    // those of the block it ends in (when that is another one); blocks in between are whole.
+    auto slot_of = [&](const Share& sh, int ls, int block) -> float* {
+        return a.part + ((size_t)ls * 2 + (sh.begins_in(ls, block) ? 0 : 1)) * (size_t)(NFI * 256);
     };
     // A shared block is counted on the line of its first part (a share is the first part of
     // at most one shared block: the one its range ends in).
     auto counter_of = [&](int first) { return op.cnt + first * kCntStride; };
 
-    // ---- one group of R tile slots streamed together.  RB == 1: the row blocks (= tiles)
-    //      item0 .. item1 of share ls, slot 0 = item0, slot 1 = item1, slots 2.. the tiles
-    //      in between.  RB == 4: the tiles of row block item0 (item1 == item0).
-    auto run_group = [&](const Share& sh, int ls, int item0, int item1) {
-        auto item_of = [&](int t) { return RB == 1 ? (t == 0 ? item0 : (t == 1 ? item1 : item0 + t - 1)) : item0; };
-        auto valid_of = [&](int t) {
-            return RB == 1 ? (t == 0 || (t == 1 ? item1 > item0 : item0 + t - 1 < item1)) : true;
-        };
-        // k range of the slot (empty: the slot is unused, and its loads re-read slot 0's first
-        // block) and index of the 1 KiB block of its k-step 0
-        int s_k0[R], s_k1[R], s_blk[R];
-        int kmin = nks, kmax = 0;
+    // ---- one group of R tile slots streamed together over the k-steps k0 .. k1 - 1.
+    //      RB == 1: the tiles first .. first + count - 1 (count <= R; the other slots re-read
+    //      slot 0's blocks, and what they accumulate is never looked at).
+    //      RB == 4: the four tiles of row block `first`.
+    auto run_group = [&](const Share& sh, int ls, int first, int count, int k0, int k1) {
+        int s_blk[R];       // index of the 1 KiB block of the slot's k-step 0
 #pragma unroll
         for (int t = 0; t < R; ++t) {
-            const int item = item_of(t);
-            const bool valid = valid_of(t);
-            const int ai = valid ? item : item0;
-            const int k0 = max(sh.c0 - ai * nks, 0), k1 = min(sh.c1 - ai * nks, nks);
-            s_k0[t] = k0;
-            s_k1[t] = valid ? k1 : k0;
-            s_blk[t] = RB == 1 ? (ai >> blk_sh) * (nks << blk_sh) + (ai & ((1 << blk_sh) - 1)) : ai * nks * RB + t;
-            if (valid) {
-                kmin = min(kmin, k0);
-                kmax = max(kmax, k1);
-            }
+            const int tile = first + (t < count ? t : 0);
+            s_blk[t] = RB == 1 ? (tile >> blk_sh) * (nks << blk_sh) + (tile & ((1 << blk_sh) - 1)) : first * nks * RB + t;
         }
         // this wavefront's k-steps
-        const int n = kmax - kmin;
-        const int ws = kmin + n * wave / 8, we = kmin + n * (wave + 1) / 8;
-        const int s_hi = max(we - 1, kmin);       // loads never go past the wavefront's last k-step
+        const int n = k1 - k0;
+        const int ws = k0 + n * wave / 8, we = k0 + n * (wave + 1) / 8;
+        const int s_hi = max(we - 1, k0);       // loads never go past the wavefront's last k-step
 
         half8 wr[PD][R], xr[PD][MT];
         floatx4 acc[R][MT];
@@ -307,9 +287,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             for (int b = 0; b < MT; ++b) acc[t][b] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
         // All loads are unconditional (clamped addresses): the compiler's wait counts then
-        // stay exact and the queue is never drained inside the loop.  Blocks outside a
-        // slot's or the wavefront's range are re-reads of a block that is needed anyway;
-        // they are zeroed before use.
+        // stay exact and the queue is never drained inside the loop.  K-steps past the
+        // wavefront's range are re-reads of its last one; they are zeroed before use.
         auto load = [&](auto slot, int s) {
             constexpr int p = decltype(slot)::value;
             const int sl = min(s, s_hi);
@@ -318,37 +297,29 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             for (int b = 0; b < MT; ++b) xr[p][b] = *(const half8*)(xq + (b << 10) + lane16);
 #pragma unroll
             for (int t = 0; t < R; ++t) {
-                const int st = min(max(sl, s_k0[t]), max(s_k1[t] - 1, s_k0[t]));
-                const char* wq = (const char*)op.W + ((size_t)(s_blk[t] + (RB == 1 ? st << blk_sh : st * RB)) << 10);
+                const char* wq = (const char*)op.W + ((size_t)(s_blk[t] + (RB == 1 ? sl << blk_sh : sl * RB)) << 10);
                 wr[p][t] = __builtin_nontemporal_load((const half8*)(wq + lane16));
             }
         };
-        // MASKED: blocks outside a slot's or the wavefront's k range, and columns past K in the
-        // last k-step, count as zeros.  The unmasked form is for k-steps where every slot is
-        // inside its range.
+        // MASKED: k-steps past the wavefront's range, and columns past K in the last k-step,
+        // count as zeros (the x fragments are zeroed: one select for all the slots).
         auto compute = [&](auto masked, auto slot, int s) {
             constexpr int p = decltype(slot)::value;
             constexpr bool MASKED = decltype(masked)::value;
             half8 xf[MT];
             if constexpr (MASKED) {
-                const bool kok = s * 32 + g4 * 8 < op.K;
+                const bool use = s < we && s * 32 + g4 * 8 < op.K;
 #pragma unroll
-                for (int b = 0; b < MT; ++b) xf[b] = kok ? xr[p][b] : zero8;
+                for (int b = 0; b < MT; ++b) xf[b] = use ? xr[p][b] : zero8;
             } else {
 #pragma unroll
                 for (int b = 0; b < MT; ++b) xf[b] = xr[p][b];
             }
 #pragma unroll
-            for (int t = 0; t < R; ++t) {
-                half8 wv = wr[p][t];
-                if constexpr (MASKED) {
-                    const bool act = s >= s_k0[t] && s < s_k1[t] && s < we;
-                    wv = act ? wv : zero8;
-                }
+            for (int t = 0; t < R; ++t)
 #pragma unroll
                 for (int b = 0; b < MT; ++b)
-                    acc[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wv, xf[b], acc[t][b], 0, 0, 0);
-            }
+                    acc[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wr[p][t], xf[b], acc[t][b], 0, 0, 0);
         };
         auto ring = [&](auto self, auto masked, auto slot, int s) {
             constexpr int p = decltype(slot)::value;
@@ -372,11 +343,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         prologue(prologue, std::integral_constant<int, 0>{});
         if (!rinv_loaded) rinv_sum();
         {
-            // does every k-step of this wavefront lie inside every used slot's range?  (What an
-            // unused slot accumulates is never looked at.)
-            bool plain = (op.K & 31) == 0 || we < nks;
-#pragma unroll
-            for (int t = 0; t < R; ++t) plain = plain && (s_k1[t] == s_k0[t] || (s_k0[t] <= ws && s_k1[t] >= we));
+            // whole rings of k-steps that need no masking first, then the rest
+            const bool plain = (op.K & 31) == 0 || we < nks;
             int s = ws;
             if (plain)
                 for (; s + PD <= we; s += PD) ring(ring, std::false_type{}, std::integral_constant<int, 0>{}, s);
@@ -384,21 +352,12 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         }
 
         // ---- the eight k slices are added up through LDS, FR fragments per round; wavefront
-        //      w reduces fragments w, w + 8 of the round (in wavefront order) and finishes them.
-        //      The fragments of row blocks shared with other shares come first (slots 0 and 1 of
-        //      a wide matrix; all of a narrow one): their partial sums are stored and signalled
-        //      as soon as they are complete, so that they are on their way while the rest of the
-        //      share is finished.
+        //      w reduces fragments w, w + 8 of the round (in wavefront order) and finishes them:
+        //      the layer's epilogue, or - for a row block that other shares have parts of -
+        //      a store of the partial sums, which are signalled once all of them are stored.
         if (!rinv_ready) rinv_finish();
-        bool any_shared = false;
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int item = k ? item1 : item0;
-            if (k && item1 == item0) break;
-            any_shared = any_shared || is_shared(sh, item);
-        }
-        constexpr int kSignalRound = RB == 1 ? 0 : (NF - 1) / FR;
-        static_assert(RB != 1 || 2 * MT <= FR || NF <= FR, "the shared slots' fragments are in the first round");
+        const bool shared = is_shared(sh, first);
+        constexpr int kLastRound = (NF - 1) / FR;
 #pragma unroll
         for (int r0 = 0; r0 < NF; r0 += FR) {
 #pragma unroll
@@ -410,26 +369,18 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
 #pragma unroll
                 for (int w = 1; w < 8; ++w) v += red[(w * FR + ff) * 64 + lane];
                 const int f = r0 + ff, t = f / MT, b = f % MT;
-                if (!valid_of(t)) continue;
-                const int item = item_of(t);
-                const int tile = RB == 1 ? item : item * RB + t;
-                if (!is_shared(sh, item))
+                if (RB == 1 && t >= count) continue;
+                const int tile = RB == 1 ? first + t : first * RB + t;
+                if (!shared)
                     epilogue(a, op, v, b * 16 + c, tile * 16 + g4 * 4, lane, s_rinv);
                 else
-                    *(floatx4*)(slot_of(sh, ls, item) + ((size_t)((RB == 1 ? 0 : t) * MT + b) * 64 + lane) * 4) = v;
+                    *(floatx4*)(slot_of(sh, ls, first) + ((size_t)(t * MT + b) * 64 + lane) * 4) = v;
             }
-            if (any_shared && r0 / FR == kSignalRound) wait_own_stores();   // the partials are in the L2
+            if (shared && r0 / FR == kLastRound) wait_own_stores();   // the partials are in the L2
             __syncthreads();
-            if (any_shared && r0 / FR == kSignalRound && tid == 0) {
-#pragma unroll
-                for (int k = 0; k < 2; ++k) {
-                    const int item = k ? item1 : item0;
-                    if (k && item1 == item0) break;
-                    if (is_shared(sh, item)) atomicAdd(counter_of(sh.first_of(item)), 1u);
-                }
-            }
+            if (shared && r0 / FR == kLastRound && tid == 0) atomicAdd(counter_of(sh.first_of(first)), 1u);
         }
-        return any_shared;
+        return shared;
     };
 
     // ---- the shares of this workgroup, one after the other
@@ -438,27 +389,28 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         const int ls = cx.j * op.passes + p;
         const Share sh = share_of(ls);
         if (sh.c0 >= sh.c1) continue;
-        const int it0 = sh.c0 / nks, it1 = (sh.c1 - 1) / nks;
         if constexpr (RB == 1) {
-            shared_any = run_group(sh, ls, it0, it1) || shared_any;
+            run_group(sh, ls, sh.c0, sh.c1 - sh.c0, 0, nks);      // (the launch was planned for c1 - c0 <= R)
         } else {
-            for (int it = it0; it <= it1; ++it) shared_any = run_group(sh, ls, it, it) || shared_any;
+            const int it0 = sh.c0 / nks, it1 = (sh.c1 - 1) / nks;
+            for (int it = it0; it <= it1; ++it)
+                shared_any = run_group(sh, ls, it, RB, max(sh.c0 - it * nks, 0), min(sh.c1 - it * nks, nks)) || shared_any;
         }
     }
     if (!shared_any) return true;
 
-    // ---- cooperative finish of the shared row blocks this workgroup has parts of.  All its
-    //      partial sums were stored and signalled before it waits for anybody else's.
+    // ---- joint finish of the shared row blocks this workgroup has parts of.  All its partial
+    //      sums were stored and signalled before it waits for anybody else's.
     for (int p = 0; p < op.passes; ++p) {
         const int ls = cx.j * op.passes + p;
         const Share sh = share_of(ls);
         if (sh.c0 >= sh.c1) continue;
         const int it0 = sh.c0 / nks, it1 = (sh.c1 - 1) / nks;
         for (int k = 0; k < 2; ++k) {
-            const int item = k ? it1 : it0;
+            const int block = k ? it1 : it0;
             if (k && it1 == it0) break;
-            if (!is_shared(sh, item)) continue;
-            const int first = sh.first_of(item), last = sh.last_of(item);
+            if (!is_shared(sh, block)) continue;
+            const int first = sh.first_of(block), last = sh.last_of(block);
             const int np = last - first + 1, me = ls - first;
             if (tid == 0)
                 *s_wait_ok = bounded_wait(a.sync, counter_of(first), (uint32_t)np * (op.epoch + 1), 1000u + op.epi);
@@ -469,17 +421,17 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
                 // Sum the parts in index order (fixed order: the result does not depend on
                 // timing), eight loads in flight at a time.
                 const size_t foff = ((size_t)f * 64 + lane) * 4;
-                floatx4 v = *(const floatx4*)(slot_of(sh, first, item) + foff);
+                floatx4 v = *(const floatx4*)(slot_of(sh, first, block) + foff);
                 for (int p0 = 1; p0 < np; p0 += 8) {
                     floatx4 t[8];
 #pragma unroll
                     for (int q = 0; q < 8; ++q)
-                        if (p0 + q < np) t[q] = *(const floatx4*)(slot_of(sh, first + p0 + q, item) + foff);
+                        if (p0 + q < np) t[q] = *(const floatx4*)(slot_of(sh, first + p0 + q, block) + foff);
 #pragma unroll
                     for (int q = 0; q < 8; ++q)
                         if (p0 + q < np) v += t[q];
                 }
-                const int tile = RB == 1 ? item : item * RB + f / MT, b = f % MT;
+                const int tile = block * RB + f / MT, b = f % MT;
                 epilogue(a, op, v, b * 16 + c, tile * 16 + g4 * 4, lane, s_rinv);
             }
         }
@@ -505,7 +457,6 @@ __device__ __forceinline__ GemmOp linear_op_of(const FusedArgs& a)
     op.cnt = a.sync + a.lin_cnt;
     op.epoch = a.lin_epoch;
     op.passes = a.lin_passes;
-    op.whole = a.lin_whole != 0;
     return op;
 }
 
