@@ -132,7 +132,12 @@ size_t ghd_packed_weight_bytes(int N, int K);
  *   GHD_PACK_QKV      src is [3H, K] (q, k, v rows; heads of head_dim rows): in
  *                     every head, packed rows 4i..4i+3 hold channels 2i, 2i+1,
  *                     2i+head_dim/2, 2i+1+head_dim/2 (the two rotary pairs of a
- *                     quad end up in one lane of the GEMM output)
+ *                     quad end up in one lane of the GEMM output).  The heads'
+ *                     row blocks come in the order q of all heads, k of all
+ *                     heads, v of all heads - or, when the number of heads is a
+ *                     multiple of 8, in eight groups of nh/8 heads, each group
+ *                     as q rows, k rows, v rows of its heads (the group whose
+ *                     attention runs on the same eighth of the GPU)
  *   GHD_PACK_GATE_UP  src is [2F, K] (gate rows then up rows), F%8 == 0: packed
  *                     rows 16t+4i .. +3 hold gate 8t+2i, gate 8t+2i+1, up 8t+2i,
  *                     up 8t+2i+1
@@ -245,9 +250,9 @@ ghd_status ghd_verify_stack_argmax(const ghd_model_cfg *cfg, const ghd_layer_wei
                                    int32_t *amax_dev, float *logits, float *x_out, void *ws,
                                    size_t ws_bytes, void *stream);
 
-/* Every linear layer and every attention is one launch of a persistent kernel
- * (one workgroup per compute unit, all resident) whose workgroups hand partial
- * results to each other; every wait is bounded and gives up rather than hang
+/* Every linear layer and every attention runs in a launch of a persistent kernel
+ * (one workgroup per compute unit, all resident; a layer's QKV layer and attention
+ * may share one) whose workgroups hand partial results to each other; every wait is bounded and gives up rather than hang
  * (for instance if other work on the GPU keeps some workgroups from becoming
  * resident).  This call synchronises `stream` and reports the status word the
  * last ghd_linear_skinny / ghd_tree_attention / ghd_verify_layer /

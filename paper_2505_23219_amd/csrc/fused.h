@@ -15,17 +15,18 @@ enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 // The unit is the 1 KiB A operand of v_mfma_f32_16x16x32_f16: 16 output features (a
 // "tile") by 32 input features (a "k-step"), 16 bytes per lane in lane order.  Tiles are
 // stored in blocks of `blk` tiles, k-step major inside a block: the tiles a wavefront
-// streams together at one k-step lie side by side.  Work is shared out in row blocks
-// ("items") of rb tiles: wide matrices (many tiles per compute unit) have rb = 1 - a
-// workgroup owns whole tiles and streams several of them over the whole K range - and are
-// stored in blocks of 8 tiles; narrow ones have rb = 4 = blk - a workgroup streams a k range
-// of four tiles at once, so that the x operand it reads is shared by 64 output features.
+// streams together at one k-step lie side by side.  Wide matrices (many tiles per compute
+// unit) are stored in blocks of 8 tiles and always dealt out in whole tiles - a workgroup
+// streams several consecutive tiles over the whole K range.  Narrow ones are stored in
+// blocks of rb = 4 tiles, which are also the items of their other cut: a workgroup streams a
+// k range of one block, so that the x operand it reads is shared by 64 output features
+// (see plan_linear for which cut a launch takes).
 constexpr int kRbNarrow = 4;
 constexpr int kWideBlock = 8;
-constexpr int kWideTiles = 640;   // from this many tiles on, rb = 1
+constexpr int kWideTiles = 640;   // from this many tiles on a matrix is wide
 
 struct WLayout {
-    int rb;        // tiles per item
+    int rb;        // 1: wide matrix; 4: narrow one (tiles per row block of the k-range cut)
     int blk;       // tiles per storage block
     int ntiles;    // 16-row tiles (last one zero padded)
     int nitems;    // row blocks (last one padded with zero tiles)

@@ -2,26 +2,24 @@
 // 512-thread workgroup per compute unit.
 //
 // The step re-reads every weight once per decoding step and is bound by that stream
-// (Ghidorah, sections 2.1 and 2.2.2), so the kernel is built around it: the k-steps of the
-// packed matrix (see w_layout) form one sequence, cut into equal contiguous shares whatever
-// the shape.  A share covers a k range of one or more row blocks.  Its eight wavefronts
-// split the k range between them; each wavefront streams its k-steps of ALL the share's
-// row tiles (W is the MFMA A operand, fetched with non-temporal 128-bit loads straight
-// into registers, a few k-steps ahead) together with the matching x fragments (the B
-// operand, read as it lies in the packed activation layout, from the L2), and keeps one
-// fp32 accumulator fragment per (row tile, 16 rows of x).  There is no LDS staging and no
-// barrier inside the stream: the wavefronts run independently until their k ranges end.
-// Then the eight partial fragments of every tile are added up through LDS, in wavefront
-// order, and the reducing wavefront runs the layer's element-wise epilogue (residual add +
-// sums of squares for the next RMSNorm, rotary embedding + KV append, SwiGLU) - or, for a
-// row block whose k range is shared with other shares, stores the partial sum; those
-// blocks are finished cooperatively at the end of the launch, parts added in index order,
-// so results never depend on timing.
+// (Ghidorah, sections 2.1 and 2.2.2), so the kernel is built around it.  A workgroup's share
+// is a group of R row tiles (16 output features each) and a k range.  Its eight wavefronts
+// split the k range between them; each wavefront streams its k-steps of ALL the group's
+// tiles (W is the MFMA A operand, fetched with non-temporal 128-bit loads straight into
+// registers, a few k-steps ahead) together with the matching x fragments (the B operand,
+// read as it lies in the packed activation layout, from the L2), and keeps one fp32
+// accumulator fragment per (row tile, 16 rows of x).  There is no LDS staging and no barrier
+// inside the stream: the wavefronts run independently until their k ranges end.  Then the
+// eight partial fragments of every tile are added up through LDS, in wavefront order, and
+// the reducing wavefront runs the layer's element-wise epilogue (residual add + sums of
+// squares for the next RMSNorm, rotary embedding + KV append, SwiGLU).
 //
-// x traffic: a share that holds R row tiles reads 16 * R weight rows and M rows of x per
-// k-step, all from the L2 except the weights.  Wide matrices (rb = 1) give every share
-// several whole tiles over the whole K range (x is read once per share, almost nothing is
-// exchanged); narrow ones (rb = 4) give it a k range of four tiles.
+// Two ways of dealing a matrix out (chosen on the host, see plan_linear).  Whole tiles: a
+// share is a run of consecutive tiles over the whole k range; nothing is exchanged between
+// workgroups, every workgroup reads all of x.  K ranges of four-tile row blocks (narrow
+// matrices at more than 16 rows of x): a share reads only its k range of x, stores the
+// block's partial sums, and the workgroups that share a block finish it jointly at the end
+// of the launch, parts added in index order, so results never depend on timing.
 #pragma once
 #include "persist.h"
 
