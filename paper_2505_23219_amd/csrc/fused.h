@@ -6,6 +6,7 @@ namespace ghd {
 
 constexpr int kFT = 512;        // threads per workgroup (8 wavefronts)
 constexpr int kMaxLayers = 48;  // the counter epochs (one per layer) are laid out for this many
+constexpr int kRangeWgs = 256;  // workgroups whose work shares fit the argument block
 
 enum { EPI_STORE_F32 = 0, EPI_STORE_F16 = 1, EPI_RESID = 2, EPI_SWIGLU = 3, EPI_QKV = 4 };
 enum { MODE_LINEAR = 0, MODE_ATTN = 1, MODE_QKV_ATTN = 2 };
@@ -176,6 +177,12 @@ struct FusedArgs {
     const half_t *att_q, *att_k, *att_v;
     half_t* att_out;
     int att_out_packed;    // output in the packed activation layout (else row-major [M, nh, d])
+    // Filled in at launch (see with_launch_facts): the matrix' layout, and every workgroup's
+    // work share when there is one share per workgroup - what the kernel would otherwise
+    // work out with a dozen integer divisions before it can request its first weights.
+    int lin_ntiles, lin_nitems, lin_nks, lin_blk_shift;
+    int lin_range_ok;                      // lin_range is filled in
+    uint32_t lin_range[2 * kRangeWgs];     // workgroup j (logical index): units c0 .. c1 - 1 of its share
 };
 
 ghd_status launch_fused(const FusedArgs& a, hipStream_t st);

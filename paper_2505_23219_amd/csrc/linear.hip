@@ -43,7 +43,8 @@ ghd_status launch_resident_checked(const void* kernel, int key, size_t lds, int*
     const int dev = current_device();
     const int G = fused_grid_size();
     // the hand-off of partial results is laid out for 8 XCDs of G / 8 compute units
-    if (dev < 0 || G <= 0 || G > 512 || (G % 8) != 0) return hip_fail(hipErrorInvalidDevice);
+    // and for at most kRangeWgs workgroups (their work shares travel in the argument block)
+    if (dev < 0 || G <= 0 || G > kRangeWgs || (G % 8) != 0) return hip_fail(hipErrorInvalidDevice);
     *grid = G;
     std::lock_guard<std::mutex> lock(mu);
     for (const void* k : checked[dev])

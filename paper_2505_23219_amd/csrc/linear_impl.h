@@ -29,7 +29,7 @@ namespace ghd {
 
 struct GemmOp {
     const half8* W;
-    WLayout lay;
+    int ntiles, nitems, nks, blk_shift;   // of the packed matrix (see WLayout)
     int N, K;
     int epi;
     const half8* in;     // packed activation layout, Mpad rows
@@ -67,6 +67,9 @@ __host__ __device__ constexpr int pd_of(int MT, int R)
 __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, floatx4 v, int m, int n0,
                                          int lane, const float* s_rinv)
 {
+    // Everything below depends on the fragment's position: the (empty) asm keeps the compiler
+    // from working parts of it out ahead of the weight stream, before the kernel's first loads.
+    asm volatile("" : "+v"(m), "+v"(n0));
     const bool mok = m < a.M;
     const int mtp = a.Mpad >> 4;
     if (op.rscale) v *= s_rinv[m];
@@ -134,8 +137,10 @@ __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, f
         *(half2_*)((half_t*)op.out + xpk_index(m, f, mtp)) = h;
     } else {   // EPI_QKV: packed rows of a head: (j, j+1, j+d/2, j+1+d/2)
         if (!mok || n0 >= op.N) return;
-        const int H = a.H, d = a.d, hd = a.d >> 1;
-        const QkvRow qr = qkv_row(n0, a.nh, d);
+        int nh = a.nh, d = a.d;
+        asm volatile("" : "+s"(nh), "+s"(d));     // (the divisions by these stay here, too)
+        const int H = nh * d, hd = d >> 1;
+        const QkvRow qr = qkv_row(n0, nh, d);
         const int part = qr.part, head = qr.head, ph = qr.ph;
         int jj = (ph >> 2) * 2;
         float o0 = v[0], o1 = v[1], o2 = v[2], o3 = v[3];
@@ -194,9 +199,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     float* s_rinv = (float*)(cx.lds + 8 * FR * 1024);      // 128 floats
     float* s_tmp = s_rinv + 128;                           // 1024 floats
     int* s_wait_ok = (int*)(s_tmp + 1024);                 // thread 0's verdict on a bounded wait
-    const int nks = op.lay.nks;
-    const int blk_sh = op.lay.blk == kWideBlock ? 3 : 2;   // tiles per storage block: 8 or 4
-    static_assert(kWideBlock == 8 && kRbNarrow == 4, "storage blocks of 8 or 4 tiles");
+    const int nks = op.nks;
+    const int blk_sh = op.blk_shift;        // tiles per storage block: 8 or 4
     const int L = cx.G * op.passes;
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
@@ -209,8 +213,8 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     //      sums are added through LDS.  Fixed order throughout.
     bool rinv_loaded = !op.rscale, rinv_ready = !op.rscale;
     floatx4 rs4 = {0.f, 0.f, 0.f, 0.f}, sst[8];
-    const int RQ = a.Mpad >> 2, n_ss = op.K >> 4;
-    const int P = kFT / RQ, rq = tid % RQ, part = tid / RQ;
+    constexpr int RQ = MT * 4, P = kFT / RQ;      // Mpad = 16 MT rows, four per thread
+    const int n_ss = op.K >> 4, rq = tid % RQ, part = tid / RQ;
     auto rinv_request = [&](int t0) {
 #pragma unroll
         for (int q = 0; q < 8; ++q)
@@ -236,7 +240,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     auto rinv_finish = [&]() {
         if (lane < RQ) *(floatx4*)(s_tmp + (wave * RQ + lane) * 4) = rs4;
         __syncthreads();
-        if (tid < a.Mpad) {
+        if (tid < MT * 16) {
             float tot = 0.f;
             for (int w = 0; w < 8; ++w) tot += s_tmp[(w * RQ + (tid >> 2)) * 4 + (tid & 3)];
             s_rinv[tid] = (1.0f / kXgScale) / sqrtf(tot / (float)op.K + a.eps);
@@ -249,7 +253,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     // RB == 4: the k-steps of the four-tile row blocks are dealt out, c0 .. c1 are indices into
     // the sequence [block][k-step]; a block whose k range is cut is finished jointly.
     auto share_of = [&](int ls) {
-        return RB == 1 ? make_share(op.lay.ntiles, 1, ls, L) : make_share(op.lay.nitems, nks, ls, L);
+        return RB == 1 ? make_share(op.ntiles, 1, ls, L) : make_share(op.nitems, nks, ls, L);
     };
     auto is_shared = [&](const Share& sh, int block) { return RB != 1 && sh.first_of(block) != sh.last_of(block); };
     // Slot 0 of a share holds the partial sums of the row block its range begins in, slot 1
@@ -265,7 +269,7 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
     //      RB == 1: the tiles first .. first + count - 1 (count <= R; the other slots re-read
     //      slot 0's blocks, and what they accumulate is never looked at).
     //      RB == 4: the four tiles of row block `first`.
-    auto run_group = [&](const Share& sh, int ls, int first, int count, int k0, int k1) {
+    auto run_group = [&](int ls, int first, int count, int k0, int k1) {
         int s_blk[R];       // index of the 1 KiB block of the slot's k-step 0
 #pragma unroll
         for (int t = 0; t < R; ++t) {
@@ -340,6 +344,17 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         // The norm factors are only needed by the epilogues, but their loads are cheapest here.
         prologue(prologue, std::integral_constant<int, 0>{});
         if (!rinv_loaded) rinv_sum();
+        // (the share's place among its neighbours is only needed for the finish: worked out
+        // here, while the first weights are on their way)
+        bool shared = false;
+        int first_part = 0;
+        float* my_slot = nullptr;
+        if constexpr (RB != 1) {
+            const Share sh = share_of(ls);
+            first_part = sh.first_of(first);
+            shared = first_part != sh.last_of(first);
+            my_slot = slot_of(sh, ls, first);
+        }
         {
             // whole rings of k-steps that need no masking first, then the rest
             const bool plain = (op.K & 31) == 0 || we < nks;
@@ -354,7 +369,6 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
         //      the layer's epilogue, or - for a row block that other shares have parts of -
         //      a store of the partial sums, which are signalled once all of them are stored.
         if (!rinv_ready) rinv_finish();
-        const bool shared = is_shared(sh, first);
         constexpr int kLastRound = (NF - 1) / FR;
 #pragma unroll
         for (int r0 = 0; r0 < NF; r0 += FR) {
@@ -372,27 +386,36 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
                 if (!shared)
                     epilogue(a, op, v, b * 16 + c, tile * 16 + g4 * 4, lane, s_rinv);
                 else
-                    *(floatx4*)(slot_of(sh, ls, first) + ((size_t)(t * MT + b) * 64 + lane) * 4) = v;
+                    *(floatx4*)(my_slot + ((size_t)(t * MT + b) * 64 + lane) * 4) = v;
             }
             if (shared && r0 / FR == kLastRound) wait_own_stores();   // the partials are in the L2
             __syncthreads();
-            if (shared && r0 / FR == kLastRound && tid == 0) atomicAdd(counter_of(sh.first_of(first)), 1u);
+            if (shared && r0 / FR == kLastRound && tid == 0) atomicAdd(counter_of(first_part), 1u);
         }
         return shared;
     };
 
-    // ---- the shares of this workgroup, one after the other
+    // ---- the shares of this workgroup, one after the other.  With one share per workgroup
+    //      its range comes from the table in the argument block.
     bool shared_any = false;
     for (int p = 0; p < op.passes; ++p) {
         const int ls = cx.j * op.passes + p;
-        const Share sh = share_of(ls);
-        if (sh.c0 >= sh.c1) continue;
-        if constexpr (RB == 1) {
-            run_group(sh, ls, sh.c0, sh.c1 - sh.c0, 0, nks);      // (the launch was planned for c1 - c0 <= R)
+        int c0, c1;
+        if (RB != 1 || a.lin_range_ok) {       // (the row-block cut always has one share per workgroup)
+            c0 = (int)a.lin_range[2 * cx.j];   // a scalar load from the argument block
+            c1 = (int)a.lin_range[2 * cx.j + 1];
         } else {
-            const int it0 = sh.c0 / nks, it1 = (sh.c1 - 1) / nks;
+            const Share sh = share_of(ls);
+            c0 = sh.c0;
+            c1 = sh.c1;
+        }
+        if (c0 >= c1) continue;
+        if constexpr (RB == 1) {
+            run_group(ls, c0, c1 - c0, 0, nks);      // (the launch was planned for c1 - c0 <= R)
+        } else {
+            const int it0 = c0 / nks, it1 = (c1 - 1) / nks;
             for (int it = it0; it <= it1; ++it)
-                shared_any = run_group(sh, ls, it, RB, max(sh.c0 - it * nks, 0), min(sh.c1 - it * nks, nks)) || shared_any;
+                shared_any = run_group(ls, it, RB, max(c0 - it * nks, 0), min(c1 - it * nks, nks)) || shared_any;
         }
     }
     if (!shared_any) return true;
@@ -443,7 +466,10 @@ __device__ __forceinline__ GemmOp linear_op_of(const FusedArgs& a)
     op.W = a.lin_W;
     op.N = a.lin_N;
     op.K = a.lin_K;
-    op.lay = w_layout(a.lin_N, a.lin_K);
+    op.ntiles = a.lin_ntiles;
+    op.nitems = a.lin_nitems;
+    op.nks = a.lin_nks;
+    op.blk_shift = a.lin_blk_shift;
     op.epi = a.lin_epi;
     op.in = (const half8*)a.lin_x;
     op.rscale = a.lin_rscale != 0;
@@ -468,6 +494,29 @@ __global__ __launch_bounds__(kFT) void k_linear(const FusedArgs a)
     gemm_phase<MT, R, RB>(a, op, cx);
 }
 
+// The launch's argument block with the facts the host can work out for the kernel: the packed
+// matrix' layout and, when there is one share per workgroup and the grid fits the table, every
+// workgroup's work share (the same make_share the kernel would evaluate).
+static inline FusedArgs with_launch_facts(const FusedArgs& a, int G)
+{
+    FusedArgs b = a;
+    const WLayout lay = w_layout(a.lin_N, a.lin_K);
+    const bool whole = lay.rb == 1 || a.lin_whole;
+    b.lin_ntiles = lay.ntiles;
+    b.lin_nitems = lay.nitems;
+    b.lin_nks = lay.nks;
+    b.lin_blk_shift = lay.blk == kWideBlock ? 3 : 2;
+    static_assert(kWideBlock == 8 && kRbNarrow == 4, "storage blocks of 8 or 4 tiles");
+    b.lin_range_ok = a.lin_passes == 1;     // (launches have at most kRangeWgs workgroups)
+    if (b.lin_range_ok)
+        for (int j = 0; j < G; ++j) {
+            const Share sh = whole ? make_share(lay.ntiles, 1, j, G) : make_share(lay.nitems, lay.nks, j, G);
+            b.lin_range[2 * j] = (uint32_t)sh.c0;
+            b.lin_range[2 * j + 1] = (uint32_t)sh.c1;
+        }
+    return b;
+}
+
 template <int MT, int R>
 constexpr size_t linear_lds_bytes()
 {
@@ -481,7 +530,7 @@ static ghd_status launch_linear_t(const FusedArgs& a, hipStream_t st)
     const size_t lds = linear_lds_bytes<MT, R>();
     ghd_status s = launch_resident_checked((const void*)k_linear<MT, R, RB>, (MT * 16 + R) * 8 + RB, lds, &G);
     if (s) return s;
-    hipLaunchKernelGGL((k_linear<MT, R, RB>), dim3(G), dim3(kFT), lds, st, a);
+    hipLaunchKernelGGL((k_linear<MT, R, RB>), dim3(G), dim3(kFT), lds, st, with_launch_facts(a, G));
     return check_launch();
 }
 

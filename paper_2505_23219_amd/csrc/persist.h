@@ -3,6 +3,8 @@
 #pragma once
 #include "fused.h"
 
+#include <cstddef>
+
 namespace ghd {
 
 constexpr long long kWaitTicks = 2000000;   // bounded waits give up after 20 ms (100 MHz clock)
@@ -111,18 +113,20 @@ __device__ __forceinline__ bool bounded_wait(uint32_t* sync, uint32_t* p, uint32
 // parked one by one, with a wait after each load.)
 __device__ __forceinline__ void touch_kernel_arguments()
 {
-    static_assert(sizeof(FusedArgs) > 256 && sizeof(FusedArgs) <= 320, "five 64-byte lines");
+    static_assert(offsetof(FusedArgs, lin_range) > 320 && offsetof(FusedArgs, lin_range) <= 384,
+                  "six 64-byte lines before the table of work shares");
     typedef const __attribute__((address_space(4))) uint32_t* kernarg_words;
     kernarg_words kp = (kernarg_words)__builtin_amdgcn_kernarg_segment_ptr();
-    uint32_t t0, t1, t2, t3, t4;
+    uint32_t t0, t1, t2, t3, t4, t5;
     asm volatile(
-        "s_load_dword %0, %5, 0x0\n\t"
-        "s_load_dword %1, %5, 0x40\n\t"
-        "s_load_dword %2, %5, 0x80\n\t"
-        "s_load_dword %3, %5, 0xc0\n\t"
-        "s_load_dword %4, %5, 0x100\n\t"
+        "s_load_dword %0, %6, 0x0\n\t"
+        "s_load_dword %1, %6, 0x40\n\t"
+        "s_load_dword %2, %6, 0x80\n\t"
+        "s_load_dword %3, %6, 0xc0\n\t"
+        "s_load_dword %4, %6, 0x100\n\t"
+        "s_load_dword %5, %6, 0x140\n\t"
         "s_waitcnt lgkmcnt(0)"
-        : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4)
+        : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4), "=&s"(t5)
         : "s"(kp)
         : "memory");
 }

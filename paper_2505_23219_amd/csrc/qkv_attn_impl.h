@@ -55,7 +55,7 @@ static ghd_status launch_qkv_attn_t(const FusedArgs& a, hipStream_t st)
     const size_t lds = l1 > l2 ? l1 : l2;
     ghd_status s = launch_resident_checked((const void*)k_qkv_attn<MT, R, D>, 0, lds, &G);
     if (s) return s;
-    hipLaunchKernelGGL((k_qkv_attn<MT, R, D>), dim3(G), dim3(kFT), lds, st, a);
+    hipLaunchKernelGGL((k_qkv_attn<MT, R, D>), dim3(G), dim3(kFT), lds, st, with_launch_facts(a, G));
     return check_launch();
 }
 
