@@ -86,8 +86,9 @@ struct AttnLds {
     static constexpr int MTW = (MT + 3) / 4;
     static constexpr int KS = D + 8;    // halves per K row (padded)
     static constexpr int VS = 64 + 8;   // halves per V^T row (padded, rows stay 16-byte aligned)
-    half_t k[64 * KS];
-    half_t vt[D * VS];
+    // two tile buffers: while one tile is being multiplied, the next one is staged
+    half_t k[2][64 * KS];
+    half_t vt[2][D * VS];
     // state of the wavefronts working on the second key half, handed to their partners on
     // the first half when a head ends: [row-tile slot][tile][fragment][lane]
     floatx4 o2[4][MTW][D / 16][64];
@@ -217,7 +218,7 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
                 int id = tid + kFT * i;
-                *(half8*)(&sm.k[k_row[i] * L::KS + k_off[i]]) = kreg[S][i];
+                *(half8*)(&sm.k[S & 1][k_row[i] * L::KS + k_off[i]]) = kreg[S][i];
                 int vch = id >> 3, seg = id & 7;
                 half8 v = vreg[S][i];
                 int nvalid = T - (tile * 64 + seg * 8);  // rows from T on hold no data: zero them,
@@ -226,7 +227,7 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
                     for (int e = 0; e < 8; ++e)
                         if (e >= nvalid) v[e] = (half_t)0;
                 }
-                *(half8*)(&sm.vt[vch * L::VS + seg * 8]) = v;
+                *(half8*)(&sm.vt[S & 1][vch * L::VS + seg * 8]) = v;
             }
         };
         // Requests, in tile order: [tiles known before the gate] gate [queries] [the rest].
@@ -275,13 +276,19 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
             if (n_pre < 3) load_tile(s2);
             if (n_pre < 4) load_tile(s3);
         }
+        // The tiles alternate between the two LDS buffers (register set S goes to buffer
+        // S & 1: the number of sets is even).  While tile i is multiplied out of one buffer,
+        // tile i + 1 is staged into the other and its registers are refilled - one barrier
+        // per tile.  Past the share's last tile the staged data is a dummy nobody reads.
         int p_tile = t0;                                   // the tile being processed
-        auto do_tile = [&](auto set) {
+        store_tile(s0, t0);
+        load_tile(s0);
+        auto do_tile = [&](auto set, auto next) {
+            constexpr int B = decltype(set)::value & 1;
             const int tile = p_tile++;
-            __syncthreads();            // previous tile fully consumed
-            store_tile(set, tile);
-            __syncthreads();
-            load_tile(set);
+            __syncthreads();            // tile staged by everybody; the other buffer is free
+            store_tile(next, tile + 1);
+            load_tile(next);
         if (!wave_active) return;
         const int key0 = tile * 64 + kh * 32;    // this wavefront's 32 keys
         const bool committed = key0 + 32 <= kv_len;   // every key visible to every row
@@ -295,7 +302,7 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
                     s[jx] = (floatx4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int ds = 0; ds < DS; ++ds) {
-                        half8 kf = *(const half8*)(&sm.k[(kh * 32 + jx * 16 + c) * L::KS + ds * 32 + g4 * 8]);
+                        half8 kf = *(const half8*)(&sm.k[B][(kh * 32 + jx * 16 + c) * L::KS + ds * 32 + g4 * 8]);
                         s[jx] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[t][ds], s[jx], 0, 0, 0);
                     }
                     s[jx] *= scale_log2e;
@@ -328,7 +335,7 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
                     if (vis_any) {
 #pragma unroll
                         for (int ds = 0; ds < DS; ++ds) {
-                            half8 kf = *(const half8*)(&sm.k[(kh * 32 + jx * 16 + c) * L::KS + ds * 32 + g4 * 8]);
+                            half8 kf = *(const half8*)(&sm.k[B][(kh * 32 + jx * 16 + c) * L::KS + ds * 32 + g4 * 8]);
                             s[jx] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[t][ds], s[jx], 0, 0, 0);
                         }
                     }
@@ -371,7 +378,7 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
 #pragma unroll
             for (int e = 0; e < DT; ++e) {
                 oacc[t][e] *= alpha;
-                const half_t* vrow = &sm.vt[(e * 16 + c) * L::VS + kh * 32];
+                const half_t* vrow = &sm.vt[B][(e * 16 + c) * L::VS + kh * 32];
                 half4 a0 = *(const half4*)(vrow + g4 * 4);
                 half4 a1 = *(const half4*)(vrow + 16 + g4 * 4);
                 half8 vf = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
@@ -386,24 +393,24 @@ __device__ __forceinline__ bool attn_phase(const FusedArgs& a, Ctx& cx, const ha
             int u = t0;
             if constexpr (NT == 4) {
                 for (; u + 3 < t1; u += 4) {
-                    do_tile(s0);
-                    do_tile(s1);
-                    do_tile(s2);
-                    do_tile(s3);
+                    do_tile(s0, s1);
+                    do_tile(s1, s2);
+                    do_tile(s2, s3);
+                    do_tile(s3, s0);
                 }
                 if (u < t1) {
-                    do_tile(s0);
+                    do_tile(s0, s1);
                     if (u + 1 < t1) {
-                        do_tile(s1);
-                        if (u + 2 < t1) do_tile(s2);
+                        do_tile(s1, s2);
+                        if (u + 2 < t1) do_tile(s2, s3);
                     }
                 }
             } else {
                 for (; u + 1 < t1; u += 2) {
-                    do_tile(s0);
-                    do_tile(s1);
+                    do_tile(s0, s1);
+                    do_tile(s1, s0);
                 }
-                if (u < t1) do_tile(s0);
+                if (u < t1) do_tile(s0, s1);
             }
         }
 
