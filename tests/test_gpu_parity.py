@@ -132,7 +132,11 @@ def test_tree_mask_bit_exact(B, orc32):
 
 LINEAR_CASES = [(1, 64, 64), (3, 130, 688), (8, 1000, 256), (16, 256, 256), (17, 48, 96),
                 (33, 688 * 2, 256), (64, 256, 688), (100, 130, 520), (128, 512, 1024),
-                (16, 12288, 4096), (64, 4096, 11008), (1, 4096, 4096)]
+                (16, 12288, 4096), (64, 4096, 11008), (1, 4096, 4096),
+                # narrow matrices at few rows: whole tiles where they spread evenly over the workgroups
+                # (256 tiles), k ranges of row blocks where they do not (320 tiles); a wide one with
+                # shares of unequal tile counts and a ragged last tile
+                (16, 4096, 11008), (1, 5120, 5120), (8, 5120, 13824), (4, 22016, 4096), (64, 11000, 1000)]
 
 
 @pytest.mark.parametrize("M,N,K", LINEAR_CASES)
