@@ -61,6 +61,11 @@ __host__ __device__ constexpr int pd_of(int MT, int R)
     return pd < 1 ? 1 : (pd > 8 ? 8 : pd);
 }
 
+// share of a group's k range, in 32nds, that the first wavefront of every SIMD's pair takes
+// (measured on one box, alternating builds: 16 -> 3949 us per 64-row step, 17 -> 3896,
+// 18 -> 3871, 19 -> 3899)
+constexpr int kFirstSet = 18;
+
 // ---------------------------------------------------------------------------
 // epilogue of one 16x16 output fragment: lane (c, g4) holds y[m][n0 .. n0+3]
 // ---------------------------------------------------------------------------
@@ -276,9 +281,13 @@ __device__ __forceinline__ bool gemm_phase(const FusedArgs& a, const GemmOp& op,
             const int tile = first + (t < count ? t : 0);
             s_blk[t] = RB == 1 ? (tile >> blk_sh) * (nks << blk_sh) + (tile & ((1 << blk_sh) - 1)) : first * nks * RB + t;
         }
-        // this wavefront's k-steps
-        const int n = k1 - k0;
-        const int ws = k0 + n * wave / 8, we = k0 + n * (wave + 1) / 8;
+        // This wavefront's k-steps.  Wavefronts w and w + 4 share a SIMD, and the first of the
+        // two gets its data sooner throughout the stream (measured: with equal ranges
+        // wavefronts 0-3 end 2.5-6 us before 4-7, which then stream on alone, no faster).
+        // So the first four split kFirstSet/32 of the range between them, the other four the rest.
+        const int n = k1 - k0, n_a = n * kFirstSet / 32, w4 = wave & 3;
+        const int ws = wave < 4 ? k0 + n_a * w4 / 4 : k0 + n_a + (n - n_a) * w4 / 4;
+        const int we = wave < 4 ? k0 + n_a * (w4 + 1) / 4 : k0 + n_a + (n - n_a) * (w4 + 1) / 4;
         const int s_hi = max(we - 1, k0);       // loads never go past the wavefront's last k-step
 
         half8 wr[PD][R], xr[PD][MT];
