@@ -126,7 +126,8 @@ constexpr int kCntLm = kCntDown + kMaxShares * kCntStride;   // LM head and stan
 constexpr int kCntDraft = kCntLm + kMaxShares * kCntStride;  // drafting heads inside a whole decoding step
 constexpr int kCntAttn = kCntDraft + kMaxShares * kCntStride;   // up to 256 heads
 constexpr int kCntXcd = kCntAttn + 256 * kCntStride;            // one line per XCD: QKV done, attention may start
-constexpr int kSyncWords = kCntXcd + 8 * kCntStride;
+constexpr int kCntGo = kCntXcd + 8 * kCntStride;                // one line per workgroup: its XCD has met
+constexpr int kSyncWords = kCntGo + kRangeWgs * kCntStride;
 
 // RMSNorm is split around the linear layer that consumes it: the producer of the residual
 // stream x also leaves xg16 = fp16(x * g * kXgScale) (g = gain of the next norm), which is

@@ -24,17 +24,31 @@ __global__ __launch_bounds__(kFT) void k_qkv_attn(const FusedArgs a)
     // ---- the XCD's workgroups meet.  Every one of them counts itself in once its part of
     //      q16 and of the cache rows is acknowledged by the L2 they share (the wait below
     //      covers loads too, so it comes before the attention requests anything) ...
-    const int Gx = cx.G / 8;
-    uint32_t* const cnt = a.sync + kCntXcd + (cx.j / Gx) * kCntStride;
+    //      Thirty-two workgroups polling one counter line with read-modify-writes queue up
+    //      behind each other (a poll then takes microseconds), so the counter is only
+    //      incremented: the workgroup that arrives last tells the others, each on a line of
+    //      its own.
+    const int Gx = cx.G / 8, xcd = cx.j / Gx;
+    uint32_t* const cnt = a.sync + kCntXcd + xcd * kCntStride;
+    uint32_t* const go = a.sync + kCntGo;
+    const uint32_t round = a.att_epoch + 1;
     wait_own_stores();
     __syncthreads();       // also: the linear phase's use of the LDS is over
-    if (threadIdx.x == 0) atomicAdd(cnt, 1u);
+    bool last = false;
+    if (threadIdx.x == 0) {
+        last = atomicAdd(cnt, 1u) + 1u == (uint32_t)Gx * round;
+        if (last)
+            for (int w = 0; w < Gx; ++w)
+                __hip_atomic_store(go + (xcd * Gx + w) * kCntStride, round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     // ... and waits for the others at the attention's gate, after it has set up its indices
-    //     and requested the cache rows of earlier steps that it starts with.
+    //     and requested the cache rows of earlier steps that it starts with.  (Counting in
+    //     only after that set-up was measured slower: it is the stores that make a workgroup
+    //     late, and everybody waits for the last.)
     auto gate = [&]() -> bool {
         int* s_ok = &reinterpret_cast<AttnLds<MT, D>*>(cx.lds)->wait_ok;
         if (threadIdx.x == 0)
-            *s_ok = ok && bounded_wait(a.sync, cnt, (uint32_t)Gx * (a.att_epoch + 1), 3000u);
+            *s_ok = ok && (last || bounded_wait(a.sync, go + cx.j * kCntStride, round, 3000u));
         __syncthreads();
         if (!*s_ok) return false;
         // Nothing of q16 or of the tree's cache rows should be in this compute unit's L1 (it
