@@ -136,8 +136,10 @@ __device__ __forceinline__ void epilogue(const FusedArgs& a, const GemmOp& op, f
         if (!mok) return;
         int f = (n0 >> 4) * 8 + ((n0 & 15) >> 2) * 2;
         if (f >= a.F) return;
-        float a0 = v[0] / (1.0f + expf(-v[0])) * v[2];
-        float a1 = v[1] / (1.0f + expf(-v[1])) * v[3];
+        // silu with the hardware's exp2 and reciprocal: a few ulp, far below the fp16 rounding
+        // of the result (and 0.3 us per launch on the critical path)
+        float a0 = __fdividef(v[0], 1.0f + __expf(-v[0])) * v[2];
+        float a1 = __fdividef(v[1], 1.0f + __expf(-v[1])) * v[3];
         half2_ h = {(half_t)a0, (half_t)a1};
         *(half2_*)((half_t*)op.out + xpk_index(m, f, mtp)) = h;
     } else {   // EPI_QKV: packed rows of a head: (j, j+1, j+d/2, j+1+d/2)
